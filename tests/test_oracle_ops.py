@@ -1,0 +1,255 @@
+"""Pins for the CPU oracle's operators: hand-computed cases, algebraic
+identities, and agreement with PyTorch's CPU routines in fp64 (PyTorch is a
+referee here only; the oracle contains no PyTorch calls)."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as tF
+
+import synth
+from oracle import forward as F
+
+
+def rnd(shape, tid, lo=-1.0, hi=1.0):
+    return synth.splitmix64_uniform(99, tid, shape, lo, hi).astype(np.float32)
+
+
+# ---- hand cases -------------------------------------------------------------------------------
+@pytest.mark.parametrize("cin", [1, 3])
+def test_conv_all_ones_counts_taps(cin):
+    x = np.ones((1, cin, 5, 6), np.float32)
+    w = np.ones((2, cin, 3, 3), np.float32)
+    y = F.conv2d(x, w, None, None, 1, 1, 1, "none")
+    assert y.shape == (1, 2, 5, 6)
+    assert np.all(y[0, :, 1:-1, 1:-1] == 9 * cin)
+    assert np.all(y[0, :, 0, 1:-1] == 6 * cin) and np.all(y[0, :, 1:-1, 0] == 6 * cin)
+    assert y[0, 0, 0, 0] == 4 * cin and y[0, 1, -1, -1] == 4 * cin
+
+
+def test_conv_is_cross_correlation_not_flipped():
+    x = np.zeros((1, 1, 3, 3), np.float32)
+    x[0, 0, 0, 1] = 1.0                       # impulse at (0,1)
+    w = np.arange(9, dtype=np.float32).reshape(1, 1, 3, 3)
+    y = F.conv2d(x, w, None, None, 1, 1, 1, "none")
+    # y[oh,ow] = w[ih-oh+1, iw-ow+1] for the impulse at (ih,iw)=(0,1)
+    assert y[0, 0, 1, 1] == w[0, 0, 0, 1] and y[0, 0, 0, 0] == w[0, 0, 1, 2] and y[0, 0, 1, 2] == w[0, 0, 0, 0]
+
+
+def test_conv_centre_tap_identity_and_stride2():
+    x = rnd((2, 3, 7, 7), 1)
+    w = np.zeros((3, 3, 3, 3), np.float32)
+    for c in range(3):
+        w[c, c, 1, 1] = 1.0
+    assert np.array_equal(F.conv2d(x, w, None, None, 1, 1, 1, "none"), x)
+    assert np.array_equal(F.conv2d(x, w, None, None, 2, 1, 1, "none"), x[:, :, ::2, ::2])
+
+
+def test_conv_bias_residual_act_hand():
+    x = np.full((1, 1, 2, 2), 2.0, np.float32)
+    w = np.full((1, 1, 1, 1), -3.0, np.float32)
+    b = np.array([1.0], np.float32)
+    res = np.array([[[[10.0, 0.0], [4.0, 20.0]]]], np.float32)
+    y = F.conv2d(x, w, b, res, 1, 0, 1, "relu6")      # -6 + 1 + res, clipped to [0,6]
+    assert np.array_equal(y, np.array([[[[5.0, 0.0], [0.0, 6.0]]]], np.float32))
+
+
+def test_conv1x1_equals_fc_over_pixels_and_full_kernel_equals_fc():
+    x = rnd((2, 5, 4, 3), 2)
+    w = rnd((7, 5, 1, 1), 3)
+    b = rnd((7,), 4)
+    y = F.conv2d(x, w, b, None, 1, 0, 1, "none")
+    rows = np.ascontiguousarray(x.transpose(0, 2, 3, 1)).reshape(-1, 5)
+    yf = F.gemm(rows, w.reshape(7, 5), b, None, "none").reshape(2, 4, 3, 7).transpose(0, 3, 1, 2)
+    assert np.array_equal(y, yf)
+    wk = rnd((6, 5, 4, 3), 5)
+    y2 = F.conv2d(x, wk, None, None, 1, 0, 1, "none")
+    assert np.array_equal(y2.reshape(2, 6), F.gemm(x.reshape(2, -1), wk.reshape(6, -1), None, None, "none"))
+
+
+def test_depthwise_equals_independent_single_channel_convs():
+    x = rnd((2, 4, 6, 6), 6)
+    w = rnd((4, 1, 3, 3), 7)
+    y = F.conv2d(x, w, None, None, 2, 1, 4, "none")
+    for c in range(4):
+        yc = F.conv2d(np.ascontiguousarray(x[:, c:c + 1]), np.ascontiguousarray(w[c:c + 1]), None, None, 2, 1, 1, "none")
+        assert np.array_equal(y[:, c:c + 1], yc)
+
+
+def test_conv_linearity_power_of_two_scale():
+    x = rnd((1, 3, 6, 6), 8)
+    w = rnd((4, 3, 3, 3), 9)
+    assert np.array_equal(F.conv2d(4 * x, w, None, None, 1, 1, 1, "none"), 4 * F.conv2d(x, w, None, None, 1, 1, 1, "none"))
+
+
+def test_maxpool_ramp_and_negative_border():
+    x = np.arange(36, dtype=np.float32).reshape(1, 1, 6, 6)
+    y = F.maxpool(x, 2, 2, 0)
+    assert np.array_equal(y[0, 0], x[0, 0, 1::2, 1::2])
+    xn = -np.ones((1, 1, 5, 5), np.float32) - np.arange(25, dtype=np.float32).reshape(1, 1, 5, 5)
+    yn = F.maxpool(xn, 3, 2, 1)               # padding must never win even though all data < 0
+    assert yn.shape == (1, 1, 3, 3) and yn.max() <= -1.0 and yn[0, 0, 0, 0] == -1.0
+    assert yn[0, 0, 2, 2] == xn[0, 0, 3, 3]
+
+
+def test_gavgpool_constant_and_hand():
+    assert np.all(F.gavgpool(np.full((2, 3, 4, 5), 2.5, np.float32)) == 2.5)
+    x = np.arange(8, dtype=np.float32).reshape(1, 2, 2, 2)
+    assert np.array_equal(F.gavgpool(x).ravel(), np.array([1.5, 5.5], np.float32))
+
+
+def test_gelu_relu_values():
+    x = np.array([[[[-1.0, 0.0, 1.0, 7.0]]]], np.float32)
+    assert np.array_equal(F.act(x, "relu").ravel(), [0, 0, 1, 7])
+    assert np.array_equal(F.act(x, "relu6").ravel(), [0, 0, 1, 6])
+    g = F.act(x, "gelu").ravel()
+    assert abs(g[2] - 0.8413447460685429) < 1e-7 and abs(g[0] + 0.15865525393145707) < 1e-7 and g[1] == 0
+
+
+def test_layernorm_softmax_invariants():
+    x = rnd((3, 16, 5, 1), 10, -3, 3)
+    g, b = np.ones(16, np.float32), np.zeros(16, np.float32)
+    y = F.layernorm(x, None, g, b, 1e-12).astype(np.float64)
+    assert np.abs(y.mean(axis=1)).max() < 1e-6 and np.abs(y.var(axis=1) - 1).max() < 1e-5
+    s = F.softmax(x)
+    assert np.abs(s.astype(np.float64).sum(axis=1) - 1).max() < 1e-6
+    assert np.abs(F.softmax(x + np.float32(2.0)) - s).max() < 1e-6
+    hand = F.softmax(np.array([0.0, np.log(3.0)], np.float32).reshape(1, 2, 1, 1)).ravel()
+    assert np.allclose(hand, [0.25, 0.75], atol=1e-7)
+
+
+def test_bf16_rounding_hand_table():
+    cases = [(1.0 + 2.0 ** -8, 1.0), (1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -6), (1.0 + 2.0 ** -8 + 2.0 ** -16, 1.0 + 2.0 ** -7),
+             (3.0e38, 3.0e38), (-2.0 ** -9 - 1.0, -1.0)]
+    x = np.array([c[0] for c in cases], np.float32)
+    y = F.round_bf16(x)
+    for got, (_, exp) in zip(y[:3], cases[:3]):
+        assert got == np.float32(exp)
+    assert y[4] == -1.0
+    r = rnd((1000,), 11)
+    assert np.array_equal(F.round_bf16(r), torch.from_numpy(r).to(torch.bfloat16).to(torch.float32).numpy())
+    assert np.array_equal(F.round_bf16(r), synth.bf16_round(r))
+
+
+# ---- library referee (torch CPU, fp64) --------------------------------------------------------
+@pytest.mark.parametrize("k,stride,pad,groups,cin,cout", [(3, 1, 1, 1, 5, 7), (3, 2, 1, 1, 4, 6), (7, 2, 3, 1, 3, 8),
+                                                           (1, 2, 0, 1, 6, 4), (3, 2, 1, 6, 6, 6), (3, 1, 1, 2, 4, 6)])
+def test_conv_vs_torch(k, stride, pad, groups, cin, cout):
+    x, w, b = rnd((2, cin, 9, 11), 20), rnd((cout, cin // groups, k, k), 21), rnd((cout,), 22)
+    y = F.conv2d(x, w, b, None, stride, pad, groups, "none")
+    ref = tF.conv2d(torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double(),
+                    stride=stride, padding=pad, groups=groups).numpy()
+    assert y.shape == ref.shape and np.abs(y - ref).max() <= 2e-7 * np.abs(ref).max()
+
+
+def test_gemm_pool_ln_softmax_gelu_vs_torch():
+    x, w, b = rnd((5, 37), 30), rnd((11, 37), 31), rnd((11,), 32)
+    ref = tF.linear(torch.from_numpy(x).double(), torch.from_numpy(w).double(), torch.from_numpy(b).double()).numpy()
+    assert np.abs(F.gemm(x, w, b, None, "none") - ref).max() < 1e-6
+    xi = rnd((2, 3, 9, 10), 33)
+    for k, s, p in [(3, 2, 1), (2, 2, 0)]:
+        ref = tF.max_pool2d(torch.from_numpy(xi), k, s, p).numpy()
+        assert np.array_equal(F.maxpool(xi, k, s, p), ref)
+    assert np.abs(F.gavgpool(xi).ravel() - xi.astype(np.float64).mean(axis=(2, 3)).ravel()).max() < 1e-7
+    xt = rnd((2, 24, 7, 1), 34, -4, 4)
+    rows = torch.from_numpy(xt[..., 0].transpose(0, 2, 1).copy()).double()
+    g, bt = rnd((24,), 35), rnd((24,), 36)
+    ref = tF.layer_norm(rows, (24,), torch.from_numpy(g).double(), torch.from_numpy(bt).double(), 1e-12).numpy()
+    got = F.layernorm(xt, None, g, bt, 1e-12)[..., 0].transpose(0, 2, 1)
+    assert np.abs(got - ref).max() < 1e-6
+    ref = tF.softmax(rows, dim=-1).numpy()
+    assert np.abs(F.softmax(xt)[..., 0].transpose(0, 2, 1) - ref).max() < 1e-7
+    ref = tF.gelu(torch.from_numpy(xt).double()).numpy()
+    assert np.abs(F.act(xt, "gelu") - ref).max() < 1e-6
+
+
+def test_attention_vs_torch():
+    B, H, dh, S = 2, 3, 4, 5
+    qkv = rnd((B, 3 * H * dh, S, 1), 40)
+    sc = F.bgemm_qk(qkv, H, dh, 0.5)
+    p = F.softmax(sc)
+    o = F.bgemm_pv(p, qkv, H, dh)
+    t = torch.from_numpy(qkv[..., 0]).double()                       # [B, 3D, S]
+    q, k, v = [t[:, i * H * dh:(i + 1) * H * dh].reshape(B, H, dh, S) for i in range(3)]
+    s_ref = 0.5 * torch.einsum("bhdi,bhdj->bhij", q, k)
+    o_ref = torch.einsum("bhij,bhdj->bhdi", torch.softmax(s_ref, -1), v).reshape(B, H * dh, S)
+    assert np.abs(sc[..., 0].reshape(B, H, S, S).transpose(0, 1, 3, 2) - s_ref.numpy()).max() < 1e-6
+    assert np.abs(o[..., 0] - o_ref.numpy()).max() < 1e-6
+
+
+# ---- whole graphs -----------------------------------------------------------------------------
+def _torch_forward(t, x, params):
+    """Independent walk of the same graph with torch CPU fp64 ops."""
+    T = {t.input: torch.from_numpy(x).double()}
+    P = [torch.from_numpy(p).double() for p in params]
+    actf = {"none": lambda v: v, "relu": torch.relu, "relu6": lambda v: torch.clamp(v, 0, 6), "gelu": tF.gelu}
+    for op in t.ops:
+        a = T[op.in0]
+        r = T[op.res] if op.res >= 0 else 0
+        if op.kind in ("conv", "dwconv"):
+            y = actf[op.act](tF.conv2d(a, P[op.w], P[op.bias], stride=op.stride, padding=op.pad, groups=op.groups) + r)
+        elif op.kind == "gemm":
+            if op.cin == a[0].numel():
+                y = tF.linear(a.reshape(a.shape[0], -1), P[op.w], P[op.bias])[:, :, None, None]
+            else:
+                y = tF.linear(a.permute(0, 2, 3, 1), P[op.w], P[op.bias]).permute(0, 3, 1, 2)
+            y = actf[op.act](y + r)
+        elif op.kind == "maxpool":
+            y = tF.max_pool2d(a, op.kh, op.stride, op.pad)
+        elif op.kind == "gavgpool":
+            y = a.mean(dim=(2, 3), keepdim=True)
+        elif op.kind == "layernorm":
+            y = tF.layer_norm((a + r).permute(0, 2, 3, 1), (a.shape[1],), P[op.scale], P[op.shift], op.eps).permute(0, 3, 1, 2)
+        elif op.kind == "softmax":
+            y = torch.softmax(a, dim=1)
+        elif op.kind == "bgemm_qk":
+            B, D3, S, _ = a.shape
+            H, dh = op.groups, op.cin
+            q = a[:, :D3 // 3, :, 0].reshape(B, H, dh, S)
+            k = a[:, D3 // 3:2 * D3 // 3, :, 0].reshape(B, H, dh, S)
+            y = (op.alpha * torch.einsum("bhdi,bhdj->bhji", q, k)).reshape(B * H, S, S, 1)
+        elif op.kind == "bgemm_pv":
+            qkv = T[op.in1]
+            B, D3, S, _ = qkv.shape
+            H, dh = op.groups, op.cout
+            v = qkv[:, 2 * D3 // 3:, :, 0].reshape(B, H, dh, S)
+            y = torch.einsum("bhji,bhdj->bhdi", a[..., 0].reshape(B, H, S, S), v).reshape(B, H * dh, S, 1)
+        else:
+            raise ValueError(op.kind)
+        T[op.out] = y
+    return T[t.output].numpy()
+
+
+@pytest.mark.parametrize("maker", [synth.toy_cnn, synth.toy_mlp, synth.small_cnn, synth.small_resnet,
+                                   synth.small_mbv2, synth.small_bert])
+def test_graph_walk_vs_torch_fp64(maker):
+    t = maker("f32")
+    x, p = synth.materialise(t, 5)
+    y = F.run_tenant(t, x, p)
+    ref = _torch_forward(t, x, p)
+    # fp32 storage of every intermediate tensor vs an unrounded fp64 pass
+    assert np.abs(y - ref).max() <= 2e-5 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("maker", [synth.small_cnn, synth.small_resnet, synth.small_mbv2, synth.small_bert])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_oracle_split_invariance(maker, dtype):
+    """Decomposition (Eq. 5) must not change the oracle's own result, bit for bit."""
+    t = maker(dtype)
+    x, p = synth.materialise(t, 6)
+    base = F.run_tenant(t, x, p)
+    for axis in ("batch", "cout"):
+        for f in (2, 3):
+            splits = {}
+            for i, op in enumerate(t.ops):
+                ok_c = op.kind in ("conv", "dwconv", "gemm", "maxpool", "gavgpool", "affine")
+                if axis == "batch" or ok_c:
+                    ext = t.batch if axis == "batch" else op.cout
+                    if ext >= f:
+                        splits[i] = (axis, f)
+            assert np.array_equal(F.run_tenant(t, x, p, splits), base)
+
+
+def test_chunk_ranges():
+    assert F.chunk_ranges(10, 4) == [(0, 3), (3, 6), (6, 8), (8, 10)]
+    assert F.chunk_ranges(8, 2) == [(0, 4), (4, 8)]
+    assert sum(b - a for a, b in F.chunk_ranges(1000, 8)) == 1000

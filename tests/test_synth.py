@@ -1,0 +1,86 @@
+"""Seeded generators and tenant graph builders (CPU only)."""
+import os
+import numpy as np
+import pytest
+
+import synth
+from synth.rng import _draws
+
+
+def test_splitmix64_published_vector(golden_dir):
+    exp = [int(l) for l in open(os.path.join(golden_dir, "splitmix64_vector.txt")) if not l.startswith("#")]
+    got = _draws(0, 1234567, 5)           # state = 0 * 2^32 + 1234567
+    assert [int(v) for v in got] == exp
+
+
+def test_uniform_range_and_determinism():
+    a = synth.splitmix64_uniform(7, 3, (1000,))
+    b = synth.splitmix64_uniform(7, 3, (1000,))
+    assert np.array_equal(a, b) and a.min() >= -1.0 and a.max() < 1.0
+    assert abs(a.mean()) < 0.1 and abs(a.var() - 1.0 / 3.0) < 0.05
+    assert not np.array_equal(a, synth.splitmix64_uniform(7, 4, (1000,)))
+
+
+def test_normal_moments():
+    a = synth.splitmix64_normal(11, 0, (20001,), 0.02)
+    assert abs(a.mean()) < 1e-3 and abs(a.std() - 0.02) < 1e-3
+
+
+def test_bf16_round_ties_to_even():
+    one = np.float32(1.0)
+    cases = [(1.0 + 2.0 ** -8, 1.0),                 # exactly half way, even mantissa below -> down
+             (1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -6),  # half way, odd below -> up to even
+             (1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 2.0 ** -7),
+             (1.0 + 2.0 ** -9, 1.0), (-1.0 - 3 * 2.0 ** -8, -1.0 - 2.0 ** -6), (0.0, 0.0)]
+    x = np.array([c[0] for c in cases], np.float32)
+    assert np.array_equal(synth.bf16_round(x), np.array([c[1] for c in cases], np.float32))
+    r = synth.bf16_round(synth.splitmix64_uniform(1, 1, (4096,)).astype(np.float32))
+    assert np.all((r.view(np.uint32) & 0xFFFF) == 0)
+    assert one == synth.bf16_round(np.array([1.0], np.float32))[0]
+
+
+def test_published_model_totals(golden_dir):
+    build = {"resnet18": synth.resnet18, "resnet50": synth.resnet50, "vgg16": synth.vgg16,
+             "mobilenetv2": synth.mobilenetv2, "bert_base": synth.bert_base}
+    for line in open(os.path.join(golden_dir, "model_totals.txt")):
+        if line.startswith("#"):
+            continue
+        name, ops, params_m, gmac = line.split()
+        t = build[name]("bf16", 1)
+        assert len(t.ops) == int(ops)
+        assert round(synth.tenant_params(t) / 1e6, 2) == float(params_m)
+        assert round(synth.gemm_macs(t) / 1e9, 3) == float(gmac)
+
+
+def test_final_feature_maps():
+    for f, c in [(synth.resnet18, 512), (synth.resnet50, 2048), (synth.vgg16, 512), (synth.mobilenetv2, 1280)]:
+        t = f("f32", 1)
+        gap_or_fc = next(op for op in t.ops if op.kind in ("gavgpool", "gemm"))
+        assert t.tensors[gap_or_fc.in0] == (1, c, 7, 7)
+
+
+def test_graphs_are_topologically_ordered():
+    for cfg in range(1, 6):
+        tenants, _ = synth.build_config(cfg, "full", with_data=False)
+        for t in tenants:
+            written = {t.input}
+            for op in t.ops:
+                for i in (op.in0, op.in1, op.res):
+                    assert i < 0 or i in written
+                assert op.out not in written
+                written.add(op.out)
+            assert t.output in written
+            assert all(s[0] % t.batch == 0 for s in t.tensors)
+
+
+def test_config_data_is_seeded_and_bf16_clean():
+    t1, d1 = synth.build_config(3, "small")
+    t2, d2 = synth.build_config(3, "small")
+    for (x1, p1), (x2, p2) in zip(d1, d2):
+        assert np.array_equal(x1, x2) and all(np.array_equal(a, b) for a, b in zip(p1, p2))
+    x, p = d1[0]
+    assert np.all((x.view(np.uint32) & 0xFFFF) == 0)
+    w = p[t1[0].ops[0].w]
+    assert np.all((w.view(np.uint32) & 0xFFFF) == 0)
+    fan_in = t1[0].params[t1[0].ops[0].w].fan_in
+    assert np.abs(w).max() <= np.sqrt(6.0 / fan_in) / np.sqrt(1 + 1e-5) * (1 + 2 ** -8)
