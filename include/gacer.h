@@ -1,0 +1,206 @@
+/*
+ * gacer.h -- C ABI of the multi-tenant regulated executor for one AMD MI355X (gfx950).
+ *
+ * Several DNN tenants M_1..M_N, each a flat operator list M_n = [O_n,1 .. O_n,i]
+ * (Section 4.1, "Multi-Tenant Runtime Deployment"), run concurrently on one GPU, one HIP
+ * stream per tenant.  A *regulation plan* says
+ *   - spatially: which operators are decomposed into chunks (the mask list and list_B of
+ *     Section 4.2, Eq. 5) -- here along the batch axis or the output-channel axis; and
+ *   - temporally: which operators must wait for which (the synchronisation pointers /
+ *     Matrix_P of Section 4.3, Eq. 6 and Eq. 7), expressed as event edges between streams.
+ * Every valid plan produces bit-identical tenant outputs; a plan only changes when work runs.
+ *
+ * Conventions
+ *   - All `dptr`, weight, bias, scale and shift pointers are DEVICE pointers owned by the
+ *     caller.  They must stay valid until gacer_destroy / the next gacer_load_tenants.
+ *     The library never allocates, frees or copies tenant memory.  Descriptor structs
+ *     (gacer_tenant, gacer_op, ...) are HOST memory and are deep-copied by the call.
+ *   - Activations are stored channels-last: element (n,c,h,w) of a tensor with logical shape
+ *     (n,c,h,w) lives at index ((n*H + h)*W + w)*C + c.  Token tensors use c = features,
+ *     h = sequence position, w = 1.  Element type is float (GACER_F32) or bfloat16
+ *     (GACER_BF16) for activations and for CONV2D/DWCONV2D/GEMM weights; bias, scale and
+ *     shift vectors are always float.  All device pointers must be 16-byte aligned.
+ *   - Weight layouts: CONV2D [cout][kh][kw][cin/groups];  DWCONV2D [kh][kw][c];
+ *     GEMM [cout][cin] with the cin index running over the input item in storage order.
+ *   - Functions return a gacer_status and never throw or abort; gacer_last_error gives text.
+ *     A failing call leaves the context as it was before the call.
+ *   - A context is not thread-safe; calls on one context must not overlap.
+ */
+#ifndef GACER_H
+#define GACER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gacer_ctx gacer_ctx; /* opaque, owned by the library */
+
+typedef enum {
+    GACER_OK = 0,
+    GACER_EINVAL = 1, /* null pointer, bad enum, misaligned device pointer            */
+    GACER_ESHAPE = 2, /* operator / tensor shapes inconsistent                        */
+    GACER_EPLAN = 3,  /* plan rejected (illegal split, bad or cyclic sync edges, ...) */
+    GACER_ESTATE = 4, /* call order violated (e.g. run before load)                   */
+    GACER_ENOMEM = 5,
+    GACER_EHIP = 6    /* a HIP runtime call failed; text in gacer_last_error          */
+} gacer_status;
+
+typedef enum { GACER_F32 = 0, GACER_BF16 = 1 } gacer_dtype;
+
+typedef enum {
+    GACER_CONV2D = 0,     /* y = act(conv(x,w) + bias + res)        dense or grouped          */
+    GACER_DWCONV2D = 1,   /* depthwise (groups == cin == cout), same epilogue                */
+    GACER_GEMM = 2,       /* y[r,o] = act(sum_k x[r,k] w[o,k] + bias[o] + res[r,o])          */
+    GACER_BGEMM_QK = 3,   /* attention scores, see below                                     */
+    GACER_BGEMM_PV = 4,   /* attention context, see below                                    */
+    GACER_MAXPOOL = 5,    /* window max, padding never wins                                  */
+    GACER_GAVGPOOL = 6,   /* mean over h*w                                                   */
+    GACER_AFFINE_ACT = 7, /* y = act(x*scale[c] + shift[c] + res)   (bias + folded BN + ReLU) */
+    GACER_ADD = 8,        /* y = act(in0 + in1)                                              */
+    GACER_LAYERNORM = 9,  /* over c, of (in0 + res); scale = gamma, shift = beta, alpha = eps */
+    GACER_SOFTMAX = 10,   /* over c                                                          */
+    GACER_ACT = 11        /* y = act(x)                                                      */
+} gacer_opkind;
+
+typedef enum { GACER_ACT_NONE = 0, GACER_ACT_RELU = 1, GACER_ACT_RELU6 = 2, GACER_ACT_GELU = 3 } gacer_act;
+
+/* Decomposition axis of an operator (Eq. 5 decomposes along batch; the output-channel
+ * axis is this library's second axis).  Chunk j of `factor` covers a contiguous sub-range;
+ * the first (extent % factor) chunks are one element longer, sizes sum to the extent. */
+typedef enum { GACER_AXIS_NONE = 0, GACER_AXIS_BATCH = 1, GACER_AXIS_COUT = 2 } gacer_axis;
+
+typedef struct {
+    int64_t n, c, h, w; /* logical shape; n must be a multiple of the tenant's batch */
+    void *dptr;         /* device, caller-owned, 16-byte aligned                     */
+} gacer_tensor;
+
+/*
+ * One operator O_n,i.  in0/in1/res/out index the tenant's tensor table (-1 = absent).
+ *   CONV2D/DWCONV2D: cin,cout,kh,kw,stride,pad,groups as usual; out h = (h+2*pad-kh)/stride+1.
+ *   GEMM: cin = features consumed per output row.  If cin == c(in0) every position (n,h,w)
+ *         is a row (a 1x1 convolution); if cin == c*h*w(in0) every item n is one row and the
+ *         output has h = w = 1.
+ *   BGEMM_QK: in0 = qkv tokens (n=B, c=3*D, h=S, w=1), D = groups*cin (groups = heads,
+ *         cin = head size); out (n=B*groups, c=S, h=S, w=1):
+ *         out[b*heads+hd, key j, query i] = alpha * sum_d q[b,i,hd,d] * k[b,j,hd,d].
+ *   BGEMM_PV: in0 = probabilities (n=B*groups, c=S, h=S, w=1), in1 = qkv tokens, cout = head
+ *         size; out (n=B, c=D, h=S, w=1): out[b,i,hd*cout+d] = sum_j p[b*heads+hd,j,i] * v[b,j,hd,d].
+ *   MAXPOOL: kh (=kw), stride, pad.   LAYERNORM: alpha = epsilon.
+ */
+typedef struct {
+    gacer_opkind kind;
+    int in0, in1, res, out;
+    const void *w;      /* device: weights (dtype of the tenant)           */
+    const float *bias;  /* device: [cout] or NULL                          */
+    const float *scale; /* device: [c]   AFFINE_ACT scale / LAYERNORM gamma */
+    const float *shift; /* device: [c]   AFFINE_ACT shift / LAYERNORM beta  */
+    int cin, cout, kh, kw, stride, pad, groups;
+    gacer_act act;
+    float alpha;
+} gacer_op;
+
+/* One tenant: its operator list in execution order, its tensors, and the stream it runs on. */
+typedef struct {
+    int n_ops;
+    const gacer_op *ops;
+    int n_tensors;
+    const gacer_tensor *tensors;
+    int input, output; /* tensor indices */
+    gacer_dtype dtype;
+    int batch;
+    void *stream; /* hipStream_t created by the caller (default priority); NULL = null stream */
+} gacer_tenant;
+
+/* mask + list_B (Section 4.2): operator (tenant, op) is decomposed `factor` ways on `axis`. */
+typedef struct { int tenant, op; gacer_axis axis; int factor; } gacer_split;
+/* One ordering constraint between streams: (dst_tenant,dst_op) starts only after every chunk
+ * of (src_tenant,src_op) has finished.  Cluster barriers of Matrix_P expand into such edges. */
+typedef struct { int src_tenant, src_op, dst_tenant, dst_op; } gacer_sync;
+typedef struct { int n_split; const gacer_split *split; int n_sync; const gacer_sync *sync; } gacer_plan;
+
+/* One row of the lookup table of Section 4.1: operator (tenant, op) decomposed `factor` ways on
+ * `axis` takes `ms` per chunk in isolation, launches `workgroups` workgroups per chunk and
+ * occupies `cu_share` (0..1] of the compute units (the analogue of SM occupancy W).  The row
+ * with tenant == -1 carries the synchronisation wait T_SW (Eq. 8) in `ms`. */
+typedef struct { int tenant, op; gacer_axis axis; int factor; float ms; int workgroups; float cu_share; } gacer_prof;
+
+typedef enum { GACER_MODE_PLAN = 0, GACER_MODE_SEQUENTIAL = 1, GACER_MODE_STREAM_PARALLEL = 2 } gacer_mode;
+
+/* Creates an empty context bound to the current HIP device.  GACER_ENOMEM / GACER_EHIP. */
+gacer_status gacer_create(gacer_ctx **out);
+/* Waits for the tenant streams, destroys library-owned events.  NULL is allowed. */
+void gacer_destroy(gacer_ctx *ctx);
+
+/*
+ * Problem statement, Section 4.1: registers the N tenant operator lists.  Validates every
+ * operator against its tensors (GACER_ESHAPE names the first offending tenant/op), checks
+ * that operators only read tensors written earlier, deep-copies the descriptors and resets the
+ * plan to "no decomposition, no pointers".  1 <= n <= 64.
+ */
+gacer_status gacer_load_tenants(gacer_ctx *ctx, const gacer_tenant *tenants, int n);
+
+/*
+ * Installs a regulation plan (mask/list_B of Section 4.2 + pointer edges of Section 4.3); NULL
+ * means unsplit and unsynchronised.  Rejected with GACER_EPLAN and no change when: factor not
+ * in {1,2,4,8}; factor larger than the axis extent; axis not legal for the kind (COUT is legal
+ * for CONV2D, DWCONV2D, GEMM, MAXPOOL, GAVGPOOL, AFFINE_ACT only; BATCH for all); duplicate
+ * entry for one operator; an edge names a missing operator or stays inside one tenant; the
+ * union of stream order and sync edges has a cycle.  The plan is copied.
+ */
+gacer_status gacer_set_plan(gacer_ctx *ctx, const gacer_plan *plan);
+
+/*
+ * Matrix_P -> sync edges (Eq. 6 / Eq. 7).  P holds n_tenants rows of n_ptr sorted pointer
+ * values; value p cuts after the p-th operator (1-based; 0 and n_ops give empty segments).
+ * Same-index segments form a cluster; the edges make the first operator of every tenant's
+ * segment k+1 wait for the last operator of every other tenant's segments <= k.  The split
+ * part of the returned plan is empty.  Free with gacer_plan_free.  GACER_EPLAN if a row is
+ * unsorted or out of range.
+ */
+gacer_status gacer_plan_from_pointers(gacer_ctx *ctx, const int *P, int n_ptr, gacer_plan **out);
+
+/*
+ * Runs `rounds` rounds; in each round every tenant executes once.  Mode PLAN issues the
+ * decomposed operators on the tenants' streams, ordered by the plan's edges (hipEvent
+ * record / wait; the host never blocks inside a round).  SEQUENTIAL issues all tenants one
+ * after another, unsplit, on tenant 0's stream.  STREAM_PARALLEL uses one stream per tenant,
+ * unsplit, no edges.  Rounds are separated by a fork/join over all streams.  ms_per_round
+ * (host, `rounds` floats, may be NULL) receives each round's makespan measured with
+ * hipEvents.  Returns after all work of all rounds has finished.
+ */
+gacer_status gacer_run(gacer_ctx *ctx, int mode, int rounds, float *ms_per_round);
+
+/*
+ * Builds the lookup table of Section 4.1 by timing, in isolation on the tenant's stream, every
+ * operator unsplit and for every legal (axis, factor in {2,4,8}); plus the T_SW row.  Tenant
+ * inputs must hold finite data (the call runs each tenant once first).  Writes up to `cap`
+ * rows to `out` (host) and the total number of rows to *n; call with cap = 0 to size.
+ */
+gacer_status gacer_profile(gacer_ctx *ctx, gacer_prof *out, size_t cap, size_t *n);
+
+/*
+ * Granularity-aware search (Section 4.4, Algorithm 1, alternated with the spatial step of
+ * Section 4.2) on the CPU, over the lookup table `prof`: returns the plan (splits + pointer
+ * edges) with the smallest modelled residue R (Eq. 8).  `pointers_out`, if not NULL, receives
+ * n_tenants * (*n_ptr_out) pointer values (capacity 8 per tenant).  No GPU work is done.
+ */
+gacer_status gacer_search(gacer_ctx *ctx, const gacer_prof *prof, size_t n, int max_rounds,
+                          gacer_plan **out, int *pointers_out, int *n_ptr_out, double *residue_out);
+
+/* Modelled residue R (Eq. 8) of an explicit (splits, Matrix_P) on the table; CPU only. */
+gacer_status gacer_model_residue(gacer_ctx *ctx, const gacer_prof *prof, size_t n, const gacer_split *split,
+                                 int n_split, const int *P, int n_ptr, double *residue_out, double *makespan_out);
+
+void gacer_plan_free(gacer_plan *plan);
+/* Text of the last error on this context ("" if none); valid until the next call. */
+const char *gacer_last_error(const gacer_ctx *ctx);
+/* Number of kernel launches one round issues in the given mode under the current plan. */
+gacer_status gacer_launch_count(gacer_ctx *ctx, int mode, int *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GACER_H */

@@ -1,0 +1,64 @@
+// Library-internal state behind the opaque gacer_ctx.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <string>
+#include <vector>
+#include "../../include/gacer.h"
+#include "kernels.h"
+
+namespace gacer {
+
+enum LaunchKind { LK_IGEMM, LK_DWCONV, LK_MAXPOOL, LK_GAVGPOOL, LK_ELTWISE, LK_LAYERNORM, LK_SOFTMAX };
+
+struct Launch {
+    LaunchKind kind;
+    GemmArgs g;
+    StreamArgs s;
+};
+
+struct Tenant {
+    std::vector<gacer_op> ops;
+    std::vector<gacer_tensor> tensors;
+    int input = 0, output = 0, batch = 1;
+    gacer_dtype dtype = GACER_F32;
+    hipStream_t stream = nullptr;
+};
+
+// One operator after plan expansion: its chunk launches plus the events it waits on / records.
+struct OpExec {
+    std::vector<Launch> chunks;
+    std::vector<int> waits;     // indices into Ctx::sync_events
+    int record = -1;            // event recorded after the last chunk, -1 = none
+};
+
+struct Ctx {
+    int device = 0;
+    int n_cu = 256;
+    std::vector<Tenant> tenants;
+    bool loaded = false;
+    // current plan (copied)
+    std::vector<gacer_split> splits;
+    std::vector<gacer_sync> syncs;
+    // expansion: [tenant][op]
+    std::vector<std::vector<OpExec>> plan_exec;     // decomposed + edges
+    std::vector<std::vector<OpExec>> plain_exec;    // unsplit, no edges
+    std::vector<std::pair<int, int>> plan_order;    // host issue order (tenant, op), topological
+    std::vector<std::pair<int, int>> par_order;     // stream-parallel issue order
+    std::vector<hipEvent_t> sync_events;
+    size_t n_sync_events = 0;                       // events the current plan needs
+    std::vector<hipEvent_t> join_events;            // one per tenant
+    std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
+    std::string err;
+};
+
+// axis extent and legality of a decomposition
+int axis_extent(const Tenant &t, int op, gacer_axis axis);
+bool axis_legal(gacer_opkind kind, gacer_axis axis);
+void chunk_range(int extent, int factor, int j, int *lo, int *hi);
+// builds the launch of operator `op` restricted to batch items [b_lo,b_hi) and channels [c_lo,c_hi)
+Launch make_launch(const Tenant &t, int op, int b_lo, int b_hi, int c_lo, int c_hi);
+LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry);
+
+}  // namespace gacer
+
+struct gacer_ctx : gacer::Ctx {};

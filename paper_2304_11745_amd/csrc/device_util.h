@@ -1,0 +1,72 @@
+// Small device helpers shared by the streaming kernels (element conversion, activations).
+#pragma once
+#include <hip/hip_runtime.h>
+#include "kernels.h"
+
+namespace gacer {
+
+__device__ __forceinline__ float ld_f32(const float *p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float ld_f32(const unsigned short *p, int64_t i) { return __uint_as_float(((unsigned)p[i]) << 16); }
+
+__device__ __forceinline__ unsigned short to_bf16(float f)
+{
+    unsigned u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (unsigned short)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ void st_f32(float *p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st_f32(unsigned short *p, int64_t i, float v) { p[i] = to_bf16(v); }
+
+__device__ __forceinline__ float activate(float v, int act)
+{
+    if (act == ACT_RELU) return v > 0.f ? v : 0.f;
+    if (act == ACT_RELU6) return v < 0.f ? 0.f : (v > 6.f ? 6.f : v);
+    if (act == ACT_GELU) return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
+    return v;
+}
+
+// 16-byte vector of V elements of type T, unpacked to / packed from float.
+template <typename T, int V> struct Vec;
+template <> struct Vec<float, 4> {
+    float4 raw;
+    __device__ __forceinline__ float get(int i) const { return i == 0 ? raw.x : i == 1 ? raw.y : i == 2 ? raw.z : raw.w; }
+    __device__ __forceinline__ void set(int i, float v) { if (i == 0) raw.x = v; else if (i == 1) raw.y = v; else if (i == 2) raw.z = v; else raw.w = v; }
+};
+template <> struct Vec<unsigned short, 8> {
+    uint4 raw;
+    __device__ __forceinline__ float get(int i) const
+    {
+        const unsigned wd = (i >> 1) == 0 ? raw.x : (i >> 1) == 1 ? raw.y : (i >> 1) == 2 ? raw.z : raw.w;
+        return __uint_as_float((i & 1) ? (wd & 0xFFFF0000u) : (wd << 16));
+    }
+    __device__ __forceinline__ void set(int i, float v)
+    {
+        const unsigned b = to_bf16(v);
+        unsigned &wd = (i >> 1) == 0 ? raw.x : (i >> 1) == 1 ? raw.y : (i >> 1) == 2 ? raw.z : raw.w;
+        wd = (i & 1) ? ((wd & 0x0000FFFFu) | (b << 16)) : ((wd & 0xFFFF0000u) | b);
+    }
+};
+template <> struct Vec<float, 1> {
+    float raw;
+    __device__ __forceinline__ float get(int) const { return raw; }
+    __device__ __forceinline__ void set(int, float v) { raw = v; }
+};
+template <> struct Vec<unsigned short, 1> {
+    unsigned short raw;
+    __device__ __forceinline__ float get(int) const { return __uint_as_float(((unsigned)raw) << 16); }
+    __device__ __forceinline__ void set(int, float v) { raw = to_bf16(v); }
+};
+
+template <typename T, int V> __device__ __forceinline__ Vec<T, V> ld_vec(const T *p, int64_t i)
+{
+    Vec<T, V> v;
+    v.raw = *(const decltype(v.raw) *)(p + i);
+    return v;
+}
+template <typename T, int V> __device__ __forceinline__ void st_vec(T *p, int64_t i, const Vec<T, V> &v)
+{
+    *(decltype(v.raw) *)(p + i) = v.raw;
+}
+
+}  // namespace gacer

@@ -1,0 +1,678 @@
+// Tenant registration, plan validation / expansion, the multi-stream issue loop and the
+// per-operator profiler.  Host code only; kernels are reached through kernels.h.
+//
+// Temporal regulation (Section 4.3) is realised with hipEvents: a synchronisation pointer becomes
+// "record on the producer stream, wait on the consumer streams".  The host never blocks inside a
+// round, so the GPU does not idle while the CPU synchronises (the overhead analysed around Eq. 8
+// shrinks to the device-side wait).
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <new>
+#include <set>
+#include "ctx.h"
+
+using namespace gacer;
+
+#define HIPCHK(ctx, call)                                                                                   \
+    do {                                                                                                    \
+        hipError_t e_ = (call);                                                                             \
+        if (e_ != hipSuccess) return fail(ctx, GACER_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));  \
+    } while (0)
+
+static gacer_status fail(Ctx *c, gacer_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (c) c->err = buf;
+    return st;
+}
+
+namespace gacer {
+
+bool axis_legal(gacer_opkind kind, gacer_axis axis)
+{
+    if (axis == GACER_AXIS_BATCH) return true;
+    if (axis == GACER_AXIS_COUT)
+        return kind == GACER_CONV2D || kind == GACER_DWCONV2D || kind == GACER_GEMM || kind == GACER_MAXPOOL ||
+               kind == GACER_GAVGPOOL || kind == GACER_AFFINE_ACT;
+    return false;
+}
+
+int axis_extent(const Tenant &t, int op, gacer_axis axis)
+{
+    if (axis == GACER_AXIS_BATCH) return t.batch;
+    if (axis == GACER_AXIS_COUT) return (int)t.tensors[t.ops[op].out].c;
+    return 1;
+}
+
+void chunk_range(int extent, int factor, int j, int *lo, int *hi)
+{
+    const int base = extent / factor, rem = extent % factor;
+    *lo = j * base + std::min(j, rem);
+    *hi = *lo + base + (j < rem ? 1 : 0);
+}
+
+static int dt(const Tenant &t) { return t.dtype == GACER_BF16 ? DT_BF16 : DT_F32; }
+
+Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_hi)
+{
+    const gacer_op &op = t.ops[oi];
+    const gacer_tensor &in = t.tensors[op.in0];
+    const gacer_tensor &out = t.tensors[op.out];
+    Launch l;
+    std::memset(&l, 0, sizeof l);
+    const int q_out = (int)(out.n / t.batch), q_in = (int)(in.n / t.batch);
+    GemmArgs &g = l.g;
+    StreamArgs &s = l.s;
+    g.dtype = s.dtype = dt(t);
+    g.alpha = 1.f;
+    g.zb = g.zh = 1;
+    g.act = s.act = (int)op.act;
+    switch (op.kind) {
+    case GACER_CONV2D:
+    case GACER_GEMM: {
+        l.kind = LK_IGEMM;
+        g.x = in.dptr; g.w = op.w; g.bias = op.bias; g.y = out.dptr;
+        g.res = op.res >= 0 ? t.tensors[op.res].dptr : nullptr;
+        const bool flat = (op.kind == GACER_GEMM) && (op.cin != in.c || in.h * in.w == 1);
+        if (flat) {
+            g.H = g.W = 1; g.Cin = op.cin; g.Ho = g.Wo = 1;
+            g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
+            g.x_pix = op.cin; g.x_img = op.cin;
+        } else {
+            g.H = (int)in.h; g.W = (int)in.w; g.Cin = (int)in.c; g.Ho = (int)out.h; g.Wo = (int)out.w;
+            g.kh = op.kind == GACER_GEMM ? 1 : op.kh; g.kw = op.kind == GACER_GEMM ? 1 : op.kw;
+            g.stride = op.kind == GACER_GEMM ? 1 : op.stride; g.pad = op.kind == GACER_GEMM ? 0 : op.pad;
+            g.x_pix = in.c; g.x_img = in.h * in.w * in.c;
+        }
+        g.K = g.kh * g.kw * g.Cin;
+        g.w_row = g.K;
+        g.y_row = out.c;
+        g.m_lo = b_lo * q_out * g.Ho * g.Wo; g.m_hi = b_hi * q_out * g.Ho * g.Wo;
+        g.n_lo = c_lo; g.n_hi = c_hi;
+        break;
+    }
+    case GACER_BGEMM_QK: {
+        // scores[b*heads+hd][query i][key j] = alpha * sum_d q[b,i,hd,d] * k[b,j,hd,d]
+        l.kind = LK_IGEMM;
+        const int heads = op.groups, dh = op.cin, S = (int)in.h;
+        const int64_t D = (int64_t)heads * dh;
+        const size_t esz = t.dtype == GACER_BF16 ? 2 : 4;
+        g.x = in.dptr; g.w = (const char *)in.dptr + D * esz; g.y = out.dptr;
+        g.H = S; g.W = 1; g.Cin = dh; g.Ho = S; g.Wo = 1; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
+        g.K = dh; g.x_pix = 3 * D; g.x_img = 0; g.w_row = 3 * D; g.y_row = S;
+        g.m_lo = 0; g.m_hi = S; g.n_lo = 0; g.n_hi = S;
+        g.alpha = op.alpha; g.act = ACT_NONE;
+        g.zh = heads; g.zb = (b_hi - b_lo) * q_in; g.z_lo = b_lo * q_in;
+        g.x_zb = S * 3 * D; g.x_zh = dh; g.w_zb = S * 3 * D; g.w_zh = dh;
+        g.y_zb = (int64_t)heads * S * S; g.y_zh = (int64_t)S * S;
+        break;
+    }
+    case GACER_BGEMM_PV: {
+        // ctx[b][i][hd*dh+d] = sum_j p[b*heads+hd][i][j] * v[b,j,hd,d]
+        l.kind = LK_IGEMM;
+        const gacer_tensor &qkv = t.tensors[op.in1];
+        const int heads = op.groups, dh = op.cout, S = (int)qkv.h;
+        const int64_t D = (int64_t)heads * dh;
+        const size_t esz = t.dtype == GACER_BF16 ? 2 : 4;
+        g.x = in.dptr; g.w = (const char *)qkv.dptr + 2 * D * esz; g.y = out.dptr;
+        g.H = S; g.W = 1; g.Cin = S; g.Ho = S; g.Wo = 1; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
+        g.K = S; g.x_pix = S; g.x_img = 0; g.w_row = 3 * D; g.y_row = D;
+        g.m_lo = 0; g.m_hi = S; g.n_lo = 0; g.n_hi = dh;
+        g.act = ACT_NONE; g.b_trans = 1;
+        const int qb = (int)(qkv.n / t.batch);
+        g.zh = heads; g.zb = (b_hi - b_lo) * qb; g.z_lo = b_lo * qb;
+        g.x_zb = (int64_t)heads * S * S; g.x_zh = (int64_t)S * S; g.w_zb = S * 3 * D; g.w_zh = dh;
+        g.y_zb = S * D; g.y_zh = dh;
+        break;
+    }
+    default: {
+        s.x = in.dptr; s.y = out.dptr;
+        s.x2 = op.in1 >= 0 ? t.tensors[op.in1].dptr : nullptr;
+        s.res = op.res >= 0 ? t.tensors[op.res].dptr : nullptr;
+        s.w = op.w; s.bias = op.bias; s.scale = op.scale; s.shift = op.shift;
+        s.N = (int)in.n; s.H = (int)in.h; s.W = (int)in.w; s.C = (int)in.c; s.Ho = (int)out.h; s.Wo = (int)out.w;
+        s.k = op.kh; s.stride = op.stride; s.pad = op.pad;
+        s.eps = op.alpha;
+        s.n_lo = b_lo * q_out; s.n_hi = b_hi * q_out; s.c_lo = c_lo; s.c_hi = c_hi;
+        s.rows_per_item = (int64_t)q_out * out.h * out.w;
+        switch (op.kind) {
+        case GACER_DWCONV2D: l.kind = LK_DWCONV; break;
+        case GACER_MAXPOOL: l.kind = LK_MAXPOOL; break;
+        case GACER_GAVGPOOL: l.kind = LK_GAVGPOOL; break;
+        case GACER_LAYERNORM: l.kind = LK_LAYERNORM; s.n_lo = b_lo; s.n_hi = b_hi; break;
+        case GACER_SOFTMAX: l.kind = LK_SOFTMAX; s.n_lo = b_lo; s.n_hi = b_hi; break;
+        default: l.kind = LK_ELTWISE; break;
+        }
+        if (op.kind == GACER_ADD || op.kind == GACER_ACT) { s.scale = s.shift = nullptr; }
+        if (op.kind == GACER_ACT) s.x2 = nullptr;
+    }
+    }
+    return l;
+}
+
+LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry)
+{
+    switch (l.kind) {
+    case LK_IGEMM: return launch_igemm(l.g, s, dry);
+    case LK_DWCONV: return launch_dwconv(l.s, s, dry);
+    case LK_MAXPOOL: return launch_maxpool(l.s, s, dry);
+    case LK_GAVGPOOL: return launch_gavgpool(l.s, s, dry);
+    case LK_LAYERNORM: return launch_layernorm(l.s, s, dry);
+    case LK_SOFTMAX: return launch_softmax(l.s, s, dry);
+    default: return launch_eltwise(l.s, s, dry);
+    }
+}
+
+}  // namespace gacer
+
+// ------------------------------------------------------------------------------------------------
+static bool same_shape(const gacer_tensor &a, const gacer_tensor &b) { return a.n == b.n && a.c == b.c && a.h == b.h && a.w == b.w; }
+
+static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, const std::vector<char> &written)
+{
+    const gacer_op &op = t.ops[oi];
+    auto bad = [&](const char *why) { return fail(c, GACER_ESHAPE, "tenant %d op %d: %s", ti, oi, why); };
+    auto idx_ok = [&](int i, bool required) {
+        if (i < 0) return !required;
+        return i < t.n_tensors && written[i] != 0;
+    };
+    if ((int)op.kind < 0 || (int)op.kind > (int)GACER_ACT) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown kind", ti, oi);
+    if ((int)op.act < 0 || (int)op.act > (int)GACER_ACT_GELU) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown activation", ti, oi);
+    if (!idx_ok(op.in0, true)) return bad("in0 missing or not written by an earlier operator");
+    if (!idx_ok(op.in1, false) || !idx_ok(op.res, false)) return bad("in1/res not written by an earlier operator");
+    if (op.out < 0 || op.out >= t.n_tensors) return bad("out index out of range");
+    if (written[op.out]) return bad("out tensor is written twice");
+    const gacer_tensor &in = t.tensors[op.in0], &out = t.tensors[op.out];
+    if (op.res >= 0 && !same_shape(t.tensors[op.res], out)) return bad("res shape differs from out");
+    const int B = t.batch;
+    switch (op.kind) {
+    case GACER_CONV2D:
+    case GACER_DWCONV2D: {
+        if (!op.w) return fail(c, GACER_EINVAL, "tenant %d op %d: null weights", ti, oi);
+        if (op.kh < 1 || op.kw < 1 || op.stride < 1 || op.pad < 0) return bad("bad kernel/stride/pad");
+        if (op.cin != in.c || op.cout != out.c || in.n != out.n) return bad("cin/cout/n do not match the tensors");
+        if (out.h != (in.h + 2 * op.pad - op.kh) / op.stride + 1 || out.w != (in.w + 2 * op.pad - op.kw) / op.stride + 1)
+            return bad("output extent does not match (h+2*pad-k)/stride+1");
+        if (op.kind == GACER_DWCONV2D) {
+            if (op.groups != op.cin || op.cin != op.cout || op.kh != op.kw) return bad("depthwise needs groups == cin == cout, square kernel");
+        } else if (op.groups != 1) return bad("grouped convolution other than depthwise is not supported");
+        break;
+    }
+    case GACER_GEMM: {
+        if (!op.w) return fail(c, GACER_EINVAL, "tenant %d op %d: null weights", ti, oi);
+        if (op.cout != out.c || in.n != out.n) return bad("cout/n do not match the tensors");
+        if (op.cin == in.c) { if (out.h != in.h || out.w != in.w) return bad("per-position GEMM must keep h,w"); }
+        else if (op.cin == in.c * in.h * in.w) { if (out.h != 1 || out.w != 1) return bad("flattening GEMM must produce h = w = 1"); }
+        else return bad("cin is neither c nor c*h*w of in0");
+        break;
+    }
+    case GACER_BGEMM_QK: {
+        const int64_t D = (int64_t)op.groups * op.cin;
+        if (op.groups < 1 || op.cin < 1 || in.c != 3 * D || in.w != 1) return bad("in0 must be (B, 3*heads*dh, S, 1)");
+        if (out.n != in.n * op.groups || out.c != in.h || out.h != in.h || out.w != 1) return bad("out must be (B*heads, S, S, 1)");
+        break;
+    }
+    case GACER_BGEMM_PV: {
+        if (!idx_ok(op.in1, true)) return bad("in1 (qkv) missing");
+        const gacer_tensor &qkv = t.tensors[op.in1];
+        const int64_t D = (int64_t)op.groups * op.cout;
+        if (op.groups < 1 || op.cout < 1 || qkv.c != 3 * D || qkv.w != 1) return bad("in1 must be (B, 3*heads*dh, S, 1)");
+        if (in.n != qkv.n * op.groups || in.c != qkv.h || in.h != qkv.h || in.w != 1) return bad("in0 must be (B*heads, S, S, 1)");
+        if (out.n != qkv.n || out.c != D || out.h != qkv.h || out.w != 1) return bad("out must be (B, heads*dh, S, 1)");
+        if (qkv.h % 8 || op.cout % 8) return bad("attention context needs S and head size to be multiples of 8");
+        break;
+    }
+    case GACER_MAXPOOL:
+        if (op.kh < 1 || op.stride < 1 || op.pad < 0 || 2 * op.pad > op.kh) return bad("bad window");
+        if (in.n != out.n || in.c != out.c || out.h != (in.h + 2 * op.pad - op.kh) / op.stride + 1 ||
+            out.w != (in.w + 2 * op.pad - op.kh) / op.stride + 1) return bad("output extent mismatch");
+        break;
+    case GACER_GAVGPOOL:
+        if (in.n != out.n || in.c != out.c || out.h != 1 || out.w != 1) return bad("out must be (n,c,1,1)");
+        break;
+    case GACER_AFFINE_ACT:
+        if (!op.scale || !op.shift) return fail(c, GACER_EINVAL, "tenant %d op %d: null scale/shift", ti, oi);
+        if (!same_shape(in, out)) return bad("in/out shapes differ");
+        break;
+    case GACER_ADD:
+        if (!idx_ok(op.in1, true) || !same_shape(in, out) || !same_shape(t.tensors[op.in1], out)) return bad("add needs two inputs of the output shape");
+        break;
+    case GACER_LAYERNORM:
+        if (!op.scale || !op.shift) return fail(c, GACER_EINVAL, "tenant %d op %d: null gamma/beta", ti, oi);
+        if (!same_shape(in, out)) return bad("in/out shapes differ");
+        break;
+    case GACER_SOFTMAX:
+    case GACER_ACT:
+        if (!same_shape(in, out)) return bad("in/out shapes differ");
+        break;
+    }
+    if (in.n % B || out.n % B) return bad("tensor n is not a multiple of the tenant batch");
+    return GACER_OK;
+}
+
+static void expand_plain(Ctx *c)
+{
+    c->plain_exec.assign(c->tenants.size(), {});
+    c->par_order.clear();
+    size_t longest = 0;
+    for (size_t t = 0; t < c->tenants.size(); ++t) {
+        const Tenant &T = c->tenants[t];
+        c->plain_exec[t].resize(T.ops.size());
+        for (size_t i = 0; i < T.ops.size(); ++i)
+            c->plain_exec[t][i].chunks.push_back(make_launch(T, (int)i, 0, T.batch, 0, (int)T.tensors[T.ops[i].out].c));
+        longest = std::max(longest, T.ops.size());
+    }
+    for (size_t i = 0; i < longest; ++i)
+        for (size_t t = 0; t < c->tenants.size(); ++t)
+            if (i < c->tenants[t].ops.size()) c->par_order.push_back({(int)t, (int)i});
+}
+
+// Validates and expands (splits, syncs) into c->plan_exec / plan_order.  On failure nothing changes.
+static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits, const std::vector<gacer_sync> &syncs)
+{
+    const int NT = (int)c->tenants.size();
+    std::map<std::pair<int, int>, gacer_split> smap;
+    for (const gacer_split &s : splits) {
+        if (s.tenant < 0 || s.tenant >= NT || s.op < 0 || s.op >= (int)c->tenants[s.tenant].ops.size())
+            return fail(c, GACER_EPLAN, "split names a missing operator (tenant %d op %d)", s.tenant, s.op);
+        if (s.factor != 1 && s.factor != 2 && s.factor != 4 && s.factor != 8)
+            return fail(c, GACER_EPLAN, "tenant %d op %d: factor %d not in {1,2,4,8}", s.tenant, s.op, s.factor);
+        if (smap.count({s.tenant, s.op})) return fail(c, GACER_EPLAN, "tenant %d op %d: split listed twice", s.tenant, s.op);
+        if (s.factor > 1) {
+            const Tenant &T = c->tenants[s.tenant];
+            if (s.axis != GACER_AXIS_BATCH && s.axis != GACER_AXIS_COUT)
+                return fail(c, GACER_EPLAN, "tenant %d op %d: factor > 1 needs an axis", s.tenant, s.op);
+            if (!axis_legal(T.ops[s.op].kind, s.axis))
+                return fail(c, GACER_EPLAN, "tenant %d op %d: this operator kind cannot be split on that axis", s.tenant, s.op);
+            if (s.factor > axis_extent(T, s.op, s.axis))
+                return fail(c, GACER_EPLAN, "tenant %d op %d: factor %d exceeds the axis extent %d", s.tenant, s.op, s.factor,
+                            axis_extent(T, s.op, s.axis));
+        }
+        smap[{s.tenant, s.op}] = s;
+    }
+    for (const gacer_sync &e : syncs) {
+        if (e.src_tenant < 0 || e.src_tenant >= NT || e.dst_tenant < 0 || e.dst_tenant >= NT ||
+            e.src_op < 0 || e.src_op >= (int)c->tenants[e.src_tenant].ops.size() ||
+            e.dst_op < 0 || e.dst_op >= (int)c->tenants[e.dst_tenant].ops.size())
+            return fail(c, GACER_EPLAN, "sync edge names a missing operator");
+        if (e.src_tenant == e.dst_tenant) return fail(c, GACER_EPLAN, "sync edge inside one tenant (stream order already holds)");
+    }
+    // topological issue order over (stream order U sync edges); round-robin over tenants so that
+    // every stream receives work early.  No progress in a sweep means a cycle.
+    std::vector<std::vector<std::vector<std::pair<int, int>>>> deps(NT);
+    for (int t = 0; t < NT; ++t) deps[t].resize(c->tenants[t].ops.size());
+    for (const gacer_sync &e : syncs) deps[e.dst_tenant][e.dst_op].push_back({e.src_tenant, e.src_op});
+    std::vector<int> pos(NT, 0);
+    std::vector<std::pair<int, int>> order;
+    size_t total = 0;
+    for (int t = 0; t < NT; ++t) total += c->tenants[t].ops.size();
+    while (order.size() < total) {
+        bool progress = false;
+        for (int t = 0; t < NT; ++t) {
+            if (pos[t] >= (int)c->tenants[t].ops.size()) continue;
+            bool ready = true;
+            for (auto &d : deps[t][pos[t]]) ready = ready && (pos[d.first] > d.second);
+            if (!ready) continue;
+            order.push_back({t, pos[t]});
+            ++pos[t];
+            progress = true;
+        }
+        if (!progress) return fail(c, GACER_EPLAN, "sync edges form a cycle with the stream order (would deadlock)");
+    }
+    // events: one per distinct source operator
+    std::map<std::pair<int, int>, int> ev_of;
+    for (const gacer_sync &e : syncs)
+        if (!ev_of.count({e.src_tenant, e.src_op})) { const int id = (int)ev_of.size(); ev_of[{e.src_tenant, e.src_op}] = id; }
+    std::vector<std::vector<OpExec>> ex(NT);
+    for (int t = 0; t < NT; ++t) {
+        const Tenant &T = c->tenants[t];
+        ex[t].resize(T.ops.size());
+        for (int i = 0; i < (int)T.ops.size(); ++i) {
+            const int cout = (int)T.tensors[T.ops[i].out].c;
+            auto it = smap.find({t, i});
+            const int f = (it == smap.end()) ? 1 : it->second.factor;
+            const gacer_axis ax = (it == smap.end() || f == 1) ? GACER_AXIS_NONE : it->second.axis;
+            for (int j = 0; j < f; ++j) {
+                int lo, hi;
+                if (ax == GACER_AXIS_BATCH) {
+                    chunk_range(T.batch, f, j, &lo, &hi);
+                    ex[t][i].chunks.push_back(make_launch(T, i, lo, hi, 0, cout));
+                } else if (ax == GACER_AXIS_COUT) {
+                    chunk_range(cout, f, j, &lo, &hi);
+                    ex[t][i].chunks.push_back(make_launch(T, i, 0, T.batch, lo, hi));
+                } else {
+                    ex[t][i].chunks.push_back(make_launch(T, i, 0, T.batch, 0, cout));
+                }
+            }
+        }
+    }
+    for (const gacer_sync &e : syncs) {
+        const int id = ev_of[{e.src_tenant, e.src_op}];
+        ex[e.src_tenant][e.src_op].record = id;
+        auto &w = ex[e.dst_tenant][e.dst_op].waits;
+        if (std::find(w.begin(), w.end(), id) == w.end()) w.push_back(id);
+    }
+    c->splits = splits;
+    c->syncs = syncs;
+    c->plan_exec.swap(ex);
+    c->plan_order.swap(order);
+    c->n_sync_events = ev_of.size();     // the events themselves are created by the first run that needs them
+    return GACER_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+gacer_status gacer_create(gacer_ctx **out)
+{
+    if (!out) return GACER_EINVAL;
+    gacer_ctx *c = new (std::nothrow) gacer_ctx();
+    if (!c) return GACER_ENOMEM;
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        c->device = dev;
+        int cu = 0;
+        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cu > 0) c->n_cu = cu;
+    } else {
+        (void)hipGetLastError();   // no device: descriptor-only use (validation, search) still works
+    }
+    *out = c;
+    return GACER_OK;
+}
+
+void gacer_destroy(gacer_ctx *c)
+{
+    if (!c) return;
+    for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    for (hipEvent_t e : c->sync_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->join_events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->t_start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->t_end) (void)hipEventDestroy(e);
+    delete c;
+}
+
+const char *gacer_last_error(const gacer_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n)
+{
+    if (!c) return GACER_EINVAL;
+    if (!tenants || n < 1 || n > 64) return fail(c, GACER_EINVAL, "need 1..64 tenants");
+    std::vector<Tenant> fresh(n);
+    for (int ti = 0; ti < n; ++ti) {
+        const gacer_tenant &t = tenants[ti];
+        if (!t.ops || !t.tensors || t.n_ops < 1 || t.n_tensors < 1) return fail(c, GACER_EINVAL, "tenant %d: empty operator or tensor list", ti);
+        if (t.dtype != GACER_F32 && t.dtype != GACER_BF16) return fail(c, GACER_EINVAL, "tenant %d: unknown dtype", ti);
+        if (t.batch < 1) return fail(c, GACER_EINVAL, "tenant %d: batch < 1", ti);
+        if (t.input < 0 || t.input >= t.n_tensors || t.output < 0 || t.output >= t.n_tensors)
+            return fail(c, GACER_EINVAL, "tenant %d: input/output index out of range", ti);
+        for (int i = 0; i < t.n_tensors; ++i) {
+            const gacer_tensor &x = t.tensors[i];
+            if (x.n < 1 || x.c < 1 || x.h < 1 || x.w < 1) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: non-positive extent", ti, i);
+            if (!x.dptr) return fail(c, GACER_EINVAL, "tenant %d tensor %d: null device pointer", ti, i);
+            if (((uintptr_t)x.dptr) % 16) return fail(c, GACER_EINVAL, "tenant %d tensor %d: device pointer not 16-byte aligned", ti, i);
+            if (x.n * x.c * x.h * x.w >= ((int64_t)1 << 31)) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: more than 2^31 elements", ti, i);
+        }
+        std::vector<char> written(t.n_tensors, 0);
+        written[t.input] = 1;
+        for (int oi = 0; oi < t.n_ops; ++oi) {
+            gacer_status st = check_op(c, ti, t, oi, written);
+            if (st != GACER_OK) return st;
+            const gacer_op &op = t.ops[oi];
+            for (const void *p : {(const void *)op.w, (const void *)op.bias, (const void *)op.scale, (const void *)op.shift})
+                if (((uintptr_t)p) % 16) return fail(c, GACER_EINVAL, "tenant %d op %d: parameter pointer not 16-byte aligned", ti, oi);
+            written[op.out] = 1;
+        }
+        if (!written[t.output]) return fail(c, GACER_ESHAPE, "tenant %d: output tensor is never written", ti);
+        Tenant &T = fresh[ti];
+        T.ops.assign(t.ops, t.ops + t.n_ops);
+        T.tensors.assign(t.tensors, t.tensors + t.n_tensors);
+        T.input = t.input; T.output = t.output; T.batch = t.batch; T.dtype = t.dtype;
+        T.stream = (hipStream_t)t.stream;
+    }
+    for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    c->tenants.swap(fresh);
+    c->loaded = true;
+    expand_plain(c);
+    c->err.clear();
+    return install_plan(c, {}, {});
+}
+
+gacer_status gacer_set_plan(gacer_ctx *c, const gacer_plan *plan)
+{
+    if (!c) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_set_plan before gacer_load_tenants");
+    std::vector<gacer_split> sp;
+    std::vector<gacer_sync> sy;
+    if (plan) {
+        if ((plan->n_split > 0 && !plan->split) || (plan->n_sync > 0 && !plan->sync) || plan->n_split < 0 || plan->n_sync < 0)
+            return fail(c, GACER_EINVAL, "plan arrays missing");
+        sp.assign(plan->split, plan->split + plan->n_split);
+        sy.assign(plan->sync, plan->sync + plan->n_sync);
+    }
+    return install_plan(c, sp, sy);
+}
+
+gacer_status gacer_plan_from_pointers(gacer_ctx *c, const int *P, int n_ptr, gacer_plan **out)
+{
+    if (!c || !out) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_plan_from_pointers before gacer_load_tenants");
+    if (n_ptr < 0 || (n_ptr > 0 && !P)) return fail(c, GACER_EINVAL, "bad pointer matrix");
+    const int NT = (int)c->tenants.size();
+    for (int t = 0; t < NT; ++t)
+        for (int j = 0; j < n_ptr; ++j) {
+            const int p = P[t * n_ptr + j];
+            if (p < 0 || p > (int)c->tenants[t].ops.size() || (j > 0 && p < P[t * n_ptr + j - 1]))
+                return fail(c, GACER_EPLAN, "tenant %d: pointers must be sorted and lie in [0, n_ops]", t);
+        }
+    std::vector<gacer_sync> edges;
+    for (int j = 0; j < n_ptr; ++j)
+        for (int a = 0; a < NT; ++a) {
+            const int last = P[a * n_ptr + j] - 1;               // 0-based last operator of a's segments <= j
+            if (last < 0) continue;
+            for (int b = 0; b < NT; ++b) {
+                if (a == b) continue;
+                const int first = P[b * n_ptr + j];              // 0-based first operator after the pointer
+                if (first >= (int)c->tenants[b].ops.size()) continue;
+                edges.push_back({a, last, b, first});
+            }
+        }
+    gacer_plan *pl = new (std::nothrow) gacer_plan();
+    if (!pl) return fail(c, GACER_ENOMEM, "out of memory");
+    pl->n_split = 0; pl->split = nullptr;
+    pl->n_sync = (int)edges.size();
+    gacer_sync *arr = edges.empty() ? nullptr : new (std::nothrow) gacer_sync[edges.size()];
+    if (!edges.empty() && !arr) { delete pl; return fail(c, GACER_ENOMEM, "out of memory"); }
+    std::copy(edges.begin(), edges.end(), arr);
+    pl->sync = arr;
+    *out = pl;
+    return GACER_OK;
+}
+
+void gacer_plan_free(gacer_plan *p)
+{
+    if (!p) return;
+    delete[] p->split;
+    delete[] p->sync;
+    delete p;
+}
+
+static gacer_status issue_op(Ctx *c, const OpExec &e, hipStream_t s, bool with_events)
+{
+    if (with_events)
+        for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
+    for (const Launch &l : e.chunks) enqueue(l, s, false);
+    if (with_events && e.record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.record], s));
+    return GACER_OK;
+}
+
+gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
+{
+    if (!c) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_run before gacer_load_tenants");
+    if (mode < 0 || mode > 2 || rounds < 1) return fail(c, GACER_EINVAL, "bad mode or rounds");
+    const int NT = (int)c->tenants.size();
+    while ((int)c->t_start.size() < rounds) {
+        hipEvent_t a, b;
+        HIPCHK(c, hipEventCreate(&a));
+        c->t_start.push_back(a);
+        HIPCHK(c, hipEventCreate(&b));
+        c->t_end.push_back(b);
+    }
+    while (c->sync_events.size() < c->n_sync_events) {
+        hipEvent_t ev;
+        HIPCHK(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        c->sync_events.push_back(ev);
+    }
+    while ((int)c->join_events.size() < NT) {
+        hipEvent_t e;
+        HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c->join_events.push_back(e);
+    }
+    hipStream_t s0 = c->tenants[0].stream;
+    for (int r = 0; r < rounds; ++r) {
+        HIPCHK(c, hipEventRecord(c->t_start[r], s0));
+        if (mode == GACER_MODE_SEQUENTIAL) {
+            for (int t = 0; t < NT; ++t)
+                for (const OpExec &e : c->plain_exec[t]) {
+                    gacer_status st = issue_op(c, e, s0, false);
+                    if (st != GACER_OK) return st;
+                }
+        } else {
+            for (int t = 1; t < NT; ++t)
+                if (c->tenants[t].stream != s0) HIPCHK(c, hipStreamWaitEvent(c->tenants[t].stream, c->t_start[r], 0));
+            const bool plan = (mode == GACER_MODE_PLAN);
+            const auto &order = plan ? c->plan_order : c->par_order;
+            const auto &ex = plan ? c->plan_exec : c->plain_exec;
+            for (const auto &to : order) {
+                gacer_status st = issue_op(c, ex[to.first][to.second], c->tenants[to.first].stream, plan);
+                if (st != GACER_OK) return st;
+            }
+            for (int t = 1; t < NT; ++t)
+                if (c->tenants[t].stream != s0) {
+                    HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
+                    HIPCHK(c, hipStreamWaitEvent(s0, c->join_events[t], 0));
+                }
+        }
+        HIPCHK(c, hipEventRecord(c->t_end[r], s0));
+    }
+    HIPCHK(c, hipStreamSynchronize(s0));
+    HIPCHK(c, hipGetLastError());
+    if (ms_per_round)
+        for (int r = 0; r < rounds; ++r) HIPCHK(c, hipEventElapsedTime(&ms_per_round[r], c->t_start[r], c->t_end[r]));
+    return GACER_OK;
+}
+
+gacer_status gacer_launch_count(gacer_ctx *c, int mode, int *count)
+{
+    if (!c || !count) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "no tenants loaded");
+    const auto &ex = (mode == GACER_MODE_PLAN) ? c->plan_exec : c->plain_exec;
+    int n = 0;
+    for (const auto &t : ex)
+        for (const OpExec &e : t) n += (int)e.chunks.size();
+    *count = n;
+    return GACER_OK;
+}
+
+// Lookup table of Section 4.1: isolated time per chunk, workgroups per chunk and CU share.
+gacer_status gacer_profile(gacer_ctx *c, gacer_prof *out, size_t cap, size_t *n_out)
+{
+    if (!c || !n_out) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_profile before gacer_load_tenants");
+    const int NT = (int)c->tenants.size();
+    static const int factors[3] = {2, 4, 8};
+    struct Variant { int t, op; gacer_axis axis; int f; };
+    std::vector<Variant> vars;
+    for (int t = 0; t < NT; ++t)
+        for (int i = 0; i < (int)c->tenants[t].ops.size(); ++i) {
+            vars.push_back({t, i, GACER_AXIS_NONE, 1});
+            for (gacer_axis ax : {GACER_AXIS_BATCH, GACER_AXIS_COUT})
+                for (int f : factors)
+                    if (axis_legal(c->tenants[t].ops[i].kind, ax) && f <= axis_extent(c->tenants[t], i, ax)) vars.push_back({t, i, ax, f});
+        }
+    *n_out = vars.size() + 1;
+    if (cap == 0 || !out) return GACER_OK;
+    if (cap < vars.size() + 1) return fail(c, GACER_EINVAL, "profile buffer too small (%zu rows needed)", vars.size() + 1);
+    gacer_status st = gacer_run(c, GACER_MODE_SEQUENTIAL, 1, nullptr);   // populate every tensor
+    if (st != GACER_OK) return st;
+    hipEvent_t e0, e1;
+    HIPCHK(c, hipEventCreate(&e0));
+    HIPCHK(c, hipEventCreate(&e1));
+    const int reps = 5;
+    size_t k = 0;
+    for (const Variant &v : vars) {
+        const Tenant &T = c->tenants[v.t];
+        const int cout = (int)T.tensors[T.ops[v.op].out].c;
+        std::vector<Launch> ch;
+        for (int j = 0; j < v.f; ++j) {
+            int lo, hi;
+            if (v.axis == GACER_AXIS_BATCH) { chunk_range(T.batch, v.f, j, &lo, &hi); ch.push_back(make_launch(T, v.op, lo, hi, 0, cout)); }
+            else if (v.axis == GACER_AXIS_COUT) { chunk_range(cout, v.f, j, &lo, &hi); ch.push_back(make_launch(T, v.op, 0, T.batch, lo, hi)); }
+            else ch.push_back(make_launch(T, v.op, 0, T.batch, 0, cout));
+        }
+        const LaunchInfo li = enqueue(ch[0], T.stream, true);
+        for (const Launch &l : ch) enqueue(l, T.stream, false);            // warm-up
+        HIPCHK(c, hipEventRecord(e0, T.stream));
+        for (int r = 0; r < reps; ++r)
+            for (const Launch &l : ch) enqueue(l, T.stream, false);
+        HIPCHK(c, hipEventRecord(e1, T.stream));
+        HIPCHK(c, hipEventSynchronize(e1));
+        float ms = 0.f;
+        HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+        gacer_prof &p = out[k++];
+        p.tenant = v.t; p.op = v.op; p.axis = v.axis; p.factor = v.f;
+        p.ms = ms / (float)(reps * v.f);
+        p.workgroups = li.workgroups;
+        const float share = (float)li.workgroups / (float)(c->n_cu * std::max(1, li.wg_per_cu));
+        p.cu_share = std::min(1.f, std::max(share, 1.f / (float)(c->n_cu * 8)));
+    }
+    // T_SW: extra latency of one cross-stream event hop (record on one stream, wait on another),
+    // measured as ping-pong between two tenant streams against the same launches on one stream.
+    float t_sw = 0.f;
+    if (NT >= 2 && c->tenants[0].stream != c->tenants[1].stream) {
+        const Tenant &A = c->tenants[0], &B = c->tenants[1];
+        Launch la = make_launch(A, 0, 0, 1, 0, 1), lb = make_launch(B, 0, 0, 1, 0, 1);   // tiny: one item, one channel
+        hipEvent_t pa, pb;
+        HIPCHK(c, hipEventCreateWithFlags(&pa, hipEventDisableTiming));
+        HIPCHK(c, hipEventCreateWithFlags(&pb, hipEventDisableTiming));
+        const int hops = 50;
+        float serial = 0.f, pingpong = 0.f;
+        HIPCHK(c, hipStreamSynchronize(B.stream));
+        HIPCHK(c, hipEventRecord(e0, A.stream));
+        for (int h = 0; h < hops; ++h) { enqueue(la, A.stream, false); enqueue(lb, A.stream, false); }
+        HIPCHK(c, hipEventRecord(e1, A.stream));
+        HIPCHK(c, hipEventSynchronize(e1));
+        HIPCHK(c, hipEventElapsedTime(&serial, e0, e1));
+        HIPCHK(c, hipEventRecord(e0, A.stream));
+        for (int h = 0; h < hops; ++h) {
+            enqueue(la, A.stream, false);
+            HIPCHK(c, hipEventRecord(pa, A.stream));
+            HIPCHK(c, hipStreamWaitEvent(B.stream, pa, 0));
+            enqueue(lb, B.stream, false);
+            HIPCHK(c, hipEventRecord(pb, B.stream));
+            HIPCHK(c, hipStreamWaitEvent(A.stream, pb, 0));
+        }
+        HIPCHK(c, hipEventRecord(e1, A.stream));
+        HIPCHK(c, hipEventSynchronize(e1));
+        HIPCHK(c, hipEventElapsedTime(&pingpong, e0, e1));
+        t_sw = std::max(0.f, (pingpong - serial) / (float)(2 * hops));
+        (void)hipEventDestroy(pa);
+        (void)hipEventDestroy(pb);
+        st = gacer_run(c, GACER_MODE_SEQUENTIAL, 1, nullptr);   // restore tensors touched by the tiny launches
+        if (st != GACER_OK) return st;
+    }
+    gacer_prof &p = out[k++];
+    p.tenant = -1; p.op = -1; p.axis = GACER_AXIS_NONE; p.factor = 1; p.ms = t_sw; p.workgroups = 0; p.cu_share = 1.f;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return GACER_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,68 @@
+// Internal launch interface between the executor and the gfx950 kernels.
+// Every launcher enqueues exactly one kernel on `s` covering only the requested sub-range
+// (a decomposed operator chunk, Eq. 5, is a real smaller launch).  Launchers validate nothing:
+// the executor checks shapes when tenants are loaded and sub-ranges when a plan is set.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+namespace gacer {
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
+
+// Implicit-GEMM view of conv / GEMM / attention products:  Y[m][n] = sum_k A[m][k] * B[n][k].
+//   rows m  = output positions (image, oh, ow), cols n = output channels, k = (tap r, tap s, ci).
+//   A is gathered from a channels-last tensor, B rows are contiguous in k (b_trans == 0) or
+//   B is stored [k][n] (b_trans == 1, attention values).
+// z = blockIdx.z walks `zb * zh` independent problems (attention: batch x heads) through the
+// *_zb / *_zh element offsets.
+struct GemmArgs {
+    const void *x, *w;
+    const float *bias;
+    const void *res;
+    void *y;
+    int dtype;
+    int H, W, Cin;             // input extent per image and channels read per tap
+    int Ho, Wo;                // output extent per image
+    int kh, kw, stride, pad;
+    int K;                     // kh*kw*Cin
+    int64_t x_pix;             // elements between neighbouring input pixels
+    int64_t x_img;             // elements between images
+    int64_t w_row;             // elements between B rows (b_trans: between k rows)
+    int64_t y_row;             // elements between output rows (also used for res)
+    int m_lo, m_hi;            // output row sub-range
+    int n_lo, n_hi;            // output channel sub-range
+    int act;
+    float alpha;               // scale applied to the accumulator before bias
+    int b_trans;
+    int zb, zh;
+    int64_t x_zb, x_zh, w_zb, w_zh, y_zb, y_zh;
+    int z_lo;                  // first zb index of the sub-range (zb counts problems launched)
+};
+
+// Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).
+struct StreamArgs {
+    const void *x, *x2, *res, *w;
+    const float *bias, *scale, *shift;
+    void *y;
+    int dtype;
+    int N, H, W, C, Ho, Wo;
+    int k, stride, pad;
+    int act;
+    float eps;
+    int n_lo, n_hi, c_lo, c_hi;
+    int64_t rows_per_item;     // row operators: rows (positions) per batch item
+};
+
+struct LaunchInfo { int workgroups; int threads; int lds_bytes; int wg_per_cu; };
+
+LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry);
+LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry);
+LaunchInfo launch_maxpool(const StreamArgs &a, hipStream_t s, bool dry);
+LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry);
+LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry);   // affine / add / act
+LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry);
+LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry);
+
+}  // namespace gacer

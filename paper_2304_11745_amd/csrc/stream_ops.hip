@@ -1,0 +1,299 @@
+// HBM-bound channels-last operators: depthwise convolution, pooling, fused per-channel
+// affine / residual add / activation, layer normalisation and softmax.
+//
+// All of them move 16-byte vectors along the channel axis (4 floats / 8 bfloat16) so that a
+// wavefront touches whole cache lines, and all of them are launched on a sub-range
+// (images [n_lo,n_hi) x channels [c_lo,c_hi)): a decomposed operator chunk is a smaller grid.
+// Each output element is produced by one thread (or one wavefront) with a fixed order of
+// operations, so results do not depend on how the operator was decomposed.
+#include <hip/hip_runtime.h>
+#include "device_util.h"
+#include "kernels.h"
+
+namespace gacer {
+
+static constexpr int TPB = 256;
+
+// ---- depthwise k x k convolution, weights [kh][kw][C] ------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(TPB) void dwconv_kernel(StreamArgs a)
+{
+    const int CV = (a.c_hi - a.c_lo) / V;
+    const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * CV;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= total) return;
+    const int cv = (int)(idx % CV);
+    int64_t p = idx / CV;
+    const int ow = (int)(p % a.Wo);
+    p /= a.Wo;
+    const int oh = (int)(p % a.Ho);
+    const int n = a.n_lo + (int)(p / a.Ho);
+    const int c = a.c_lo + cv * V;
+    const T *x = (const T *)a.x;
+    const T *w = (const T *)a.w;
+    float acc[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) acc[q] = 0.f;
+    for (int r = 0; r < a.k; ++r) {
+        const int ih = oh * a.stride - a.pad + r;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int s = 0; s < a.k; ++s) {
+            const int iw = ow * a.stride - a.pad + s;
+            if (iw < 0 || iw >= a.W) continue;
+            const Vec<T, V> xv = ld_vec<T, V>(x, (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c);
+            const Vec<T, V> wv = ld_vec<T, V>(w, (int64_t)(r * a.k + s) * a.C + c);
+#pragma unroll
+            for (int q = 0; q < V; ++q) acc[q] = __fmaf_rn(xv.get(q), wv.get(q), acc[q]);
+        }
+    }
+    const int64_t o = (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.C + c;
+    Vec<T, V> rv, yv;
+    if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
+#pragma unroll
+    for (int q = 0; q < V; ++q) {
+        float v = acc[q];
+        if (a.bias) v = __fadd_rn(v, a.bias[c + q]);
+        if (a.res) v = __fadd_rn(v, rv.get(q));
+        yv.set(q, activate(v, a.act));
+    }
+    st_vec<T, V>((T *)a.y, o, yv);
+}
+
+// ---- max pooling k x k ---------------------------------------------------------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
+{
+    const int CV = (a.c_hi - a.c_lo) / V;
+    const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * CV;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= total) return;
+    const int cv = (int)(idx % CV);
+    int64_t p = idx / CV;
+    const int ow = (int)(p % a.Wo);
+    p /= a.Wo;
+    const int oh = (int)(p % a.Ho);
+    const int n = a.n_lo + (int)(p / a.Ho);
+    const int c = a.c_lo + cv * V;
+    const T *x = (const T *)a.x;
+    float m[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) m[q] = -INFINITY;
+    for (int r = 0; r < a.k; ++r) {
+        const int ih = oh * a.stride - a.pad + r;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int s = 0; s < a.k; ++s) {
+            const int iw = ow * a.stride - a.pad + s;
+            if (iw < 0 || iw >= a.W) continue;
+            const Vec<T, V> xv = ld_vec<T, V>(x, (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c);
+#pragma unroll
+            for (int q = 0; q < V; ++q) m[q] = fmaxf(m[q], xv.get(q));
+        }
+    }
+    Vec<T, V> yv;
+#pragma unroll
+    for (int q = 0; q < V; ++q) yv.set(q, m[q]);
+    st_vec<T, V>((T *)a.y, (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.C + c, yv);
+}
+
+// ---- global average pooling ------------------------------------------------------------------------
+// One workgroup per (image, 64 channels): wavefront q sums positions q, q+4, ... of its channel
+// in order; the four partial sums are then added in order 0,1,2,3.
+template <typename T>
+__global__ __launch_bounds__(TPB) void gavgpool_kernel(StreamArgs a)
+{
+    __shared__ float part[4][64];
+    const int groups = (a.c_hi - a.c_lo + 63) / 64;
+    const int n = a.n_lo + blockIdx.x / groups;
+    const int c = a.c_lo + (blockIdx.x % groups) * 64 + (threadIdx.x & 63);
+    const int q = threadIdx.x >> 6;
+    const int HW = a.H * a.W;
+    const T *x = (const T *)a.x;
+    float s = 0.f;
+    if (c < a.c_hi)
+        for (int p = q; p < HW; p += 4) s = __fadd_rn(s, ld_f32(x, ((int64_t)n * HW + p) * a.C + c));
+    part[q][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (q == 0 && c < a.c_hi) {
+        const int l = threadIdx.x;
+        const float t = __fadd_rn(__fadd_rn(__fadd_rn(part[0][l], part[1][l]), part[2][l]), part[3][l]);
+        st_f32((T *)a.y, (int64_t)n * a.C + c, __fdiv_rn(t, (float)HW));
+    }
+}
+
+// ---- y = act(x*scale[c] + shift[c] + res)  |  y = act(x + x2)  |  y = act(x) -------------------------
+template <typename T, int V>
+__global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
+{
+    const int CV = (a.c_hi - a.c_lo) / V;
+    const int64_t P = (int64_t)a.H * a.W;
+    const int64_t total = (int64_t)(a.n_hi - a.n_lo) * P * CV;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= total) return;
+    const int cv = (int)(idx % CV);
+    const int64_t pos = (int64_t)a.n_lo * P + idx / CV;
+    const int c = a.c_lo + cv * V;
+    const int64_t o = pos * a.C + c;
+    const Vec<T, V> xv = ld_vec<T, V>((const T *)a.x, o);
+    Vec<T, V> bv, rv, yv;
+    if (a.x2) bv = ld_vec<T, V>((const T *)a.x2, o);
+    if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
+#pragma unroll
+    for (int q = 0; q < V; ++q) {
+        float v = xv.get(q);
+        if (a.scale) v = __fmaf_rn(v, a.scale[c + q], a.shift[c + q]);
+        if (a.x2) v = __fadd_rn(v, bv.get(q));
+        if (a.res) v = __fadd_rn(v, rv.get(q));
+        yv.set(q, activate(v, a.act));
+    }
+    st_vec<T, V>((T *)a.y, o, yv);
+}
+
+// ---- row operators: one wavefront per row (position), C features contiguous ---------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = __fadd_rn(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(TPB) void layernorm_kernel(StreamArgs a)
+{
+    const int64_t row = (int64_t)a.n_lo * a.rows_per_item + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (int64_t)a.n_hi * a.rows_per_item) return;
+    const int lane = threadIdx.x & 63;
+    const T *x = (const T *)a.x + row * a.C;
+    const T *r = a.res ? (const T *)a.res + row * a.C : nullptr;
+    float s = 0.f;
+    for (int c = lane; c < a.C; c += 64) s = __fadd_rn(s, r ? __fadd_rn(ld_f32(x, c), ld_f32(r, c)) : ld_f32(x, c));
+    const float mu = __fdiv_rn(wave_sum(s), (float)a.C);
+    float q = 0.f;
+    for (int c = lane; c < a.C; c += 64) {
+        const float d = __fsub_rn(r ? __fadd_rn(ld_f32(x, c), ld_f32(r, c)) : ld_f32(x, c), mu);
+        q = __fmaf_rn(d, d, q);
+    }
+    const float var = __fdiv_rn(wave_sum(q), (float)a.C);
+    const float inv = __fdiv_rn(1.f, __fsqrt_rn(__fadd_rn(var, a.eps)));
+    T *y = (T *)a.y + row * a.C;
+    for (int c = lane; c < a.C; c += 64) {
+        const float d = __fsub_rn(r ? __fadd_rn(ld_f32(x, c), ld_f32(r, c)) : ld_f32(x, c), mu);
+        st_f32(y, c, __fmaf_rn(__fmul_rn(d, inv), a.scale[c], a.shift[c]));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(TPB) void softmax_kernel(StreamArgs a)
+{
+    const int64_t row = (int64_t)a.n_lo * a.rows_per_item + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (int64_t)a.n_hi * a.rows_per_item) return;
+    const int lane = threadIdx.x & 63;
+    const T *x = (const T *)a.x + row * a.C;
+    float m = -INFINITY;
+    for (int c = lane; c < a.C; c += 64) m = fmaxf(m, ld_f32(x, c));
+    m = wave_max(m);
+    float s = 0.f;
+    for (int c = lane; c < a.C; c += 64) s = __fadd_rn(s, expf(__fsub_rn(ld_f32(x, c), m)));
+    s = wave_sum(s);
+    T *y = (T *)a.y + row * a.C;
+    for (int c = lane; c < a.C; c += 64) st_f32(y, c, __fdiv_rn(expf(__fsub_rn(ld_f32(x, c), m)), s));
+}
+
+// ---- launchers --------------------------------------------------------------------------------------
+static bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
+
+template <typename T, int VFULL>
+static bool vec_ok(const StreamArgs &a)
+{
+    return a.C % VFULL == 0 && a.c_lo % VFULL == 0 && (a.c_hi - a.c_lo) % VFULL == 0 && aligned16(a.x) && aligned16(a.y) &&
+           aligned16(a.x2) && aligned16(a.res) && aligned16(a.w);
+}
+
+static LaunchInfo info(int64_t wgs)
+{
+    LaunchInfo li;
+    li.workgroups = (int)wgs;
+    li.threads = TPB;
+    li.lds_bytes = 0;
+    li.wg_per_cu = 8;
+    return li;
+}
+
+#define GACER_DISPATCH_VEC(KERNEL)                                                                         \
+    if (a.dtype == DT_BF16) {                                                                              \
+        if (vec_ok<unsigned short, 8>(a)) {                                                                \
+            const int64_t g = (outs / 8 + TPB - 1) / TPB;                                                  \
+            if (!dry && g) hipLaunchKernelGGL((KERNEL<unsigned short, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); \
+            return info(g);                                                                                \
+        }                                                                                                  \
+        const int64_t g = (outs + TPB - 1) / TPB;                                                          \
+        if (!dry && g) hipLaunchKernelGGL((KERNEL<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);     \
+        return info(g);                                                                                    \
+    }                                                                                                      \
+    if (vec_ok<float, 4>(a)) {                                                                             \
+        const int64_t g = (outs / 4 + TPB - 1) / TPB;                                                      \
+        if (!dry && g) hipLaunchKernelGGL((KERNEL<float, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
+        return info(g);                                                                                    \
+    }                                                                                                      \
+    {                                                                                                      \
+        const int64_t g = (outs + TPB - 1) / TPB;                                                          \
+        if (!dry && g) hipLaunchKernelGGL((KERNEL<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
+        return info(g);                                                                                    \
+    }
+
+LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * (a.c_hi - a.c_lo);
+    GACER_DISPATCH_VEC(dwconv_kernel)
+}
+
+LaunchInfo launch_maxpool(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * (a.c_hi - a.c_lo);
+    GACER_DISPATCH_VEC(maxpool_kernel)
+}
+
+LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.H * a.W * (a.c_hi - a.c_lo);
+    GACER_DISPATCH_VEC(eltwise_kernel)
+}
+
+LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t g = (int64_t)(a.n_hi - a.n_lo) * ((a.c_hi - a.c_lo + 63) / 64);
+    if (!dry && g) {
+        if (a.dtype == DT_BF16) hipLaunchKernelGGL((gavgpool_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        else hipLaunchKernelGGL((gavgpool_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    }
+    return info(g);
+}
+
+LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t rows = (int64_t)(a.n_hi - a.n_lo) * a.rows_per_item;
+    const int64_t g = (rows + 3) / 4;
+    if (!dry && g) {
+        if (a.dtype == DT_BF16) hipLaunchKernelGGL((layernorm_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        else hipLaunchKernelGGL((layernorm_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    }
+    return info(g);
+}
+
+LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t rows = (int64_t)(a.n_hi - a.n_lo) * a.rows_per_item;
+    const int64_t g = (rows + 3) / 4;
+    if (!dry && g) {
+        if (a.dtype == DT_BF16) hipLaunchKernelGGL((softmax_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        else hipLaunchKernelGGL((softmax_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    }
+    return info(g);
+}
+
+}  // namespace gacer

@@ -1,0 +1,192 @@
+"""Device-memory plumbing around the C ABI: allocate tensors and streams with PyTorch, lay the
+seeded data out the way include/gacer.h specifies (channels-last activations, [cout][kh][kw][cin]
+weights), fill the descriptor structs, and convert outputs back to logical NCHW.  No arithmetic
+happens here; every operator runs inside libgacer.so.
+"""
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_KIND = {"conv": B.GACER_CONV2D, "dwconv": B.GACER_DWCONV2D, "gemm": B.GACER_GEMM, "bgemm_qk": B.GACER_BGEMM_QK,
+         "bgemm_pv": B.GACER_BGEMM_PV, "maxpool": B.GACER_MAXPOOL, "gavgpool": B.GACER_GAVGPOOL,
+         "affine": B.GACER_AFFINE_ACT, "add": B.GACER_ADD, "layernorm": B.GACER_LAYERNORM,
+         "softmax": B.GACER_SOFTMAX, "act": B.GACER_ACT}
+_ACT = {"none": B.GACER_ACT_NONE, "relu": B.GACER_ACT_RELU, "relu6": B.GACER_ACT_RELU6, "gelu": B.GACER_ACT_GELU}
+AXIS = {"none": B.GACER_AXIS_NONE, "batch": B.GACER_AXIS_BATCH, "cout": B.GACER_AXIS_COUT}
+COUT_SPLITTABLE = ("conv", "dwconv", "gemm", "maxpool", "gavgpool", "affine")
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+class Session:
+    """One gacer context with its tenants resident in HBM."""
+
+    def __init__(self, tenants, data, device="cuda:0", shared_stream=False):
+        if not torch.cuda.is_available():
+            raise RuntimeError("a GPU is required: the library has no CPU fallback")
+        self.dev = torch.device(device)
+        torch.cuda.set_device(self.dev)
+        self.tenants = tenants
+        self.ctx = C.c_void_p()
+        B.check(self.ctx, B.gacer_create(C.byref(self.ctx)))
+        self._keep = []
+        self.streams = []
+        self.acts = []          # per tenant: list of device tensors (channels-last)
+        descs = (B.gacer_tenant * len(tenants))()
+        for ti, (t, (x, params)) in enumerate(zip(tenants, data)):
+            tdt = torch.bfloat16 if t.dtype == "bf16" else torch.float32
+            acts = [torch.zeros((n, h, w, c), dtype=tdt, device=self.dev) for (n, c, h, w) in t.tensors]
+            acts[t.input].copy_(torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))).to(tdt))
+            self.acts.append(acts)
+            tens = (B.gacer_tensor * len(acts))()
+            for i, ((n, c, h, w), a) in enumerate(zip(t.tensors, acts)):
+                tens[i] = B.gacer_tensor(n, c, h, w, a.data_ptr())
+            dev_params = {}
+
+            def dparam(idx, kind=None, op=None):
+                if idx < 0:
+                    return None
+                key = (idx, kind)
+                if key not in dev_params:
+                    a = params[idx]
+                    if kind == "conv":
+                        a = a.transpose(0, 2, 3, 1)                              # [O][I][kh][kw] -> [O][kh][kw][I]
+                    elif kind == "dwconv":
+                        a = a[:, 0].transpose(1, 2, 0)                           # [C][1][kh][kw] -> [kh][kw][C]
+                    elif kind == "gemm_flat":
+                        n, c, h, w = t.tensors[op.in0]
+                        a = a.reshape(a.shape[0], c, h, w).transpose(0, 2, 3, 1)   # (c,h,w) -> (h,w,c) feature order
+                    wdt = tdt if kind is not None else torch.float32
+                    dev_params[key] = torch.from_numpy(np.ascontiguousarray(a)).to(wdt).to(self.dev).contiguous()
+                return dev_params[key]
+
+            ops = (B.gacer_op * len(t.ops))()
+            for i, op in enumerate(t.ops):
+                wkind = None
+                if op.kind == "conv":
+                    wkind = "conv"
+                elif op.kind == "dwconv":
+                    wkind = "dwconv"
+                elif op.kind == "gemm":
+                    n, c, h, w = t.tensors[op.in0]
+                    wkind = "gemm_flat" if (op.cin != c and h * w > 1) else "gemm"
+                alpha = op.eps if op.kind == "layernorm" else op.alpha
+                ops[i] = B.gacer_op(_KIND[op.kind], op.in0, op.in1, op.res, op.out,
+                                    _ptr(dparam(op.w, wkind, op)), _ptr(dparam(op.bias)), _ptr(dparam(op.scale)),
+                                    _ptr(dparam(op.shift)), op.cin, op.cout, op.kh, op.kw, op.stride, op.pad,
+                                    op.groups, _ACT[op.act], alpha)
+            if shared_stream and self.streams:
+                s = self.streams[0]
+            else:
+                s = torch.cuda.Stream(device=self.dev)
+            self.streams.append(s)
+            descs[ti] = B.gacer_tenant(len(t.ops), ops, len(acts), tens, t.input, t.output,
+                                       B.GACER_BF16 if t.dtype == "bf16" else B.GACER_F32, t.batch,
+                                       C.c_void_p(s.cuda_stream))
+            self._keep += [tens, ops, dev_params]
+        torch.cuda.synchronize(self.dev)
+        self._descs = descs
+        B.check(self.ctx, B.gacer_load_tenants(self.ctx, descs, len(tenants)))
+
+    # -- plan ------------------------------------------------------------------------------------
+    def set_plan(self, splits=(), syncs=()):
+        """splits: iterable of (tenant, op, axis-name, factor); syncs: (src_t, src_op, dst_t, dst_op)."""
+        sp = (B.gacer_split * max(1, len(splits)))(*[B.gacer_split(t, o, AXIS[a], f) for (t, o, a, f) in splits])
+        sy = (B.gacer_sync * max(1, len(syncs)))(*[B.gacer_sync(*e) for e in syncs])
+        plan = B.gacer_plan(len(splits), sp, len(syncs), sy)
+        B.check(self.ctx, B.gacer_set_plan(self.ctx, C.byref(plan)))
+
+    def clear_plan(self):
+        B.check(self.ctx, B.gacer_set_plan(self.ctx, None))
+
+    def edges_from_pointers(self, matrix_P):
+        n_ptr = len(matrix_P[0])
+        flat = (C.c_int * max(1, len(matrix_P) * n_ptr))(*[p for P in matrix_P for p in P])
+        out = C.POINTER(B.gacer_plan)()
+        B.check(self.ctx, B.gacer_plan_from_pointers(self.ctx, flat, n_ptr, C.byref(out)))
+        edges = [(out.contents.sync[i].src_tenant, out.contents.sync[i].src_op, out.contents.sync[i].dst_tenant,
+                  out.contents.sync[i].dst_op) for i in range(out.contents.n_sync)]
+        B.gacer_plan_free(out)
+        return edges
+
+    def uniform_splits(self, axis, factor, tenants=None):
+        """Every operator that can be decomposed ``factor`` ways on ``axis`` (of the given tenants)."""
+        out = []
+        for ti, t in enumerate(self.tenants):
+            if tenants is not None and ti not in tenants:
+                continue
+            for oi, op in enumerate(t.ops):
+                if axis == "cout" and op.kind not in COUT_SPLITTABLE:
+                    continue
+                ext = t.batch if axis == "batch" else t.tensors[op.out][1]
+                if factor <= ext:
+                    out.append((ti, oi, axis, factor))
+        return out
+
+    # -- execution -------------------------------------------------------------------------------
+    def run(self, mode=B.GACER_MODE_PLAN, rounds=1):
+        ms = (C.c_float * rounds)()
+        B.check(self.ctx, B.gacer_run(self.ctx, mode, rounds, ms))
+        return list(ms)
+
+    def launch_count(self, mode=B.GACER_MODE_PLAN):
+        n = C.c_int()
+        B.check(self.ctx, B.gacer_launch_count(self.ctx, mode, C.byref(n)))
+        return n.value
+
+    def tensor(self, ti, idx):
+        """Tensor ``idx`` of tenant ``ti`` as float32 numpy in logical NCHW order."""
+        return self.acts[ti][idx].float().permute(0, 3, 1, 2).contiguous().cpu().numpy()
+
+    def output(self, ti):
+        return self.tensor(ti, self.tenants[ti].output)
+
+    def output_bytes(self, ti):
+        a = self.acts[ti][self.tenants[ti].output]
+        return a.contiguous().view(torch.uint8).cpu().numpy().tobytes()
+
+    def poison_outputs(self):
+        """Overwrite every non-input tensor with NaN so stale results cannot pass for fresh ones."""
+        for t, acts in zip(self.tenants, self.acts):
+            for i, a in enumerate(acts):
+                if i != t.input:
+                    a.fill_(float("nan"))
+        torch.cuda.synchronize(self.dev)
+
+    # -- lookup table and search -------------------------------------------------------------------
+    def profile(self):
+        n = C.c_size_t()
+        B.check(self.ctx, B.gacer_profile(self.ctx, None, 0, C.byref(n)))
+        rows = (B.gacer_prof * n.value)()
+        B.check(self.ctx, B.gacer_profile(self.ctx, rows, n.value, C.byref(n)))
+        return rows
+
+    def search(self, rows, max_rounds=100):
+        out = C.POINTER(B.gacer_plan)()
+        ptrs = (C.c_int * (8 * len(self.tenants)))()
+        n_ptr = C.c_int()
+        R = C.c_double()
+        B.check(self.ctx, B.gacer_search(self.ctx, rows, len(rows), max_rounds, C.byref(out), ptrs, C.byref(n_ptr), C.byref(R)))
+        pl = out.contents
+        inv = {v: k for k, v in AXIS.items()}
+        splits = [(pl.split[i].tenant, pl.split[i].op, inv[pl.split[i].axis], pl.split[i].factor) for i in range(pl.n_split)]
+        syncs = [(pl.sync[i].src_tenant, pl.sync[i].src_op, pl.sync[i].dst_tenant, pl.sync[i].dst_op) for i in range(pl.n_sync)]
+        B.gacer_plan_free(out)
+        P = [[ptrs[t * n_ptr.value + j] for j in range(n_ptr.value)] for t in range(len(self.tenants))]
+        return splits, syncs, P, R.value
+
+    def close(self):
+        if self.ctx:
+            B.gacer_destroy(self.ctx)
+            self.ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,110 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, and bit-exactness of
+every regulation plan against the unsplit run."""
+import numpy as np
+import pytest
+
+import synth
+from parity import TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2304_11745_amd import harness
+    return harness
+
+
+def _oracle_outputs(tenants, data):
+    from oracle import forward as F
+    return [F.run_tenant(t, x, p) for t, (x, p) in zip(tenants, data)]
+
+
+def _check_all_modes_and_plans(gpu, tenants, data, plans, check_intermediate=False):
+    from paper_2304_11745_amd import binding as B
+    from oracle import forward as F
+    sess = gpu.Session(tenants, data)
+    ref = _oracle_outputs(tenants, data)
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    base = [sess.output_bytes(i) for i in range(len(tenants))]
+    for i, t in enumerate(tenants):
+        out = sess.output(i)
+        assert np.isfinite(out).all(), f"{t.name}: non-finite output"
+        e = rel_err(out, ref[i])
+        print(f"{t.name}[{t.dtype}] sequential rel_err={e:.3e}")
+        assert e <= TOL[t.dtype], f"{t.name}: rel err {e} > {TOL[t.dtype]}"
+    if check_intermediate:
+        for i, (t, (x, p)) in enumerate(zip(tenants, data)):
+            allref = F.run_tenant(t, x, p, keep_all=True)
+            for k, op in enumerate(t.ops):
+                e = rel_err(sess.tensor(i, op.out), allref[op.out])
+                assert e <= TOL[t.dtype], f"{t.name} op {k} ({op.kind}): rel err {e}"
+    for mode in (B.GACER_MODE_STREAM_PARALLEL, B.GACER_MODE_PLAN):
+        sess.poison_outputs()
+        sess.run(mode, 2)
+        for i in range(len(tenants)):
+            assert sess.output_bytes(i) == base[i], f"mode {mode}: tenant {i} differs from sequential"
+    for name, (splits, ptrs) in plans(sess).items():
+        syncs = sess.edges_from_pointers(ptrs) if ptrs else []
+        sess.set_plan(splits, syncs)
+        sess.poison_outputs()
+        sess.run(B.GACER_MODE_PLAN, 2)
+        for i in range(len(tenants)):
+            assert sess.output_bytes(i) == base[i], f"plan {name}: tenant {i} not bit-identical to the unsplit run"
+        print(f"plan {name}: {sess.launch_count()} launches, bit-exact")
+    sess.close()
+
+
+def _sweep_plans(sess):
+    plans = {}
+    for axis in ("batch", "cout"):
+        for f in (2, 4, 8):
+            sp = sess.uniform_splits(axis, f)
+            if sp:
+                plans[f"{axis}x{f}"] = (sp, None)
+    n_ops = [len(t.ops) for t in sess.tenants]
+    plans["pointers1"] = ([], [[n // 2] for n in n_ops])
+    plans["pointers3+cout2"] = (sess.uniform_splits("cout", 2), [[0, n // 3, n] for n in n_ops])
+    plans["pointers2+batch2-tenant0"] = (sess.uniform_splits("batch", 2, tenants=[0]) if sess.tenants[0].batch >= 2 else [],
+                                         [[1, n - 1] for n in n_ops])
+    return plans
+
+
+def test_config1_toy_pair(gpu):
+    tenants, data = synth.build_config(1)
+
+    def plans(sess):
+        return {"unsplit": ([], None),
+                "convs-2way-cout": ([(0, 0, "cout", 2), (0, 1, "cout", 2)], None),
+                **_sweep_plans(sess)}
+    _check_all_modes_and_plans(gpu, tenants, data, plans, check_intermediate=True)
+
+
+@pytest.mark.parametrize("config", [2, 3, 4, 5])
+def test_small_families(gpu, config):
+    tenants, data = synth.build_config(config, "small")
+    _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
+
+
+def test_small_families_f32_all_kinds(gpu):
+    """Every operator kind in fp32, including the transformer tenant and standalone affine/add/act ops."""
+    from synth import graphs as G
+    b = G._B("eltwise_mix", "f32", 3)
+    x = b.tensor(3, 20, 9, 7)
+    y = b.conv(x, 24, 3, 1, 1, "none")
+    y = b.affine(y, "relu")
+    z = b.conv(y, 24, 1, 1, 0, "none")
+    z = b.affine(z, "none", res=y)
+    y = b.add(z, y, "relu6")
+    y = b.act(y, "gelu")
+    y = b.maxpool(y, 3, 2, 1)
+    y = b.gavgpool(y)
+    y = b.gemm(y, 13, flatten=True)
+    t = b.done(x, y)
+    tenants = [t, G.small_bert("f32", 3), G.small_mbv2("f32", 2)]
+    data = [G.materialise(tt, 77, i << 20) for i, tt in enumerate(tenants)]
+    _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
