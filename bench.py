@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Multi-tenant throughput benchmark on one MI355X.
+
+A step is one round: every tenant of the workload runs once (inputs, weights and activations
+resident in HBM).  Three executions of the same kernels are timed: sequential (one stream, unsplit),
+stream-parallel (one stream per tenant, unsplit, no ordering) and regulated (the chosen plan:
+operator chunks + pointer edges).  ``value`` is the regulated aggregate items/s.
+
+Prints ONE JSON line.  Plan selection (profile, search, short trials) happens before the timed
+region, as in offline deployment (Section 4.4, "Search Cost Analysis").
+"""
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"f32": 157.3e12, "bf16": 2.5e15}        # dense MFMA FLOP/s, MI355X
+HBM_PEAK = 8.0e12
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def timed_rounds(sess, mode, steps, warmup):
+    import torch
+    sess.run(mode, max(1, warmup))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    per_round = sess.run(mode, steps)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    return wall_ms, per_round
+
+
+def choose_plan(sess, B, trial_rounds):
+    """Candidates: the searched plan, plain stream-parallel, and uniform sweeps; keep the fastest."""
+    t0 = time.perf_counter()
+    rows = sess.profile()
+    t_prof = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    splits, syncs, P, R = sess.search(rows, 100)
+    t_search = time.perf_counter() - t0
+    cands = {"searched": (splits, syncs), "unsplit": ([], [])}
+    for axis in ("batch", "cout"):
+        for f in (2, 4):
+            sp = sess.uniform_splits(axis, f)
+            if sp:
+                cands[f"sweep-{axis}x{f}"] = (sp, [])
+    heavy = [i for i, t in enumerate(sess.tenants)]
+    results = {}
+    for name, (sp, sy) in cands.items():
+        sess.set_plan(sp, sy)
+        sess.run(B.GACER_MODE_PLAN, 3)
+        ms = sess.run(B.GACER_MODE_PLAN, trial_rounds)
+        results[name] = statistics.median(ms)
+    best = min(results, key=results.get)
+    info = {"profile_s": round(t_prof, 3), "search_s": round(t_search, 4), "searched_pointers": P,
+            "searched_splits": len(splits), "model_residue": R,
+            "trial_ms": {k: round(v, 4) for k, v in results.items()}, "chosen": best}
+    sp, sy = cands[best]
+    sess.set_plan(sp, sy)
+    return info
+
+
+def cpu_baseline(tenants, data, items):
+    """The oracle as it stands, timed on the host cores, on one full round of the workload."""
+    from oracle import forward as F
+    F.lib()
+    t0 = time.perf_counter()
+    for t, (x, p) in zip(tenants, data):
+        F.run_tenant(t, x, p)
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
+    return {"value": items / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"one full round of the workload ({items} items), {dt:.2f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--scale", default="full", choices=["full", "small"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plan", default="auto", help="auto | unsplit")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (tenants shard across GPUs with no exchange); use --gpus 1")
+
+    import torch
+    import synth
+    from paper_2304_11745_amd import binding as B
+    from paper_2304_11745_amd import harness
+
+    tenants, data = synth.build_config(args.config, args.scale)
+    items = sum(t.batch for t in tenants)
+    dtype = tenants[0].dtype
+    macs = sum(synth.gemm_macs(t) for t in tenants)
+    sess = harness.Session(tenants, data, "cuda:0")
+    sess.run(B.GACER_MODE_SEQUENTIAL, 3)
+
+    plan_info = {"chosen": "unsplit"}
+    if args.plan == "auto":
+        plan_info = choose_plan(sess, B, 10)
+        log("plan selection:", json.dumps(plan_info))
+
+    seq_ms, seq_rounds = timed_rounds(sess, B.GACER_MODE_SEQUENTIAL, args.steps, args.warmup)
+    par_ms, par_rounds = timed_rounds(sess, B.GACER_MODE_STREAM_PARALLEL, args.steps, args.warmup)
+    reg_ms, reg_rounds = timed_rounds(sess, B.GACER_MODE_PLAN, args.steps, args.warmup)
+
+    # per-launch durations of the regulated round, on the streams the kernels run on
+    trace = sess.trace(B.GACER_MODE_PLAN, 5)
+    per_kernel = {}
+    for r in trace:
+        k = per_kernel.setdefault(r["kernel"], {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        k["ms"] += r["ms"]; k["flops"] += r["flops"]; k["bytes"] += r["bytes"]; k["launches"] += 1
+    dom = max(per_kernel, key=lambda n: per_kernel[n]["ms"])
+    d = per_kernel[dom]
+    avg_ms = d["ms"] / d["launches"]
+    if d["flops"] > 0:
+        achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
+                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": None}
+    else:
+        achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": None}
+    roof.update({"kernel": dom, "launches_per_round": d["launches"], "avg_launch_us": avg_ms * 1e3,
+                 "share_of_kernel_time": d["ms"] / sum(k["ms"] for k in per_kernel.values())})
+
+    out = {
+        "metric": "aggregate tenant images/s (regulated concurrent run)",
+        "value": items / (reg_ms * 1e-3),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": reg_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}]: {synth.CONFIG_NAMES[args.config]}" + (" (small)" if args.scale == "small" else ""),
+                   "items_per_round": items, "tenants": [f"{t.name}({t.batch})" for t in tenants],
+                   "plan": plan_info.get("chosen"), "launches_per_round": sess.launch_count(B.GACER_MODE_PLAN)},
+        "sequential_images_per_s": items / (seq_ms * 1e-3),
+        "stream_parallel_images_per_s": items / (par_ms * 1e-3),
+        "speedup_vs_sequential": seq_ms / reg_ms,
+        "speedup_vs_stream_parallel": par_ms / reg_ms,
+        "makespan_ms_median": {"sequential": statistics.median(seq_rounds), "stream_parallel": statistics.median(par_rounds),
+                               "regulated": statistics.median(reg_rounds)},
+        "mfma_frac_of_peak": {"sequential": 2 * macs / (seq_ms * 1e-3) / PEAK[dtype],
+                              "stream_parallel": 2 * macs / (par_ms * 1e-3) / PEAK[dtype],
+                              "regulated": 2 * macs / (reg_ms * 1e-3) / PEAK[dtype]},
+        "plan_selection": plan_info,
+        "kernels": {k: {"launches": v["launches"], "ms_per_round": round(v["ms"], 4),
+                        "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else None,
+                        "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else None}
+                    for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1]["ms"])},
+        "roofline": roof,
+        "paper_context": "GACER reports 1.37x-1.66x over sequential cuDNN on Titan V (Section 5.2); other hardware, context only",
+    }
+    sess.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(tenants, data, items)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -127,6 +127,12 @@ typedef struct { int n_split; const gacer_split *split; int n_sync; const gacer_
  * with tenant == -1 carries the synchronisation wait T_SW (Eq. 8) in `ms`. */
 typedef struct { int tenant, op; gacer_axis axis; int factor; float ms; int workgroups; float cu_share; } gacer_prof;
 
+/* One kernel launch of a round, as measured by gacer_trace_run: average duration, algorithmic
+ * work of the launched sub-range (flops = 2*MACs for conv/GEMM/attention launches, 0 otherwise;
+ * bytes = inputs read once + parameters read once + output written once, at the tensor dtype),
+ * grid size and the kernel variant that ran. */
+typedef struct { int tenant, op, chunk; float ms; double flops; double bytes; int workgroups; char kernel[40]; } gacer_launch_stat;
+
 typedef enum { GACER_MODE_PLAN = 0, GACER_MODE_SEQUENTIAL = 1, GACER_MODE_STREAM_PARALLEL = 2 } gacer_mode;
 
 /* Creates an empty context bound to the current HIP device.  GACER_ENOMEM / GACER_EHIP. */
@@ -172,6 +178,15 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *ctx, const int *P, int n_ptr, g
  * hipEvents.  Returns after all work of all rounds has finished.
  */
 gacer_status gacer_run(gacer_ctx *ctx, int mode, int rounds, float *ms_per_round);
+
+/*
+ * Measurement aid: like gacer_run, but every kernel launch is bracketed by a hipEvent pair on the
+ * stream it runs on, so that per-launch durations under the chosen mode (including contention from
+ * the other tenants' streams) can be read back.  out[k].ms is the mean over `rounds`.  Writes up to
+ * `cap` rows (launch order of one round) and the row count to *n; cap = 0 sizes.  The event pairs
+ * perturb the schedule slightly; throughput must be taken from gacer_run.
+ */
+gacer_status gacer_trace_run(gacer_ctx *ctx, int mode, int rounds, gacer_launch_stat *out, size_t cap, size_t *n);
 
 /*
  * Builds the lookup table of Section 4.1 by timing, in isolation on the tenant's stream, every

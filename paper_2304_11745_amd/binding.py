@@ -19,7 +19,7 @@ GACER_MODE_PLAN, GACER_MODE_SEQUENTIAL, GACER_MODE_STREAM_PARALLEL = range(3)
 
 EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_plan", "gacer_plan_from_pointers",
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
-           "gacer_last_error", "gacer_launch_count"]
+           "gacer_last_error", "gacer_launch_count", "gacer_trace_run"]
 
 
 class gacer_tensor(C.Structure):
@@ -57,6 +57,11 @@ class gacer_prof(C.Structure):
                 ("workgroups", C.c_int), ("cu_share", C.c_float)]
 
 
+class gacer_launch_stat(C.Structure):
+    _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("chunk", C.c_int), ("ms", C.c_float), ("flops", C.c_double),
+                ("bytes", C.c_double), ("workgroups", C.c_int), ("kernel", C.c_char * 40)]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2304_11745_amd.build); "
@@ -80,6 +85,7 @@ def _load():
     lib.gacer_last_error.argtypes = [ctx]
     lib.gacer_last_error.restype = C.c_char_p
     lib.gacer_launch_count.argtypes = [ctx, C.c_int, C.POINTER(C.c_int)]
+    lib.gacer_trace_run.argtypes = [ctx, C.c_int, C.c_int, C.POINTER(gacer_launch_stat), C.c_size_t, C.POINTER(C.c_size_t)]
     return lib
 
 
@@ -97,6 +103,7 @@ gacer_model_residue = lib.gacer_model_residue
 gacer_plan_free = lib.gacer_plan_free
 gacer_last_error = lib.gacer_last_error
 gacer_launch_count = lib.gacer_launch_count
+gacer_trace_run = lib.gacer_trace_run
 
 
 class GacerError(RuntimeError):

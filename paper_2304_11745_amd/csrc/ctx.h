@@ -22,6 +22,11 @@ struct Tenant {
     int input = 0, output = 0, batch = 1;
     gacer_dtype dtype = GACER_F32;
     hipStream_t stream = nullptr;
+    // split-K bookkeeping (conv / GEMM operators only): slices and 64-byte K blocks per slice, fixed per
+    // operator from its unsplit shape; one library-owned workspace per tenant (its operators never overlap)
+    std::vector<int> ksplit, kb_per_slice;
+    float *ws = nullptr;
+    size_t ws_floats = 0;
 };
 
 // One operator after plan expansion: its chunk launches plus the events it waits on / records.
@@ -36,6 +41,7 @@ struct Ctx {
     int n_cu = 256;
     std::vector<Tenant> tenants;
     bool loaded = false;
+    bool ws_missing = false;                        // split-K workspace allocation failed at load
     // current plan (copied)
     std::vector<gacer_split> splits;
     std::vector<gacer_sync> syncs;

@@ -73,6 +73,7 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
     g.dtype = s.dtype = dt(t);
     g.alpha = 1.f;
     g.zb = g.zh = 1;
+    g.ksplit = 1; g.kb_per_slice = 1 << 28;
     g.act = s.act = (int)op.act;
     switch (op.kind) {
     case GACER_CONV2D:
@@ -96,6 +97,8 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
         g.y_row = out.c;
         g.m_lo = b_lo * q_out * g.Ho * g.Wo; g.m_hi = b_hi * q_out * g.Ho * g.Wo;
         g.n_lo = c_lo; g.n_hi = c_hi;
+        g.ksplit = t.ksplit[oi]; g.kb_per_slice = t.kb_per_slice[oi];
+        g.ws = t.ws;
         break;
     }
     case GACER_BGEMM_QK: {
@@ -257,6 +260,58 @@ static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, cons
     return GACER_OK;
 }
 
+// Split-K decision, from the operator's UNSPLIT shape only (so every chunk of it adds in the same order):
+// when 64x64 tiles alone would leave most compute units idle, cut K into up to 16 slices of at least four
+// 64-byte blocks, aiming at about two workgroups per compute unit.
+static void decide_split(int64_t M, int64_t N, int K, gacer_dtype dtype, int *S, int *kbps)
+{
+    const int bk = dtype == GACER_BF16 ? 32 : 16;
+    const int nkb = (K + bk - 1) / bk;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    int64_t s = 1;
+    if (tiles < 256) s = std::min<int64_t>(std::min<int64_t>((512 + tiles - 1) / tiles, 16), nkb / 4);
+    if (s < 1) s = 1;
+    int per = (int)((nkb + s - 1) / s);
+    per += per & 1;
+    *kbps = s == 1 ? (1 << 28) : per;
+    *S = s == 1 ? 1 : (nkb + per - 1) / per;
+}
+
+static void release_workspaces(std::vector<Tenant> &ts)
+{
+    for (Tenant &t : ts) {
+        if (t.ws) (void)hipFree(t.ws);
+        t.ws = nullptr;
+    }
+}
+
+// Sizes the per-tenant split-K workspace and tries to allocate it.  Without a usable device the pointers
+// stay null and gacer_run reports the failure; descriptor-only use (validation, search) still works.
+static void plan_workspaces(Ctx *c, std::vector<Tenant> &ts)
+{
+    for (Tenant &t : ts) {
+        t.ksplit.assign(t.ops.size(), 1);
+        t.kb_per_slice.assign(t.ops.size(), 1 << 28);
+        t.ws_floats = 0;
+        for (size_t i = 0; i < t.ops.size(); ++i) {
+            const gacer_op &op = t.ops[i];
+            if (op.kind != GACER_CONV2D && op.kind != GACER_GEMM) continue;
+            const gacer_tensor &in = t.tensors[op.in0], &out = t.tensors[op.out];
+            const int64_t M = out.n * out.h * out.w, N = out.c;
+            const int K = op.kind == GACER_GEMM ? op.cin : (int)in.c * op.kh * op.kw;
+            decide_split(M, N, K, t.dtype, &t.ksplit[i], &t.kb_per_slice[i]);
+            if (t.ksplit[i] > 1) t.ws_floats = std::max<size_t>(t.ws_floats, (size_t)t.ksplit[i] * M * N);
+        }
+        if (t.ws_floats) {
+            if (hipMalloc((void **)&t.ws, t.ws_floats * sizeof(float)) != hipSuccess) {
+                (void)hipGetLastError();
+                t.ws = nullptr;
+                c->ws_missing = true;
+            }
+        }
+    }
+}
+
 static void expand_plain(Ctx *c)
 {
     c->plain_exec.assign(c->tenants.size(), {});
@@ -391,6 +446,7 @@ void gacer_destroy(gacer_ctx *c)
 {
     if (!c) return;
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    release_workspaces(c->tenants);
     for (hipEvent_t e : c->sync_events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->join_events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->t_start) (void)hipEventDestroy(e);
@@ -437,6 +493,9 @@ gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n
         T.stream = (hipStream_t)t.stream;
     }
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    release_workspaces(c->tenants);
+    c->ws_missing = false;
+    plan_workspaces(c, fresh);
     c->tenants.swap(fresh);
     c->loaded = true;
     expand_plain(c);
@@ -517,6 +576,7 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
     if (!c) return GACER_EINVAL;
     if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_run before gacer_load_tenants");
     if (mode < 0 || mode > 2 || rounds < 1) return fail(c, GACER_EINVAL, "bad mode or rounds");
+    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
     const int NT = (int)c->tenants.size();
     while ((int)c->t_start.size() < rounds) {
         hipEvent_t a, b;
@@ -566,6 +626,116 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
     HIPCHK(c, hipGetLastError());
     if (ms_per_round)
         for (int r = 0; r < rounds; ++r) HIPCHK(c, hipEventElapsedTime(&ms_per_round[r], c->t_start[r], c->t_end[r]));
+    return GACER_OK;
+}
+
+// Algorithmic work of one launch (sub-range only).
+static void launch_work(const Launch &l, double *flops, double *bytes)
+{
+    *flops = 0;
+    if (l.kind == LK_IGEMM) {
+        const GemmArgs &g = l.g;
+        const double esz = g.dtype == DT_BF16 ? 2.0 : 4.0;
+        const double z = (double)g.zb * g.zh, M = g.m_hi - g.m_lo, N = g.n_hi - g.n_lo;
+        *flops = 2.0 * M * N * g.K * z;
+        const double rows_in = M / ((double)g.Ho * g.Wo) * g.H * g.W;      // input positions of the launched images
+        *bytes = (rows_in * g.Cin + N * g.K + M * N * (g.res ? 2.0 : 1.0)) * esz * z + (g.bias ? N * 4.0 : 0.0);
+        return;
+    }
+    const StreamArgs &s = l.s;
+    const double esz = s.dtype == DT_BF16 ? 2.0 : 4.0;
+    double items, C;
+    if (l.kind == LK_LAYERNORM || l.kind == LK_SOFTMAX) { items = (double)(s.n_hi - s.n_lo) * s.rows_per_item; C = s.C; }
+    else { items = (double)(s.n_hi - s.n_lo); C = s.c_hi - s.c_lo; }
+    double in_pos = (double)s.H * s.W, out_pos = (double)s.Ho * s.Wo;
+    if (l.kind == LK_LAYERNORM || l.kind == LK_SOFTMAX) in_pos = out_pos = 1;
+    if (l.kind == LK_GAVGPOOL) out_pos = 1;
+    double b = items * C * (in_pos + out_pos) * esz;
+    if (s.x2) b += items * C * in_pos * esz;
+    if (s.res) b += items * C * out_pos * esz;
+    if (l.kind == LK_DWCONV) b += C * s.k * s.k * esz;
+    *bytes = b;
+}
+
+gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_stat *out, size_t cap, size_t *n_out)
+{
+    if (!c || !n_out) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_trace_run before gacer_load_tenants");
+    if (mode < 0 || mode > 2 || rounds < 1) return fail(c, GACER_EINVAL, "bad mode or rounds");
+    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
+    const int NT = (int)c->tenants.size();
+    const bool plan = (mode == GACER_MODE_PLAN);
+    const auto &ex = plan ? c->plan_exec : c->plain_exec;
+    std::vector<std::pair<int, int>> order;
+    if (mode == GACER_MODE_SEQUENTIAL) {
+        for (int t = 0; t < NT; ++t)
+            for (int i = 0; i < (int)c->tenants[t].ops.size(); ++i) order.push_back({t, i});
+    } else order = plan ? c->plan_order : c->par_order;
+    size_t total = 0;
+    for (const auto &to : order) total += ex[to.first][to.second].chunks.size();
+    *n_out = total;
+    if (cap == 0 || !out) return GACER_OK;
+    if (cap < total) return fail(c, GACER_EINVAL, "trace buffer too small (%zu rows needed)", total);
+    while (c->sync_events.size() < c->n_sync_events) {
+        hipEvent_t ev;
+        HIPCHK(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        c->sync_events.push_back(ev);
+    }
+    while ((int)c->join_events.size() < NT) {
+        hipEvent_t e;
+        HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        c->join_events.push_back(e);
+    }
+    std::vector<hipEvent_t> ev(2 * total * rounds);
+    for (hipEvent_t &e : ev) HIPCHK(c, hipEventCreate(&e));
+    hipEvent_t fork;
+    HIPCHK(c, hipEventCreateWithFlags(&fork, hipEventDisableTiming));
+    hipStream_t s0 = c->tenants[0].stream;
+    size_t k = 0;
+    for (int r = 0; r < rounds; ++r) {
+        if (mode != GACER_MODE_SEQUENTIAL) {
+            HIPCHK(c, hipEventRecord(fork, s0));
+            for (int t = 1; t < NT; ++t)
+                if (c->tenants[t].stream != s0) HIPCHK(c, hipStreamWaitEvent(c->tenants[t].stream, fork, 0));
+        }
+        size_t row = 0;
+        for (const auto &to : order) {
+            const OpExec &e = ex[to.first][to.second];
+            hipStream_t s = mode == GACER_MODE_SEQUENTIAL ? s0 : c->tenants[to.first].stream;
+            if (plan)
+                for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
+            for (size_t j = 0; j < e.chunks.size(); ++j) {
+                HIPCHK(c, hipEventRecord(ev[k++], s));
+                const LaunchInfo li = enqueue(e.chunks[j], s, false);
+                HIPCHK(c, hipEventRecord(ev[k++], s));
+                if (r == 0) {
+                    gacer_launch_stat &st = out[row];
+                    st.tenant = to.first; st.op = to.second; st.chunk = (int)j; st.ms = 0.f; st.workgroups = li.workgroups;
+                    launch_work(e.chunks[j], &st.flops, &st.bytes);
+                    std::snprintf(st.kernel, sizeof st.kernel, "%s", li.kernel);
+                }
+                ++row;
+            }
+            if (plan && e.record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.record], s));
+        }
+        if (mode != GACER_MODE_SEQUENTIAL)
+            for (int t = 1; t < NT; ++t)
+                if (c->tenants[t].stream != s0) {
+                    HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
+                    HIPCHK(c, hipStreamWaitEvent(s0, c->join_events[t], 0));
+                }
+    }
+    HIPCHK(c, hipStreamSynchronize(s0));
+    HIPCHK(c, hipGetLastError());
+    for (int r = 0; r < rounds; ++r)
+        for (size_t row = 0; row < total; ++row) {
+            float ms = 0.f;
+            const size_t b = 2 * ((size_t)r * total + row);
+            HIPCHK(c, hipEventElapsedTime(&ms, ev[b], ev[b + 1]));
+            out[row].ms += ms / (float)rounds;
+        }
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    (void)hipEventDestroy(fork);
     return GACER_OK;
 }
 

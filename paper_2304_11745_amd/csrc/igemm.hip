@@ -2,18 +2,20 @@
 //
 //   Y[m][n] = act( alpha * sum_k A[m][k] * B[n][k] + bias[n] + res[m][n] )
 //
-// One 256-thread workgroup (4 wavefronts of 64) owns a BM x BN output tile and walks K in
-// blocks of 64 bytes per row (16 floats / 32 bfloat16).  Global tiles are prefetched into
-// registers, staged through double-buffered LDS and consumed by 32x32 MFMA tiles:
+// One 256-thread workgroup (4 wavefronts of 64) owns a BM x BN output tile and walks K in blocks of
+// KV 16-byte vectors per row.  Global tiles are prefetched two blocks ahead into registers, staged
+// through double-buffered LDS and consumed by 32x32 MFMA tiles:
 //   fp32 : v_mfma_f32_32x32x2_f32   (true fp32 multiply-accumulate)
 //   bf16 : v_mfma_f32_32x32x16_bf16 (fp32 accumulate)
 //
-// Bit-exactness across decompositions: each output element is one accumulator chain that
-// walks k in a fixed order that depends only on K -- never on the tile shape, on the position
-// of the element inside a tile, or on the launched sub-range.  K tails are zero filled.  A
-// chunk launch (Eq. 5: part of the batch; or part of the output channels) therefore produces
-// exactly the bits the unsplit launch produces.
+// Bit-exactness across decompositions: each output element is the ordered sum of `ksplit` slice
+// accumulators; a slice accumulator is one MFMA chain that walks its k range in ascending groups of
+// 32 bytes.  ksplit and the slice length are fixed per operator from its unsplit shape, so the order
+// of additions never depends on the tile shape, on the position of the element inside a tile, or on
+// the launched sub-range.  K tails are zero filled.  A chunk launch (Eq. 5: part of the batch, or part
+// of the output channels) therefore produces exactly the bits the unsplit launch produces.
 #include <hip/hip_runtime.h>
+#include <string>
 #include "kernels.h"
 
 namespace gacer {
@@ -21,8 +23,8 @@ namespace gacer {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-static constexpr int ROWB = 80;       // LDS bytes per tile row: 64 data + 16 pad
 static constexpr int THREADS = 256;
+enum { LOAD_VEC = 0, LOAD_GATHER = 1, LOAD_BT = 2 };
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)
@@ -55,15 +57,26 @@ __device__ __forceinline__ void split_k(int k, int Cin, int kw, bool one_tap, in
     s = tap - r * kw;
 }
 
-template <int DT, int BM, int BN, int WM, int WN, bool VEC_OK>
+template <typename T> __device__ __forceinline__ void store_out(T *y, int64_t o, float v);
+template <> __device__ __forceinline__ void store_out<float>(float *y, int64_t o, float v) { y[o] = v; }
+template <> __device__ __forceinline__ void store_out<unsigned short>(unsigned short *y, int64_t o, float v) { y[o] = f32_to_bf16(v); }
+__device__ __forceinline__ float load_in(const float *p, int64_t o) { return p[o]; }
+__device__ __forceinline__ float load_in(const unsigned short *p, int64_t o) { return bf16_to_f32(p[o]); }
+
+template <int DT, int BM, int BN, int WM, int WN, int KV, int LOAD>
 __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 {
     typedef typename El<DT>::T T;
     constexpr int VEC = El<DT>::VEC;            // elements per 16-byte vector
-    constexpr int BK = 4 * VEC;                 // elements per K block (64 bytes)
+    constexpr int BK = KV * VEC;                // elements per K block
+    constexpr int ROWB = KV * 16 + 16;          // LDS bytes per tile row (16 bytes of padding)
+    constexpr int RPP = THREADS / KV;           // tile rows covered by one pass of all threads
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int AV = (BM * 4 + THREADS - 1) / THREADS;   // 16-byte vectors per thread, A tile
-    constexpr int BV = (BN * 4 + THREADS - 1) / THREADS;
+    constexpr int AV = (BM + RPP - 1) / RPP;    // 16-byte vectors per thread, A tile
+    constexpr int BV = (BN + RPP - 1) / RPP;
+    constexpr int NV = BN / VEC;                // LOAD_BT: n-vectors per k row of the B tile
+    constexpr int BTV = (BK * NV + THREADS - 1) / THREADS;
+    constexpr int BREG = LOAD == LOAD_BT ? BTV : BV;
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
 
     __shared__ __align__(16) unsigned char smem[2 * (BM + BN) * ROWB];
@@ -83,7 +96,8 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 
     const bool one_tap = (a.kh == 1 && a.kw == 1);
     const int HoWo = a.Ho * a.Wo;
-    const int vcol = tid & 3;                   // which 16-byte vector of the row this thread moves
+    const int vcol = tid % KV;                  // which 16-byte vector of the row this thread moves
+    const int vrow = tid / KV;
 
     // ---- per-thread A rows: decode output position once ----
     int64_t a_img[AV];
@@ -91,7 +105,7 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     bool a_ok[AV];
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
-        const int row = (tid >> 2) + i * 64;
+        const int row = vrow + i * RPP;
         const int m = m0 + row;
         a_ok[i] = (row < BM) && (m < a.m_hi);
         const int mm = a_ok[i] ? m : a.m_lo;
@@ -102,11 +116,11 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         a_iw0[i] = ow * a.stride - a.pad;
     }
 
-    uint4 ra[AV], rb[BV];
+    uint4 ra[2][AV], rb[2][BREG];
 
-    auto load_global = [&](int kb) {
+    auto load_global = [&](int kb, uint4 *pa, uint4 *pb) {
         const int kv = kb * BK + vcol * VEC;    // first k of this thread's vector
-        if constexpr (VEC_OK) {
+        if constexpr (LOAD != LOAD_GATHER) {
             int r, s, ci;
             split_k(kv, a.Cin, a.kw, one_tap, r, s, ci);
             const bool k_ok = kv < a.K;
@@ -114,15 +128,27 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
             for (int i = 0; i < AV; ++i) {
                 const int ih = a_ih0[i] + r, iw = a_iw0[i] + s;
                 const bool ok = a_ok[i] && k_ok && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-                ra[i] = make_uint4(0, 0, 0, 0);
-                if (ok) ra[i] = *(const uint4 *)(xg + a_img[i] + ((int64_t)ih * a.W + iw) * a.x_pix + ci);
+                pa[i] = make_uint4(0, 0, 0, 0);
+                if (ok) pa[i] = *(const uint4 *)(xg + a_img[i] + ((int64_t)ih * a.W + iw) * a.x_pix + ci);
             }
+            if constexpr (LOAD == LOAD_VEC) {
 #pragma unroll
-            for (int i = 0; i < BV; ++i) {
-                const int row = (tid >> 2) + i * 64;
-                const int n = n0 + row;
-                rb[i] = make_uint4(0, 0, 0, 0);
-                if (row < BN && n < a.n_hi && k_ok) rb[i] = *(const uint4 *)(wg + (int64_t)n * a.w_row + kv);
+                for (int i = 0; i < BV; ++i) {
+                    const int row = vrow + i * RPP;
+                    const int n = n0 + row;
+                    pb[i] = make_uint4(0, 0, 0, 0);
+                    if (row < BN && n < a.n_hi && k_ok) pb[i] = *(const uint4 *)(wg + (int64_t)n * a.w_row + kv);
+                }
+            } else {
+                // B stored [k][n]: vectors run along n
+#pragma unroll
+                for (int i = 0; i < BTV; ++i) {
+                    const int idx = tid + i * THREADS;
+                    const int kk = idx / NV, nv = idx - kk * NV;
+                    const int k = kb * BK + kk, n = n0 + nv * VEC;
+                    pb[i] = make_uint4(0, 0, 0, 0);
+                    if (idx < BK * NV && k < a.K && n < a.n_hi) pb[i] = *(const uint4 *)(wg + (int64_t)k * a.w_row + n);
+                }
             }
         } else {
             // element-wise gather: any Cin, any alignment (stem convolutions, ragged K)
@@ -141,28 +167,41 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                 }
 #pragma unroll
                 for (int i = 0; i < BV; ++i) {
-                    const int row = (tid >> 2) + i * 64;
+                    const int row = vrow + i * RPP;
                     const int n = n0 + row;
                     eb[i][e] = (row < BN && n < a.n_hi && k_ok) ? wg[(int64_t)n * a.w_row + k] : (T)0;
                 }
             }
 #pragma unroll
-            for (int i = 0; i < AV; ++i) ra[i] = *(const uint4 *)ea[i];
+            for (int i = 0; i < AV; ++i) pa[i] = *(const uint4 *)ea[i];
 #pragma unroll
-            for (int i = 0; i < BV; ++i) rb[i] = *(const uint4 *)eb[i];
+            for (int i = 0; i < BV; ++i) pb[i] = *(const uint4 *)eb[i];
         }
     };
 
-    auto store_lds = [&](int buf) {
+    auto store_lds = [&](int buf, const uint4 *pa, const uint4 *pb) {
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
-            const int row = (tid >> 2) + i * 64;
-            if (row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = ra[i];
+            const int row = vrow + i * RPP;
+            if (row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = pa[i];
         }
+        if constexpr (LOAD != LOAD_BT) {
 #pragma unroll
-        for (int i = 0; i < BV; ++i) {
-            const int row = (tid >> 2) + i * 64;
-            if (row < BN) *(uint4 *)(Bs + (buf * BN + row) * ROWB + vcol * 16) = rb[i];
+            for (int i = 0; i < BV; ++i) {
+                const int row = vrow + i * RPP;
+                if (row < BN) *(uint4 *)(Bs + (buf * BN + row) * ROWB + vcol * 16) = pb[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < BTV; ++i) {
+                const int idx = tid + i * THREADS;
+                const int kk = idx / NV, nv = idx - kk * NV;
+                if (idx < BK * NV) {
+                    const T *e = (const T *)&pb[i];
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) *(T *)(Bs + (buf * BN + nv * VEC + q) * ROWB + kk * (int)sizeof(T)) = e[q];
+                }
+            }
         }
     };
 
@@ -174,18 +213,11 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int nkb = (a.K + BK - 1) / BK;
     const int lrow = lane & 31, lhalf = lane >> 5;
 
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-
-    for (int kb = 0; kb < nkb; ++kb) {
-        const int buf = kb & 1;
-        if (kb + 1 < nkb) load_global(kb + 1);
+    auto compute = [&](int buf) {
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
+        for (int ks = 0; ks < KV / 2; ++ks) {
             uint4 fa[TM], fb[TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -213,11 +245,53 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                         }
             }
         }
-        if (kb + 1 < nkb) store_lds(buf ^ 1);
+    };
+
+    // K range of this slice, in blocks of BK (kb_per_slice counts 64-byte blocks)
+    const int nkb_all = (a.K + BK - 1) / BK;
+    const int per = a.kb_per_slice / (KV / 4);
+    const int slice = blockIdx.y;
+    const int kb_lo = slice * per;
+    const int nkb = min(nkb_all, kb_lo + per);
+
+    // Pipeline: LDS buffer p holds block kb, register set p^1 holds block kb+1 (in flight), and the loads
+    // of block kb+2 are issued into register set p before the MFMAs of block kb start.
+    load_global(kb_lo, ra[0], rb[0]);
+    store_lds(0, ra[0], rb[0]);
+    if (kb_lo + 1 < nkb) load_global(kb_lo + 1, ra[1], rb[1]);
+    __syncthreads();
+    for (int kb = kb_lo; kb < nkb; kb += 2) {
+        if (kb + 2 < nkb) load_global(kb + 2, ra[0], rb[0]);
+        compute(0);
+        if (kb + 1 < nkb) store_lds(1, ra[1], rb[1]);
         __syncthreads();
+        if (kb + 1 < nkb) {
+            if (kb + 3 < nkb) load_global(kb + 3, ra[1], rb[1]);
+            compute(1);
+            if (kb + 2 < nkb) store_lds(0, ra[0], rb[0]);
+            __syncthreads();
+        }
     }
 
-    // ---- epilogue: 32x32 accumulator layout: element e -> row (e/4)*8 + (lane/32)*4 + e%4, col lane%32 ----
+    // ---- 32x32 accumulator layout: element e -> row (e/4)*8 + (lane/32)*4 + e%4, col lane%32 ----
+    if (a.ksplit > 1) {
+        // park the slice accumulator; splitk_finish adds the slices in order and applies the epilogue
+        const int Nl = a.n_hi - a.n_lo;
+        float *ws = a.ws + (int64_t)slice * (a.m_hi - a.m_lo) * Nl;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * (BN / WN) + j * 32 + lrow;
+            if (n >= a.n_hi) continue;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int m = m0 + wm * (BM / WM) + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+                    if (m < a.m_hi) ws[(int64_t)(m - a.m_lo) * Nl + (n - a.n_lo)] = acc[i][j][e];
+                }
+        }
+        return;
+    }
     T *yg = (T *)a.y + y_off;
     const T *rg = a.res ? (const T *)a.res + y_off : nullptr;
 #pragma unroll
@@ -233,173 +307,61 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                 if (m >= a.m_hi) continue;
                 const int64_t o = (int64_t)m * a.y_row + n;
                 float v = __fmaf_rn(acc[i][j][e], a.alpha, bias);
-                if constexpr (DT == DT_BF16) {
-                    if (rg) v = __fadd_rn(v, bf16_to_f32(rg[o]));
-                    yg[o] = f32_to_bf16(act_apply(v, a.act));
-                } else {
-                    if (rg) v = __fadd_rn(v, rg[o]);
-                    yg[o] = act_apply(v, a.act);
-                }
+                if (rg) v = __fadd_rn(v, load_in(rg, o));
+                store_out<T>(yg, o, act_apply(v, a.act));
             }
     }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Attention context (b_trans): B is stored [k][n] (values V: key position major, head channel
-// minor).  Same accumulation order as above; only the global->LDS staging of B differs: vectors
-// run along n and are scattered into the [n][k] LDS tile.
-// ------------------------------------------------------------------------------------------------
-template <int DT, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(THREADS) void igemm_bt_kernel(GemmArgs a)
+// Second pass of a split-K operator: out = act(alpha * (s0 + s1 + ... ) + bias + res), slices added in
+// ascending order.  One thread per output element of the launched sub-range, coalesced along n.
+template <typename T>
+__global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
 {
-    typedef typename El<DT>::T T;
-    constexpr int VEC = El<DT>::VEC;
-    constexpr int BK = 4 * VEC;
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int AV = (BM * 4 + THREADS - 1) / THREADS;
-    constexpr int NV = BN / VEC;                           // n-vectors per k row of the B tile
-    constexpr int BV = (BK * NV + THREADS - 1) / THREADS;
-
-    __shared__ __align__(16) unsigned char smem[2 * (BM + BN) * ROWB];
-    unsigned char *As = smem, *Bs = smem + 2 * BM * ROWB;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
-    const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
-    const int tile_n = blockIdx.x % tiles_n, tile_m = blockIdx.x / tiles_n;
-    const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
-    const int z = blockIdx.z;
-    const int zb = a.z_lo + z / a.zh, zh = z % a.zh;
-    const T *xg = (const T *)a.x + zb * a.x_zb + zh * a.x_zh;
-    const T *wg = (const T *)a.w + zb * a.w_zb + zh * a.w_zh;
-    const int64_t y_off = zb * a.y_zb + zh * a.y_zh;
-    const int vcol = tid & 3;
-
-    uint4 ra[AV], rb[BV];
-    auto load_global = [&](int kb) {
-        const int kv = kb * BK + vcol * VEC;
-#pragma unroll
-        for (int i = 0; i < AV; ++i) {
-            const int row = (tid >> 2) + i * 64;
-            const int m = m0 + row;
-            ra[i] = make_uint4(0, 0, 0, 0);
-            if (row < BM && m < a.m_hi && kv < a.K) ra[i] = *(const uint4 *)(xg + (int64_t)m * a.x_pix + kv);
-        }
-#pragma unroll
-        for (int i = 0; i < BV; ++i) {
-            const int idx = tid + i * THREADS;
-            const int kk = idx / NV, nv = idx - kk * NV;
-            const int k = kb * BK + kk, n = n0 + nv * VEC;
-            rb[i] = make_uint4(0, 0, 0, 0);
-            if (idx < BK * NV && k < a.K && n < a.n_hi) rb[i] = *(const uint4 *)(wg + (int64_t)k * a.w_row + n);
-        }
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < AV; ++i) {
-            const int row = (tid >> 2) + i * 64;
-            if (row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < BV; ++i) {
-            const int idx = tid + i * THREADS;
-            const int kk = idx / NV, nv = idx - kk * NV;
-            if (idx < BK * NV) {
-                const T *e = (const T *)&rb[i];
-#pragma unroll
-                for (int q = 0; q < VEC; ++q)
-                    *(T *)(Bs + (buf * BN + nv * VEC + q) * ROWB + kk * (int)sizeof(T)) = e[q];
-            }
-        }
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    const int nkb = (a.K + BK - 1) / BK;
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kb = 0; kb < nkb; ++kb) {
-        const int buf = kb & 1;
-        if (kb + 1 < nkb) load_global(kb + 1);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            uint4 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[i] = *(const uint4 *)(As + (buf * BM + wm * (BM / WM) + i * 32 + lrow) * ROWB + ks * 32 + lhalf * 16);
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                fb[j] = *(const uint4 *)(Bs + (buf * BN + wn * (BN / WN) + j * 32 + lrow) * ROWB + ks * 32 + lhalf * 16);
-            if constexpr (DT == DT_BF16) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                            __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const float av = __uint_as_float(e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w);
-                            const float bv = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-                        }
-            }
-        }
-        if (kb + 1 < nkb) store_lds(buf ^ 1);
-        __syncthreads();
-    }
-    T *yg = (T *)a.y + y_off;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * (BN / WN) + j * 32 + lrow;
-        if (n >= a.n_hi) continue;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * (BM / WM) + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-                if (m >= a.m_hi) continue;
-                const int64_t o = (int64_t)m * a.y_row + n;
-                const float v = __fmul_rn(acc[i][j][e], a.alpha);
-                if constexpr (DT == DT_BF16) yg[o] = f32_to_bf16(v);
-                else yg[o] = v;
-            }
-    }
+    const int Nl = a.n_hi - a.n_lo;
+    const int64_t total = (int64_t)(a.m_hi - a.m_lo) * Nl;
+    const int64_t idx = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+    if (idx >= total) return;
+    const int m = a.m_lo + (int)(idx / Nl), n = a.n_lo + (int)(idx % Nl);
+    float v = a.ws[idx];
+    for (int q = 1; q < a.ksplit; ++q) v = __fadd_rn(v, a.ws[q * total + idx]);
+    v = __fmaf_rn(v, a.alpha, a.bias ? a.bias[n] : 0.f);
+    const int64_t o = (int64_t)m * a.y_row + n;
+    if (a.res) v = __fadd_rn(v, load_in((const T *)a.res, o));
+    store_out<T>((T *)a.y, o, act_apply(v, a.act));
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int DT, int BM, int BN, int WM, int WN>
+template <int DT, int BM, int BN, int WM, int WN, int KV>
 static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok)
 {
+    typedef typename El<DT>::T T;
+    constexpr int ROWB = KV * 16 + 16;
     const int tiles_m = (a.m_hi - a.m_lo + BM - 1) / BM, tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
     const int z = a.zb * a.zh;
+    const int ks = a.b_trans ? 1 : a.ksplit;
     LaunchInfo li;
-    li.workgroups = tiles_m * tiles_n * z;
+    li.workgroups = tiles_m * tiles_n * z * ks;
     li.threads = THREADS;
     li.lds_bytes = 2 * (BM + BN) * ROWB;
     const int by_lds = (160 * 1024) / li.lds_bytes;
-    li.wg_per_cu = by_lds < 8 ? by_lds : 8;     // 8 wave slots per SIMD, 1 wave of each WG per SIMD
+    li.wg_per_cu = by_lds < 8 ? by_lds : 8;     // 8 wave slots per SIMD, one wave of each workgroup per SIMD
+    static const std::string shape = std::string(DT == DT_BF16 ? "bf16_" : "f32_") + std::to_string(BM) + "x" + std::to_string(BN) +
+                                     "x" + std::to_string(KV * El<DT>::VEC);
+    static const std::string n_vec = "igemm_" + shape, n_bt = "igemm_bt_" + shape, n_gather = "igemm_gather_" + shape;
+    li.kernel = a.b_trans ? n_bt.c_str() : (vec_ok ? n_vec.c_str() : n_gather.c_str());
     if (dry || li.workgroups == 0) return li;
-    dim3 grid(tiles_m * tiles_n, 1, z), block(THREADS);
+    dim3 grid(tiles_m * tiles_n, ks, z), block(THREADS);
     if (a.b_trans)
-        hipLaunchKernelGGL((igemm_bt_kernel<DT, BM, BN, WM, WN>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, a);
     else if (vec_ok)
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, true>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
     else
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, false>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, a);
+    if (ks > 1) {
+        const int64_t total = (int64_t)(a.m_hi - a.m_lo) * (a.n_hi - a.n_lo);
+        hipLaunchKernelGGL((splitk_finish<T>), dim3((unsigned)((total + THREADS - 1) / THREADS)), block, 0, s, a);
+    }
     return li;
 }
 
@@ -407,31 +369,33 @@ template <int DT>
 static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry)
 {
     constexpr int VEC = El<DT>::VEC;
-    const int esz = (int)sizeof(typename El<DT>::T);
-    bool vec_ok = (a.Cin % VEC == 0) && (a.x_pix % VEC == 0) && (a.x_img % VEC == 0) && (a.w_row % VEC == 0) &&
-                  (a.x_zb % VEC == 0) && (a.x_zh % VEC == 0) && (a.w_zb % VEC == 0) && (a.w_zh % VEC == 0) &&
-                  (((uintptr_t)a.x) % 16 == 0) && (((uintptr_t)a.w) % 16 == 0);
-    (void)esz;
+    const bool vec_ok = (a.Cin % VEC == 0) && (a.x_pix % VEC == 0) && (a.x_img % VEC == 0) && (a.w_row % VEC == 0) &&
+                        (a.x_zb % VEC == 0) && (a.x_zh % VEC == 0) && (a.w_zb % VEC == 0) && (a.w_zh % VEC == 0) &&
+                        (((uintptr_t)a.x) % 16 == 0) && (((uintptr_t)a.w) % 16 == 0);
     const int M = a.m_hi - a.m_lo, N = a.n_hi - a.n_lo;
-    const int64_t z = (int64_t)a.zb * a.zh;
-    // Tile choice is free (it never changes the bits): widest N tile that wastes the least padding,
-    // then the tallest M tile that still yields about two workgroups per compute unit.
+    const int64_t z = (int64_t)a.zb * a.zh * (a.b_trans ? 1 : a.ksplit);
+    // Tile choice is free (it never changes the bits): narrowest N padding first, then the largest
+    // tile that still gives every compute unit about two workgroups.
     auto waste = [&](int bn) { return (double)((N + bn - 1) / bn * bn) / (double)N; };
     int bn = 128;
     if (waste(64) < waste(bn) - 1e-9) bn = 64;
     if (waste(32) < waste(bn) - 1e-9) bn = 32;
     auto wgs = [&](int bm, int bnn) { return (int64_t)((M + bm - 1) / bm) * ((N + bnn - 1) / bnn) * z; };
     const int64_t want = 512;
-    if (bn == 128) {
-        if (wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2>(a, s, dry, vec_ok);
-        if (wgs(128, 64) >= want || M > 64) return go<DT, 128, 64, 2, 2>(a, s, dry, vec_ok);
-        return go<DT, 64, 64, 2, 2>(a, s, dry, vec_ok);
+    if (a.b_trans || a.K <= 16 * VEC) {          // short K: 64-byte blocks
+        if (bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 4>(a, s, dry, vec_ok);
+        if (bn >= 64) {
+            if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 4>(a, s, dry, vec_ok);
+            return go<DT, 64, 64, 2, 2, 4>(a, s, dry, vec_ok);
+        }
+        return go<DT, 128, 32, 4, 1, 4>(a, s, dry, vec_ok);
     }
-    if (bn == 64) {
-        if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2>(a, s, dry, vec_ok);
-        return go<DT, 64, 64, 2, 2>(a, s, dry, vec_ok);
+    if (bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 8>(a, s, dry, vec_ok);
+    if (bn >= 64) {
+        if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 8>(a, s, dry, vec_ok);
+        return go<DT, 64, 64, 2, 2, 8>(a, s, dry, vec_ok);
     }
-    return go<DT, 128, 32, 4, 1>(a, s, dry, vec_ok);
+    return go<DT, 128, 32, 4, 1, 8>(a, s, dry, vec_ok);
 }
 
 LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry)

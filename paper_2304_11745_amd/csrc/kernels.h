@@ -39,6 +39,12 @@ struct GemmArgs {
     int zb, zh;
     int64_t x_zb, x_zh, w_zb, w_zh, y_zb, y_zh;
     int z_lo;                  // first zb index of the sub-range (zb counts problems launched)
+    // Split-K: the K blocks are cut into `ksplit` slices of `kb_per_slice` 64-byte blocks.  Each slice is
+    // accumulated by its own workgroup into `ws` ([slice][row][col] floats over the launched sub-range); a
+    // second kernel adds the slices in order 0,1,2,... and applies the epilogue.  Both numbers are fixed per
+    // operator from its unsplit shape, so every decomposition adds in the same order.
+    int ksplit, kb_per_slice;
+    float *ws;
 };
 
 // Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).
@@ -55,7 +61,7 @@ struct StreamArgs {
     int64_t rows_per_item;     // row operators: rows (positions) per batch item
 };
 
-struct LaunchInfo { int workgroups; int threads; int lds_bytes; int wg_per_cu; };
+struct LaunchInfo { int workgroups; int threads; int lds_bytes; int wg_per_cu; const char *kernel; };
 
 LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry);

@@ -214,9 +214,10 @@ static bool vec_ok(const StreamArgs &a)
            aligned16(a.x2) && aligned16(a.res) && aligned16(a.w);
 }
 
-static LaunchInfo info(int64_t wgs)
+static LaunchInfo info(int64_t wgs, const char *kernel)
 {
     LaunchInfo li;
+    li.kernel = kernel;
     li.workgroups = (int)wgs;
     li.threads = TPB;
     li.lds_bytes = 0;
@@ -224,44 +225,44 @@ static LaunchInfo info(int64_t wgs)
     return li;
 }
 
-#define GACER_DISPATCH_VEC(KERNEL)                                                                         \
+#define GACER_DISPATCH_VEC(KERNEL, NAME)                                                                        \
     if (a.dtype == DT_BF16) {                                                                              \
         if (vec_ok<unsigned short, 8>(a)) {                                                                \
             const int64_t g = (outs / 8 + TPB - 1) / TPB;                                                  \
             if (!dry && g) hipLaunchKernelGGL((KERNEL<unsigned short, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); \
-            return info(g);                                                                                \
+            return info(g, NAME);                                                                               \
         }                                                                                                  \
         const int64_t g = (outs + TPB - 1) / TPB;                                                          \
         if (!dry && g) hipLaunchKernelGGL((KERNEL<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);     \
-        return info(g);                                                                                    \
+        return info(g, NAME);                                                                                   \
     }                                                                                                      \
     if (vec_ok<float, 4>(a)) {                                                                             \
         const int64_t g = (outs / 4 + TPB - 1) / TPB;                                                      \
         if (!dry && g) hipLaunchKernelGGL((KERNEL<float, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
-        return info(g);                                                                                    \
+        return info(g, NAME);                                                                                   \
     }                                                                                                      \
     {                                                                                                      \
         const int64_t g = (outs + TPB - 1) / TPB;                                                          \
         if (!dry && g) hipLaunchKernelGGL((KERNEL<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
-        return info(g);                                                                                    \
+        return info(g, NAME);                                                                                   \
     }
 
 LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * (a.c_hi - a.c_lo);
-    GACER_DISPATCH_VEC(dwconv_kernel)
+    GACER_DISPATCH_VEC(dwconv_kernel, "dwconv")
 }
 
 LaunchInfo launch_maxpool(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * (a.c_hi - a.c_lo);
-    GACER_DISPATCH_VEC(maxpool_kernel)
+    GACER_DISPATCH_VEC(maxpool_kernel, "maxpool")
 }
 
 LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.H * a.W * (a.c_hi - a.c_lo);
-    GACER_DISPATCH_VEC(eltwise_kernel)
+    GACER_DISPATCH_VEC(eltwise_kernel, "eltwise")
 }
 
 LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry)
@@ -271,7 +272,7 @@ LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry)
         if (a.dtype == DT_BF16) hipLaunchKernelGGL((gavgpool_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
         else hipLaunchKernelGGL((gavgpool_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
     }
-    return info(g);
+    return info(g, "gavgpool");
 }
 
 LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry)
@@ -282,7 +283,7 @@ LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry)
         if (a.dtype == DT_BF16) hipLaunchKernelGGL((layernorm_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
         else hipLaunchKernelGGL((layernorm_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
     }
-    return info(g);
+    return info(g, "layernorm");
 }
 
 LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry)
@@ -293,7 +294,7 @@ LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry)
         if (a.dtype == DT_BF16) hipLaunchKernelGGL((softmax_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
         else hipLaunchKernelGGL((softmax_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
     }
-    return info(g);
+    return info(g, "softmax");
 }
 
 }  // namespace gacer

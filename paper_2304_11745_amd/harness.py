@@ -139,6 +139,15 @@ class Session:
         B.check(self.ctx, B.gacer_launch_count(self.ctx, mode, C.byref(n)))
         return n.value
 
+    def trace(self, mode=B.GACER_MODE_PLAN, rounds=3):
+        """Per-launch statistics of one round (see gacer_trace_run)."""
+        n = C.c_size_t()
+        B.check(self.ctx, B.gacer_trace_run(self.ctx, mode, rounds, None, 0, C.byref(n)))
+        rows = (B.gacer_launch_stat * n.value)()
+        B.check(self.ctx, B.gacer_trace_run(self.ctx, mode, rounds, rows, n.value, C.byref(n)))
+        return [dict(tenant=r.tenant, op=r.op, chunk=r.chunk, ms=r.ms, flops=r.flops, bytes=r.bytes,
+                     workgroups=r.workgroups, kernel=r.kernel.decode()) for r in rows]
+
     def tensor(self, ti, idx):
         """Tensor ``idx`` of tenant ``ti`` as float32 numpy in logical NCHW order."""
         return self.acts[ti][idx].float().permute(0, 3, 1, 2).contiguous().cpu().numpy()

@@ -1,0 +1,43 @@
+"""Full-size parity in the launch configuration bench.py times: configs[1] (ResNet-18 + MobileNetV2,
+fp32, batch 8 each, 224x224) against the oracle, and the split sweep 1/2/4 on batch and Cout
+bit-exact against the unsplit run."""
+import numpy as np
+import pytest
+
+import synth
+from parity import TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config2_full_size_vs_oracle_and_split_sweep():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import forward as F
+    from paper_2304_11745_amd import binding as B
+    from paper_2304_11745_amd import harness
+    tenants, data = synth.build_config(2)
+    sess = harness.Session(tenants, data)
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    base = [sess.output_bytes(i) for i in range(2)]
+    for i, (t, (x, p)) in enumerate(zip(tenants, data)):
+        ref = F.run_tenant(t, x, p)
+        e = rel_err(sess.output(i), ref)
+        print(f"{t.name} full size rel_err={e:.3e}", flush=True)
+        assert e <= TOL["f32"]
+    for axis in ("batch", "cout"):
+        for f in (1, 2, 4):
+            sess.set_plan(sess.uniform_splits(axis, f) if f > 1 else [], [])
+            sess.poison_outputs()
+            sess.run(B.GACER_MODE_PLAN, 1)
+            for i in range(2):
+                assert sess.output_bytes(i) == base[i], f"{axis} x{f}: tenant {i} not bit-identical"
+    # one tenant only, plus pointers
+    sess.set_plan(sess.uniform_splits("batch", 2, tenants=[0]), sess.edges_from_pointers([[5, 12], [10, 30]]))
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_PLAN, 2)
+    for i in range(2):
+        assert sess.output_bytes(i) == base[i]
+    sess.close()
