@@ -68,6 +68,7 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
     Launch l;
     std::memset(&l, 0, sizeof l);
     const int q_out = (int)(out.n / t.batch), q_in = (int)(in.n / t.batch);
+    const size_t esz = t.dtype == GACER_BF16 ? 2 : 4;
     GemmArgs &g = l.g;
     StreamArgs &s = l.s;
     g.dtype = s.dtype = dt(t);
@@ -93,6 +94,8 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
             g.x_pix = in.c; g.x_img = in.h * in.w * in.c;
         }
         g.K = g.kh * g.kw * g.Cin;
+        g.x_bytes = in.n * in.c * in.h * in.w * (int64_t)esz;
+        g.w_bytes = (int64_t)out.c * g.K * (int64_t)esz;
         g.w_row = g.K;
         g.y_row = out.c;
         g.m_lo = b_lo * q_out * g.Ho * g.Wo; g.m_hi = b_hi * q_out * g.Ho * g.Wo;
@@ -106,8 +109,9 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
         l.kind = LK_IGEMM;
         const int heads = op.groups, dh = op.cin, S = (int)in.h;
         const int64_t D = (int64_t)heads * dh;
-        const size_t esz = t.dtype == GACER_BF16 ? 2 : 4;
         g.x = in.dptr; g.w = (const char *)in.dptr + D * esz; g.y = out.dptr;
+        g.x_bytes = in.n * in.c * in.h * in.w * (int64_t)esz;
+        g.w_bytes = g.x_bytes - D * (int64_t)esz;
         g.H = S; g.W = 1; g.Cin = dh; g.Ho = S; g.Wo = 1; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
         g.K = dh; g.x_pix = 3 * D; g.x_img = 0; g.w_row = 3 * D; g.y_row = S;
         g.m_lo = 0; g.m_hi = S; g.n_lo = 0; g.n_hi = S;
@@ -123,8 +127,9 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
         const gacer_tensor &qkv = t.tensors[op.in1];
         const int heads = op.groups, dh = op.cout, S = (int)qkv.h;
         const int64_t D = (int64_t)heads * dh;
-        const size_t esz = t.dtype == GACER_BF16 ? 2 : 4;
         g.x = in.dptr; g.w = (const char *)qkv.dptr + 2 * D * esz; g.y = out.dptr;
+        g.x_bytes = in.n * in.c * in.h * in.w * (int64_t)esz;
+        g.w_bytes = qkv.n * qkv.c * qkv.h * qkv.w * (int64_t)esz - 2 * D * (int64_t)esz;
         g.H = S; g.W = 1; g.Cin = S; g.Ho = S; g.Wo = 1; g.kh = g.kw = 1; g.stride = 1; g.pad = 0;
         g.K = S; g.x_pix = S; g.x_img = 0; g.w_row = 3 * D; g.y_row = D;
         g.m_lo = 0; g.m_hi = S; g.n_lo = 0; g.n_hi = dh;
@@ -199,7 +204,7 @@ static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, cons
     case GACER_CONV2D:
     case GACER_DWCONV2D: {
         if (!op.w) return fail(c, GACER_EINVAL, "tenant %d op %d: null weights", ti, oi);
-        if (op.kh < 1 || op.kw < 1 || op.stride < 1 || op.pad < 0) return bad("bad kernel/stride/pad");
+        if (op.kh < 1 || op.kw < 1 || op.kh > 31 || op.kw > 31 || op.stride < 1 || op.pad < 0) return bad("bad kernel/stride/pad (kernel extent 1..31)");
         if (op.cin != in.c || op.cout != out.c || in.n != out.n) return bad("cin/cout/n do not match the tensors");
         if (out.h != (in.h + 2 * op.pad - op.kh) / op.stride + 1 || out.w != (in.w + 2 * op.pad - op.kw) / op.stride + 1)
             return bad("output extent does not match (h+2*pad-k)/stride+1");
@@ -473,7 +478,8 @@ gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n
             if (x.n < 1 || x.c < 1 || x.h < 1 || x.w < 1) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: non-positive extent", ti, i);
             if (!x.dptr) return fail(c, GACER_EINVAL, "tenant %d tensor %d: null device pointer", ti, i);
             if (((uintptr_t)x.dptr) % 16) return fail(c, GACER_EINVAL, "tenant %d tensor %d: device pointer not 16-byte aligned", ti, i);
-            if (x.n * x.c * x.h * x.w >= ((int64_t)1 << 31)) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: more than 2^31 elements", ti, i);
+            if (x.n * x.c * x.h * x.w * (t.dtype == GACER_BF16 ? 2 : 4) >= ((int64_t)1 << 31))
+                return fail(c, GACER_ESHAPE, "tenant %d tensor %d: 2 GiB or more", ti, i);
         }
         std::vector<char> written(t.n_tensors, 0);
         written[t.input] = 1;

@@ -24,7 +24,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 static constexpr int THREADS = 256;
-enum { LOAD_VEC = 0, LOAD_GATHER = 1, LOAD_BT = 2 };
+enum { LOAD_VEC = 0, LOAD_GATHER = 1, LOAD_BT = 2, LOAD_TAPS = 3 };
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)
@@ -35,11 +35,17 @@ __device__ __forceinline__ unsigned short f32_to_bf16(float f)
     return (unsigned short)(u >> 16);
 }
 
+// exact (erf) GELU; kept out of line so that the unrolled epilogues stay small
+__device__ __attribute__((noinline)) float gelu_erf(float v)
+{
+    return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
+}
+
 __device__ __forceinline__ float act_apply(float v, int act)
 {
     if (act == ACT_RELU) return v > 0.f ? v : 0.f;
     if (act == ACT_RELU6) return v < 0.f ? 0.f : (v > 6.f ? 6.f : v);
-    if (act == ACT_GELU) return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
+    if (act == ACT_GELU) return gelu_erf(v);
     return v;
 }
 
@@ -63,11 +69,44 @@ template <> __device__ __forceinline__ void store_out<unsigned short>(unsigned s
 __device__ __forceinline__ float load_in(const float *p, int64_t o) { return p[o]; }
 __device__ __forceinline__ float load_in(const unsigned short *p, int64_t o) { return bf16_to_f32(p[o]); }
 
+// Buffer descriptors let every global load be unconditional: a masked element gets an offset beyond the
+// descriptor's range and the hardware returns zero (zero padding of the image border, of the K tail and of
+// ragged tile edges), so the main loop has no branches and loads can stay in flight across MFMA blocks.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+static constexpr unsigned OOB = 0x80000000u;     // tensors are smaller than 2 GiB (checked when tenants load)
+
+// The descriptor must live in scalar registers: its inputs are wave-uniform by construction, which
+// readfirstlane makes visible to the compiler (integer divisions are otherwise computed per lane).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, int64_t bytes)
+{
+    int rec = bytes > 0x7FFFFFFF ? 0x7FFFFFFF : (bytes < 0 ? 0 : (int)bytes);
+    rec = __builtin_amdgcn_readfirstlane(rec);
+    const uint64_t u = (uint64_t)p;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)hi << 32) | lo), 0, rec, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4((unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w);
+}
+template <typename T> __device__ __forceinline__ T buf_load1(__amdgpu_buffer_rsrc_t r, unsigned off);
+template <> __device__ __forceinline__ float buf_load1<float>(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    return __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+template <> __device__ __forceinline__ unsigned short buf_load1<unsigned short>(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 0);
+}
+
 template <int DT, int BM, int BN, int WM, int WN, int KV, int LOAD>
 __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 {
     typedef typename El<DT>::T T;
     constexpr int VEC = El<DT>::VEC;            // elements per 16-byte vector
+    constexpr int ESZ = (int)sizeof(T);
     constexpr int BK = KV * VEC;                // elements per K block
     constexpr int ROWB = KV * 16 + 16;          // LDS bytes per tile row (16 bytes of padding)
     constexpr int RPP = THREADS / KV;           // tile rows covered by one pass of all threads
@@ -77,6 +116,7 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     constexpr int NV = BN / VEC;                // LOAD_BT: n-vectors per k row of the B tile
     constexpr int BTV = (BK * NV + THREADS - 1) / THREADS;
     constexpr int BREG = LOAD == LOAD_BT ? BTV : BV;
+    constexpr bool TAPS = (LOAD == LOAD_TAPS);  // k walks (tap row, tap col, channel); otherwise one tap
     static_assert(WM * WN == 4 && TM >= 1 && TN >= 1, "tile shape");
 
     __shared__ __align__(16) unsigned char smem[2 * (BM + BN) * ROWB];
@@ -85,97 +125,145 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
-    const int tile_n = blockIdx.x % tiles_n, tile_m = blockIdx.x / tiles_n;
+    const int tile_m = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / tiles_n));
+    const int tile_n = (int)blockIdx.x - tile_m * tiles_n;
     const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
 
     const int z = blockIdx.z;
-    const int zb = a.z_lo + z / a.zh, zh = z % a.zh;
-    const T *xg = (const T *)a.x + zb * a.x_zb + zh * a.x_zh;
-    const T *wg = (const T *)a.w + zb * a.w_zb + zh * a.w_zh;
+    const int zq = __builtin_amdgcn_readfirstlane(z / a.zh);
+    const int zb = a.z_lo + zq, zh = z - zq * a.zh;
+    const int64_t x_zoff = zb * a.x_zb + zh * a.x_zh, w_zoff = zb * a.w_zb + zh * a.w_zh;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc((const T *)a.x + x_zoff, a.x_bytes - x_zoff * ESZ);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc((const T *)a.w + w_zoff, a.w_bytes - w_zoff * ESZ);
     const int64_t y_off = zb * a.y_zb + zh * a.y_zh;
 
-    const bool one_tap = (a.kh == 1 && a.kw == 1);
     const int HoWo = a.Ho * a.Wo;
     const int vcol = tid % KV;                  // which 16-byte vector of the row this thread moves
     const int vrow = tid / KV;
 
-    // ---- per-thread A rows: decode output position once ----
-    int64_t a_img[AV];
-    int a_ih0[AV], a_iw0[AV];
-    bool a_ok[AV];
+    // ---- per-thread A rows: byte offset of the window origin (or OOB) and validity masks of its taps ----
+    unsigned a_off[AV], a_hm[AV], a_wm[AV];
 #pragma unroll
     for (int i = 0; i < AV; ++i) {
         const int row = vrow + i * RPP;
         const int m = m0 + row;
-        a_ok[i] = (row < BM) && (m < a.m_hi);
-        const int mm = a_ok[i] ? m : a.m_lo;
+        const bool ok = (row < BM) && (m < a.m_hi);
+        const int mm = ok ? m : a.m_lo;
         const int img = mm / HoWo, rem = mm - img * HoWo;
         const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
-        a_img[i] = (int64_t)img * a.x_img;
-        a_ih0[i] = oh * a.stride - a.pad;
-        a_iw0[i] = ow * a.stride - a.pad;
+        const int ih0 = oh * a.stride - a.pad, iw0 = ow * a.stride - a.pad;
+        const int64_t e0 = (int64_t)img * a.x_img + ((int64_t)ih0 * a.W + iw0) * a.x_pix;   // may be negative at the border
+        a_off[i] = ok ? (unsigned)(int)(e0 * ESZ) : OOB;
+        unsigned hm = 0, wmk = 0;
+        for (int r = 0; r < a.kh; ++r) hm |= (unsigned)(ih0 + r >= 0 && ih0 + r < a.H) << r;
+        for (int q = 0; q < a.kw; ++q) wmk |= (unsigned)(iw0 + q >= 0 && iw0 + q < a.W) << q;
+        a_hm[i] = ok ? hm : 0u;
+        a_wm[i] = wmk;
+    }
+    // ---- per-thread B rows: byte offset of the weight row, and whether the row exists ----
+    unsigned b_off[BV];
+    bool b_ok[BV];
+#pragma unroll
+    for (int i = 0; i < BV; ++i) {
+        const int row = vrow + i * RPP;
+        const int n = n0 + row;
+        b_ok[i] = row < BN && n < a.n_hi;
+        b_off[i] = b_ok[i] ? (unsigned)((int64_t)n * a.w_row * ESZ) : 0u;
+    }
+
+    // K range of this slice, in blocks of BK (kb_per_slice counts 64-byte blocks)
+    const int nkb_all = (a.K + BK - 1) / BK;
+    const int per = a.kb_per_slice / (KV / 4);
+    const int slice = blockIdx.y;
+    const int kb_lo = slice * per;
+    const int nkb = min(nkb_all, kb_lo + per);
+    const int k_end = min(a.K, nkb * BK);       // loads at or beyond k_end return zeros
+
+    // running position of this thread's vector in K: element index kv and, for tapped walks, (r, s, ci)
+    int kv = kb_lo * BK + vcol * VEC;
+    int kr = 0, ksx = 0, kci = kv;
+    if constexpr (TAPS) {
+        const int tap = kv / a.Cin;
+        kci = kv - tap * a.Cin;
+        kr = tap / a.kw;
+        ksx = tap - kr * a.kw;
     }
 
     uint4 ra[2][AV], rb[2][BREG];
 
-    auto load_global = [&](int kb, uint4 *pa, uint4 *pb) {
-        const int kv = kb * BK + vcol * VEC;    // first k of this thread's vector
-        if constexpr (LOAD != LOAD_GATHER) {
-            int r, s, ci;
-            split_k(kv, a.Cin, a.kw, one_tap, r, s, ci);
-            const bool k_ok = kv < a.K;
-#pragma unroll
-            for (int i = 0; i < AV; ++i) {
-                const int ih = a_ih0[i] + r, iw = a_iw0[i] + s;
-                const bool ok = a_ok[i] && k_ok && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-                pa[i] = make_uint4(0, 0, 0, 0);
-                if (ok) pa[i] = *(const uint4 *)(xg + a_img[i] + ((int64_t)ih * a.W + iw) * a.x_pix + ci);
-            }
-            if constexpr (LOAD == LOAD_VEC) {
-#pragma unroll
-                for (int i = 0; i < BV; ++i) {
-                    const int row = vrow + i * RPP;
-                    const int n = n0 + row;
-                    pb[i] = make_uint4(0, 0, 0, 0);
-                    if (row < BN && n < a.n_hi && k_ok) pb[i] = *(const uint4 *)(wg + (int64_t)n * a.w_row + kv);
-                }
-            } else {
-                // B stored [k][n]: vectors run along n
-#pragma unroll
-                for (int i = 0; i < BTV; ++i) {
-                    const int idx = tid + i * THREADS;
-                    const int kk = idx / NV, nv = idx - kk * NV;
-                    const int k = kb * BK + kk, n = n0 + nv * VEC;
-                    pb[i] = make_uint4(0, 0, 0, 0);
-                    if (idx < BK * NV && k < a.K && n < a.n_hi) pb[i] = *(const uint4 *)(wg + (int64_t)k * a.w_row + n);
-                }
-            }
-        } else {
+    // loads the next K block of this thread (blocks are requested in ascending order, one call per block)
+    auto load_global = [&](uint4 *pa, uint4 *pb) {
+        if constexpr (LOAD == LOAD_GATHER) {
             // element-wise gather: any Cin, any alignment (stem convolutions, ragged K)
             T ea[AV][VEC], eb[BV][VEC];
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const int k = kv + e;
-                int r, s, ci;
-                split_k(k, a.Cin, a.kw, one_tap, r, s, ci);
-                const bool k_ok = k < a.K;
+                const int tap = k / a.Cin, ci = k - tap * a.Cin;
+                const int r = (tap / a.kw) & 31, q = (tap - (tap / a.kw) * a.kw) & 31;
+                const bool k_ok = k < k_end;
+                const unsigned delta = (unsigned)((((int64_t)r * a.W + q) * a.x_pix + ci) * ESZ);
 #pragma unroll
                 for (int i = 0; i < AV; ++i) {
-                    const int ih = a_ih0[i] + r, iw = a_iw0[i] + s;
-                    const bool ok = a_ok[i] && k_ok && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-                    ea[i][e] = ok ? xg[a_img[i] + ((int64_t)ih * a.W + iw) * a.x_pix + ci] : (T)0;
+                    const bool ok = k_ok && ((a_hm[i] >> r) & (a_wm[i] >> q) & 1u);
+                    ea[i][e] = buf_load1<T>(xr, ok ? a_off[i] + delta : OOB);
                 }
 #pragma unroll
-                for (int i = 0; i < BV; ++i) {
-                    const int row = vrow + i * RPP;
-                    const int n = n0 + row;
-                    eb[i][e] = (row < BN && n < a.n_hi && k_ok) ? wg[(int64_t)n * a.w_row + k] : (T)0;
-                }
+                for (int i = 0; i < BV; ++i) eb[i][e] = buf_load1<T>(wr, (k_ok && b_ok[i]) ? b_off[i] + (unsigned)(k * ESZ) : OOB);
             }
 #pragma unroll
             for (int i = 0; i < AV; ++i) pa[i] = *(const uint4 *)ea[i];
 #pragma unroll
             for (int i = 0; i < BV; ++i) pb[i] = *(const uint4 *)eb[i];
+        } else {
+            const bool k_ok = kv < k_end;
+            if constexpr (TAPS) {
+                const unsigned delta = (unsigned)((((int64_t)kr * a.W + ksx) * a.x_pix + kci) * ESZ);
+                const unsigned rr = k_ok ? (unsigned)kr : 31u, qq = (unsigned)ksx;
+#pragma unroll
+                for (int i = 0; i < AV; ++i) {
+                    const bool ok = k_ok && ((a_hm[i] >> rr) & (a_wm[i] >> qq) & 1u);
+                    pa[i] = buf_load16(xr, ok ? a_off[i] + delta : OOB);
+                }
+            } else {
+                const unsigned delta = (unsigned)(kv * ESZ);
+#pragma unroll
+                for (int i = 0; i < AV; ++i) pa[i] = buf_load16(xr, (k_ok && a_hm[i]) ? a_off[i] + delta : OOB);
+            }
+            if constexpr (LOAD != LOAD_BT) {
+                const unsigned delta = (unsigned)(kv * ESZ);
+#pragma unroll
+                for (int i = 0; i < BV; ++i) pb[i] = buf_load16(wr, (k_ok && b_ok[i]) ? b_off[i] + delta : OOB);
+            } else {
+                // B stored [k][n]: vectors run along n
+                const int kb0 = kv - vcol * VEC;
+#pragma unroll
+                for (int i = 0; i < BTV; ++i) {
+                    const int idx = tid + i * THREADS;
+                    const int kk = idx / NV, nv = idx - kk * NV;
+                    const int k = kb0 + kk, n = n0 + nv * VEC;
+                    const bool ok = idx < BK * NV && k < k_end && n < a.n_hi;
+                    pb[i] = buf_load16(wr, ok ? (unsigned)(((int64_t)k * a.w_row + n) * ESZ) : OOB);
+                }
+            }
+        }
+        // advance to the next block
+        kv += BK;
+        if constexpr (TAPS) {
+            kci += BK;
+            if (a.Cin >= BK) {                  // at most one tap boundary per block: select-only update
+                const bool w1 = kci >= a.Cin;
+                kci -= w1 ? a.Cin : 0;
+                ksx += w1 ? 1 : 0;
+                const bool w2 = ksx == a.kw;
+                ksx = w2 ? 0 : ksx;
+                kr += w2 ? 1 : 0;
+            } else {
+                const int tap = kv / a.Cin;
+                kci = kv - tap * a.Cin;
+                kr = tap / a.kw;
+                ksx = tap - kr * a.kw;
+            }
         }
     };
 
@@ -183,13 +271,13 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
             const int row = vrow + i * RPP;
-            if (row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = pa[i];
+            if (BM % RPP == 0 || row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = pa[i];
         }
         if constexpr (LOAD != LOAD_BT) {
 #pragma unroll
             for (int i = 0; i < BV; ++i) {
                 const int row = vrow + i * RPP;
-                if (row < BN) *(uint4 *)(Bs + (buf * BN + row) * ROWB + vcol * 16) = pb[i];
+                if (BN % RPP == 0 || row < BN) *(uint4 *)(Bs + (buf * BN + row) * ROWB + vcol * 16) = pb[i];
             }
         } else {
 #pragma unroll
@@ -247,30 +335,24 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         }
     };
 
-    // K range of this slice, in blocks of BK (kb_per_slice counts 64-byte blocks)
-    const int nkb_all = (a.K + BK - 1) / BK;
-    const int per = a.kb_per_slice / (KV / 4);
-    const int slice = blockIdx.y;
-    const int kb_lo = slice * per;
-    const int nkb = min(nkb_all, kb_lo + per);
-
     // Pipeline: LDS buffer p holds block kb, register set p^1 holds block kb+1 (in flight), and the loads
-    // of block kb+2 are issued into register set p before the MFMAs of block kb start.
-    load_global(kb_lo, ra[0], rb[0]);
+    // of block kb+2 are issued into register set p before the MFMAs of block kb start.  Loads and LDS
+    // stores in the loop body are unconditional (blocks past the end of the slice read as zeros and land in
+    // a buffer nobody reads), which keeps the body branch-free and the outstanding-load counts exact.
+    load_global(ra[0], rb[0]);
     store_lds(0, ra[0], rb[0]);
-    if (kb_lo + 1 < nkb) load_global(kb_lo + 1, ra[1], rb[1]);
+    load_global(ra[1], rb[1]);
     __syncthreads();
     for (int kb = kb_lo; kb < nkb; kb += 2) {
-        if (kb + 2 < nkb) load_global(kb + 2, ra[0], rb[0]);
+        load_global(ra[0], rb[0]);
         compute(0);
-        if (kb + 1 < nkb) store_lds(1, ra[1], rb[1]);
+        store_lds(1, ra[1], rb[1]);
         __syncthreads();
-        if (kb + 1 < nkb) {
-            if (kb + 3 < nkb) load_global(kb + 3, ra[1], rb[1]);
-            compute(1);
-            if (kb + 2 < nkb) store_lds(0, ra[0], rb[0]);
-            __syncthreads();
-        }
+        if (kb + 1 >= nkb) break;
+        load_global(ra[1], rb[1]);
+        compute(1);
+        store_lds(0, ra[0], rb[0]);
+        __syncthreads();
     }
 
     // ---- 32x32 accumulator layout: element e -> row (e/4)*8 + (lane/32)*4 + e%4, col lane%32 ----
@@ -352,12 +434,15 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok)
     li.kernel = a.b_trans ? n_bt.c_str() : (vec_ok ? n_vec.c_str() : n_gather.c_str());
     if (dry || li.workgroups == 0) return li;
     dim3 grid(tiles_m * tiles_n, ks, z), block(THREADS);
+    const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
     if (a.b_trans)
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, a);
-    else if (vec_ok)
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
-    else
+    else if (!vec_ok)
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, a);
+    else if (taps)
+        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
     if (ks > 1) {
         const int64_t total = (int64_t)(a.m_hi - a.m_lo) * (a.n_hi - a.n_lo);
         hipLaunchKernelGGL((splitk_finish<T>), dim3((unsigned)((total + THREADS - 1) / THREADS)), block, 0, s, a);

@@ -19,6 +19,7 @@ enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
 // *_zb / *_zh element offsets.
 struct GemmArgs {
     const void *x, *w;
+    int64_t x_bytes, w_bytes;  // bytes from x / w to the end of their tensors (bounds of the buffer descriptors)
     const float *bias;
     const void *res;
     void *y;
