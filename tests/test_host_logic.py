@@ -1,0 +1,254 @@
+"""Host-side logic of the library through the C ABI, no GPU needed: exported symbols, descriptor
+validation, plan validation, Matrix_P -> edges, and the host search against the oracle's search."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import schedule as S
+from paper_2304_11745_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+KIND = {"conv": B.GACER_CONV2D, "dwconv": B.GACER_DWCONV2D, "gemm": B.GACER_GEMM, "bgemm_qk": B.GACER_BGEMM_QK,
+        "bgemm_pv": B.GACER_BGEMM_PV, "maxpool": B.GACER_MAXPOOL, "gavgpool": B.GACER_GAVGPOOL,
+        "affine": B.GACER_AFFINE_ACT, "add": B.GACER_ADD, "layernorm": B.GACER_LAYERNORM,
+        "softmax": B.GACER_SOFTMAX, "act": B.GACER_ACT}
+ACT = {"none": 0, "relu": 1, "relu6": 2, "gelu": 3}
+FAKE = 0x10000      # 16-byte aligned, never dereferenced: nothing is launched in these tests
+
+
+def descriptors(tenants, mutate=None):
+    keep = []
+    descs = (B.gacer_tenant * len(tenants))()
+    for ti, t in enumerate(tenants):
+        tens = (B.gacer_tensor * len(t.tensors))(*[B.gacer_tensor(n, c, h, w, FAKE) for (n, c, h, w) in t.tensors])
+        ops = (B.gacer_op * len(t.ops))()
+        for i, op in enumerate(t.ops):
+            p = lambda idx: FAKE if idx >= 0 else None
+            ops[i] = B.gacer_op(KIND[op.kind], op.in0, op.in1, op.res, op.out, p(op.w), p(op.bias), p(op.scale), p(op.shift),
+                                op.cin, op.cout, op.kh, op.kw, op.stride, op.pad, op.groups, ACT[op.act],
+                                op.eps if op.kind == "layernorm" else op.alpha)
+        descs[ti] = B.gacer_tenant(len(t.ops), ops, len(t.tensors), tens, t.input, t.output,
+                                   1 if t.dtype == "bf16" else 0, t.batch, None)
+        keep += [tens, ops]
+    if mutate:
+        mutate(descs)
+    return descs, keep
+
+
+@pytest.fixture()
+def ctx():
+    c = C.c_void_p()
+    assert B.gacer_create(C.byref(c)) == B.GACER_OK
+    yield c
+    B.gacer_destroy(c)
+
+
+def load(ctx, tenants, mutate=None):
+    d, keep = descriptors(tenants, mutate)
+    return B.gacer_load_tenants(ctx, d, len(tenants)), keep
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "gacer.h")).read()
+    declared = set(re.findall(r"\b(gacer_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+
+
+def test_state_and_argument_errors(ctx):
+    assert B.gacer_run(ctx, 0, 1, None) == B.GACER_ESTATE
+    assert B.gacer_set_plan(ctx, None) == B.GACER_ESTATE
+    assert b"before" in B.gacer_last_error(ctx)
+    assert B.gacer_load_tenants(ctx, None, 1) == B.GACER_EINVAL
+    assert B.gacer_create(None) == B.GACER_EINVAL
+    B.gacer_destroy(None)
+
+
+@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+def test_all_configs_load_and_count_launches(ctx, config):
+    tenants, _ = synth.build_config(config, "full", with_data=False)
+    st, keep = load(ctx, tenants)
+    assert st == B.GACER_OK, B.gacer_last_error(ctx)
+    n = C.c_int()
+    assert B.gacer_launch_count(ctx, B.GACER_MODE_SEQUENTIAL, C.byref(n)) == B.GACER_OK
+    assert n.value == sum(len(t.ops) for t in tenants)
+
+
+def test_shape_validation(ctx):
+    tenants = [synth.small_resnet("f32", 2)]
+
+    def bad_cout(d):
+        d[0].ops[0].cout += 1
+    st, _ = load(ctx, tenants, bad_cout)
+    assert st == B.GACER_ESHAPE and b"tenant 0 op 0" in B.gacer_last_error(ctx)
+
+    def bad_order(d):
+        d[0].ops[1].in0 = d[0].ops[3].out          # reads a tensor that is written later
+    st, _ = load(ctx, tenants, bad_order)
+    assert st == B.GACER_ESHAPE
+
+    def misaligned(d):
+        d[0].tensors[1].dptr = FAKE + 4
+    st, _ = load(ctx, tenants, misaligned)
+    assert st == B.GACER_EINVAL
+
+    def null_w(d):
+        d[0].ops[0].w = None
+    st, _ = load(ctx, tenants, null_w)
+    assert st == B.GACER_EINVAL
+    st, _ = load(ctx, tenants)
+    assert st == B.GACER_OK
+
+
+def _plan(splits=(), syncs=()):
+    sp = (B.gacer_split * max(1, len(splits)))(*[B.gacer_split(*s) for s in splits])
+    sy = (B.gacer_sync * max(1, len(syncs)))(*[B.gacer_sync(*s) for s in syncs])
+    return B.gacer_plan(len(splits), sp, len(syncs), sy), (sp, sy)
+
+
+def test_plan_validation(ctx):
+    tenants = [synth.small_resnet("f32", 3), synth.small_bert("f32", 3)]
+    st, keep = load(ctx, tenants)
+    assert st == B.GACER_OK
+    ln = next(i for i, op in enumerate(tenants[1].ops) if op.kind == "layernorm")
+    bad = [
+        [(0, 0, B.GACER_AXIS_COUT, 3)],                                   # factor not in {1,2,4,8}
+        [(0, 0, B.GACER_AXIS_BATCH, 4)],                                  # factor > batch (3)
+        [(1, ln, B.GACER_AXIS_COUT, 2)],                                  # layernorm cannot split on channels
+        [(0, 0, B.GACER_AXIS_COUT, 2), (0, 0, B.GACER_AXIS_BATCH, 2)],    # listed twice
+        [(0, 99, B.GACER_AXIS_BATCH, 2)],                                 # missing operator
+        [(0, 0, B.GACER_AXIS_NONE, 2)],                                   # factor > 1 without an axis
+    ]
+    for sp in bad:
+        plan, k = _plan(sp)
+        assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_EPLAN, sp
+    for sy in ([(0, 1, 0, 3)], [(0, 99, 1, 0)], [(0, 3, 1, 1), (1, 2, 0, 2)]):   # same tenant; missing; cycle
+        plan, k = _plan((), sy)
+        assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_EPLAN, sy
+    assert b"cycle" in B.gacer_last_error(ctx)
+    plan, k = _plan([(0, 0, B.GACER_AXIS_COUT, 2), (0, 1, B.GACER_AXIS_BATCH, 2)], [(0, 3, 1, 1), (1, 0, 0, 2)])
+    assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_OK
+    n = C.c_int()
+    B.gacer_launch_count(ctx, B.GACER_MODE_PLAN, C.byref(n))
+    assert n.value == sum(len(t.ops) for t in tenants) + 2          # two operators became two chunks each
+    assert B.gacer_set_plan(ctx, None) == B.GACER_OK
+
+
+def _edges(ctx, matrix_P):
+    n_ptr = len(matrix_P[0])
+    flat = (C.c_int * max(1, len(matrix_P) * n_ptr))(*[p for P in matrix_P for p in P])
+    out = C.POINTER(B.gacer_plan)()
+    st = B.gacer_plan_from_pointers(ctx, flat, n_ptr, C.byref(out))
+    if st != B.GACER_OK:
+        return st, None
+    e = [(out.contents.sync[i].src_tenant, out.contents.sync[i].src_op, out.contents.sync[i].dst_tenant,
+          out.contents.sync[i].dst_op) for i in range(out.contents.n_sync)]
+    B.gacer_plan_free(out)
+    return st, e
+
+
+def test_pointers_to_edges_follow_the_worked_example(ctx):
+    """Eq. 6 / Eq. 7: M_1 with 12 operators and P_1=(2,8); M_2 with 8 operators and an empty first segment."""
+    a, b = synth.graphs._B("m1", "f32", 1), synth.graphs._B("m2", "f32", 1)
+    for bld, n in ((a, 12), (b, 8)):
+        x = y = bld.tensor(1, 8, 4, 4)
+        for _ in range(n):
+            y = bld.act(y, "relu")
+        bld.done(x, y)
+    st, keep = load(ctx, [a.t, b.t])
+    assert st == B.GACER_OK
+    st, edges = _edges(ctx, [[2, 8], [0, 4]])
+    assert st == B.GACER_OK
+    # oracle: cluster k+1 of every model starts after cluster <= k of every other model
+    cl = S.clusters([12, 8], [[2, 8], [0, 4]])
+    expect = set()
+    for k in range(2):
+        for src in range(2):
+            done = [o for kk in range(k + 1) for o in cl[kk][src]]
+            for dst in range(2):
+                nxt = [o for kk in range(k + 1, 3) for o in cl[kk][dst]]
+                if src != dst and done and nxt:
+                    expect.add((src, done[-1] - 1, dst, nxt[0] - 1))
+    assert set(edges) == expect
+    assert (0, 1, 1, 0) in expect and (1, 3, 0, 8) in expect and (0, 7, 1, 4) in expect
+    plan, k = _plan((), edges)
+    assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_OK
+    assert _edges(ctx, [[8, 2], [0, 4]])[0] == B.GACER_EPLAN
+    assert _edges(ctx, [[2, 13], [0, 4]])[0] == B.GACER_EPLAN
+
+
+def _chain_tenants(n_ops):
+    out = []
+    for k, n in enumerate(n_ops):
+        b = synth.graphs._B(f"m{k}", "f32", 8)
+        x = y = b.tensor(8, 16, 6, 6)
+        for _ in range(n):
+            y = b.conv(y, 16, 3, 1, 1, "relu")
+        out.append(b.done(x, y))
+    return out
+
+
+def _table_rows(rng, n_ops, wmax=1.0):
+    rows, table, splittable = [], {}, {}
+    for n, k in enumerate(n_ops):
+        for i in range(k):
+            T, W = float(np.float32(rng.uniform(0.1, 2.0))), float(np.float32(rng.uniform(0.05, wmax)))
+            rows.append((n, i, 0, 1, T, W))
+            axes = (1, 2) if rng.random() < 0.7 else ((1,) if rng.random() < 0.5 else ())
+            if axes:
+                splittable[(n, i)] = axes
+            for a in axes:
+                for f in (2, 4, 8):
+                    rows.append((n, i, a, f, float(np.float32(T / f * rng.uniform(1.0, 1.3))), float(np.float32(max(0.02, W / f)))))
+    for (n, i, a, f, T, W) in rows:
+        table[(n, i, a, f)] = S.Entry(T, W)
+    return rows, table, splittable
+
+
+def _prof(rows, t_sw):
+    arr = (B.gacer_prof * (len(rows) + 1))()
+    for k, (n, i, a, f, T, W) in enumerate(rows):
+        arr[k] = B.gacer_prof(n, i, a, f, T, 0, W)
+    arr[len(rows)] = B.gacer_prof(-1, -1, 0, 1, t_sw, 0, 1.0)
+    return arr
+
+
+def test_model_residue_and_search_match_the_oracle(ctx):
+    rng = np.random.default_rng(11)
+    for trial in range(8):
+        n_ops = [int(rng.integers(2, 7)) for _ in range(int(rng.integers(2, 4)))]
+        st, keep = load(ctx, _chain_tenants(n_ops))
+        assert st == B.GACER_OK, B.gacer_last_error(ctx)
+        rows, table, splittable = _table_rows(rng, n_ops)
+        t_sw = float(np.float32(0.03))
+        prof = _prof(rows, t_sw)
+        # (1) residue model on an explicit plan
+        npnt = int(rng.integers(0, 3))
+        P = [sorted(int(rng.integers(0, k + 1)) for _ in range(npnt)) for k in n_ops]
+        split = {key: (axes[0], 2) for key, axes in splittable.items() if rng.random() < 0.5}
+        sp = (B.gacer_split * max(1, len(split)))(*[B.gacer_split(n, i, a, f) for (n, i), (a, f) in split.items()])
+        flat = (C.c_int * max(1, len(n_ops) * npnt))(*[p for row in P for p in row])
+        R, mk = C.c_double(), C.c_double()
+        assert B.gacer_model_residue(ctx, prof, len(prof), sp, len(split), flat, npnt, C.byref(R), C.byref(mk)) == B.GACER_OK
+        iv, _, total = S.simulate(n_ops, table, split, P, t_sw)
+        assert abs(R.value - S.residue(iv, npnt, t_sw)) < 1e-9 and abs(mk.value - total) < 1e-9
+        # (2) the search itself: same decisions as the step-by-step oracle
+        o_split, o_P, o_R, _ = S.search(n_ops, table, t_sw, splittable, rounds=20, max_pointers=8)
+        out = C.POINTER(B.gacer_plan)()
+        ptrs = (C.c_int * (8 * len(n_ops)))()
+        n_ptr, Rs = C.c_int(), C.c_double()
+        assert B.gacer_search(ctx, prof, len(prof), 20, C.byref(out), ptrs, C.byref(n_ptr), C.byref(Rs)) == B.GACER_OK
+        assert abs(Rs.value - o_R) < 1e-9
+        got_P = [[ptrs[t * n_ptr.value + j] for j in range(n_ptr.value)] for t in range(len(n_ops))]
+        assert got_P == [list(p) for p in o_P]
+        got_split = {(out.contents.split[k].tenant, out.contents.split[k].op): (out.contents.split[k].axis, out.contents.split[k].factor)
+                     for k in range(out.contents.n_split)}
+        assert got_split == {k: v for k, v in o_split.items() if v[1] > 1}
+        # the returned plan is installable
+        assert B.gacer_set_plan(ctx, out) == B.GACER_OK
+        B.gacer_plan_free(out)
