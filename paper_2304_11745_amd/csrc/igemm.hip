@@ -355,44 +355,97 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         __syncthreads();
     }
 
-    // ---- 32x32 accumulator layout: element e -> row (e/4)*8 + (lane/32)*4 + e%4, col lane%32 ----
-    if (a.ksplit > 1) {
-        // park the slice accumulator; splitk_finish adds the slices in order and applies the epilogue
-        const int Nl = a.n_hi - a.n_lo;
-        float *ws = a.ws + (int64_t)slice * (a.m_hi - a.m_lo) * Nl;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn * (BN / WN) + j * 32 + lrow;
-            if (n >= a.n_hi) continue;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int m = m0 + wm * (BM / WM) + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-                    if (m < a.m_hi) ws[(int64_t)(m - a.m_lo) * Nl + (n - a.n_lo)] = acc[i][j][e];
-                }
-        }
-        return;
-    }
+    // ---- epilogue ----
+    // MFMA leaves element e of a 32x32 tile at row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.  Each wave
+    // turns its tiles through a private LDS patch so that a lane owns EV consecutive output channels of
+    // one row: residual loads and output stores are then 16-byte vectors along the contiguous axis.
+    constexpr int EV = DT == DT_BF16 ? 8 : 4;          // outputs per lane and group
+    constexpr int LPR = 32 / EV;                        // lanes per tile row
+    constexpr int GROUPS = 16 / EV;                     // row groups per lane
+    constexpr int SROW = 36;                            // floats per staged row (16-byte aligned, padded)
+    float *stage = (float *)smem + wave * (32 * SROW);
+    const bool split = a.ksplit > 1;
+    const int Nl = a.n_hi - a.n_lo;
+    float *ws = split ? a.ws + (int64_t)slice * (a.m_hi - a.m_lo) * Nl : nullptr;
     T *yg = (T *)a.y + y_off;
     const T *rg = a.res ? (const T *)a.res + y_off : nullptr;
+    const bool vec_out = split ? (Nl % 4 == 0 && (((uintptr_t)a.ws) & 15) == 0)
+                               : (a.y_row % EV == 0 && a.n_lo % EV == 0 && (y_off % EV) == 0 && (((uintptr_t)a.y) & 15) == 0 &&
+                                  (((uintptr_t)a.res) & 15) == 0 && (((uintptr_t)a.bias) & 15) == 0);
+    const int erow = lane / LPR, ecol = (lane % LPR) * EV;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int n = n0 + wn * (BN / WN) + j * 32 + lrow;
-        if (n >= a.n_hi) continue;
-        const float bias = a.bias ? a.bias[n] : 0.f;
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int j = 0; j < TN; ++j) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m0 + wm * (BM / WM) + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-                if (m >= a.m_hi) continue;
+            for (int e = 0; e < 16; ++e) stage[((e >> 2) * 8 + lhalf * 4 + (e & 3)) * SROW + lrow] = acc[i][j][e];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int row = erow + g * (64 / LPR);
+                const int m = m0 + wm * (BM / WM) + i * 32 + row;
+                const int n = n0 + wn * (BN / WN) + j * 32 + ecol;
+                float v[EV];
+#pragma unroll
+                for (int q = 0; q < EV; q += 4) {
+                    const float4 t4 = *(const float4 *)(stage + row * SROW + ecol + q);
+                    v[q] = t4.x; v[q + 1] = t4.y; v[q + 2] = t4.z; v[q + 3] = t4.w;
+                }
+                if (m >= a.m_hi || n >= a.n_hi) continue;
+                if (split) {
+                    float *p = ws + (int64_t)(m - a.m_lo) * Nl + (n - a.n_lo);
+                    if (vec_out && n + EV <= a.n_hi) {
+#pragma unroll
+                        for (int q = 0; q < EV; q += 4) *(float4 *)(p + q) = make_float4(v[q], v[q + 1], v[q + 2], v[q + 3]);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < EV; ++q)
+                            if (n + q < a.n_hi) p[q] = v[q];
+                    }
+                    continue;
+                }
                 const int64_t o = (int64_t)m * a.y_row + n;
-                float v = __fmaf_rn(acc[i][j][e], a.alpha, bias);
-                if (rg) v = __fadd_rn(v, load_in(rg, o));
-                store_out<T>(yg, o, act_apply(v, a.act));
+                if (vec_out && n + EV <= a.n_hi) {
+                    float r[EV];
+                    if (rg) {
+                        if constexpr (DT == DT_BF16) {
+                            const uint4 rv = *(const uint4 *)(rg + o);
+                            const unsigned rw[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) { r[2 * q] = __uint_as_float(rw[q] << 16); r[2 * q + 1] = __uint_as_float(rw[q] & 0xFFFF0000u); }
+                        } else {
+                            const float4 rv = *(const float4 *)(rg + o);
+                            r[0] = rv.x; r[1] = rv.y; r[2] = rv.z; r[3] = rv.w;
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < EV; ++q) {
+                        float t = __fmaf_rn(v[q], a.alpha, a.bias ? a.bias[n + q] : 0.f);
+                        if (rg) t = __fadd_rn(t, r[q]);
+                        v[q] = act_apply(t, a.act);
+                    }
+                    if constexpr (DT == DT_BF16) {
+                        uint4 ov;
+                        ov.x = (unsigned)f32_to_bf16(v[0]) | ((unsigned)f32_to_bf16(v[1]) << 16);
+                        ov.y = (unsigned)f32_to_bf16(v[2]) | ((unsigned)f32_to_bf16(v[3]) << 16);
+                        ov.z = (unsigned)f32_to_bf16(v[4]) | ((unsigned)f32_to_bf16(v[5]) << 16);
+                        ov.w = (unsigned)f32_to_bf16(v[6]) | ((unsigned)f32_to_bf16(v[7]) << 16);
+                        *(uint4 *)(yg + o) = ov;
+                    } else {
+                        *(float4 *)(yg + o) = make_float4(v[0], v[1], v[2], v[3]);
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < EV; ++q) {
+                        if (n + q >= a.n_hi) continue;
+                        float t = __fmaf_rn(v[q], a.alpha, a.bias ? a.bias[n + q] : 0.f);
+                        if (rg) t = __fadd_rn(t, load_in(rg, o + q));
+                        store_out<T>(yg, o + q, act_apply(t, a.act));
+                    }
+                }
             }
-    }
+            __builtin_amdgcn_wave_barrier();
+        }
 }
 
 // Second pass of a split-K operator: out = act(alpha * (s0 + s1 + ... ) + bias + res), slices added in
