@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--scale", default="full", choices=["full", "small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan", default="auto", help="auto | unsplit")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain copy of known size (256 MiB in, 256 MiB out) three times, as the "
+                         "reference dispatch for scaling hardware traffic counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (tenants shard across GPUs with no exchange); use --gpus 1")
@@ -98,6 +101,16 @@ def main():
     import synth
     from paper_2304_11745_amd import binding as B
     from paper_2304_11745_amd import harness
+
+    if args.copy_probe:
+        from synth import graphs as G
+        b = G._B("copy_probe", "f32", 64)
+        x = b.tensor(64, 256, 64, 64)                      # 64 Mi floats = 256 MiB
+        t = b.done(x, b.act(x, "none"))
+        probe = harness.Session([t], [G.materialise(t, 1)], "cuda:0")
+        probe.run(B.GACER_MODE_SEQUENTIAL, 3)
+        probe.close()
+        log("copy probe: eltwise kernel, 3 dispatches, 268435456 bytes read + 268435456 bytes written each")
 
     tenants, data = synth.build_config(args.config, args.scale)
     items = sum(t.batch for t in tenants)

@@ -183,7 +183,8 @@ gacer_status gacer_run(gacer_ctx *ctx, int mode, int rounds, float *ms_per_round
  * Measurement aid: like gacer_run, but every kernel launch is bracketed by a hipEvent pair on the
  * stream it runs on, so that per-launch durations under the chosen mode (including contention from
  * the other tenants' streams) can be read back.  out[k].ms is the mean over `rounds`.  Writes up to
- * `cap` rows (launch order of one round) and the row count to *n; cap = 0 sizes.  The event pairs
+ * `cap` rows (launch order of one round; an operator whose K range is cut into slices contributes its
+ * slice kernel and its finishing pass as two rows) and the row count to *n; cap = 0 sizes.  The event pairs
  * perturb the schedule slightly; throughput must be taken from gacer_run.
  */
 gacer_status gacer_trace_run(gacer_ctx *ctx, int mode, int rounds, gacer_launch_stat *out, size_t cap, size_t *n);
@@ -214,6 +215,11 @@ void gacer_plan_free(gacer_plan *plan);
 const char *gacer_last_error(const gacer_ctx *ctx);
 /* Number of kernel launches one round issues in the given mode under the current plan. */
 gacer_status gacer_launch_count(gacer_ctx *ctx, int mode, int *count);
+
+/* Host cost of the issue loop (Section 4.2, "more operators ... more CPU operators issuing overhead"): wall time
+ * the last gacer_run spent enqueueing its rounds, before it started to wait, and the number of operator
+ * launches it enqueued. */
+gacer_status gacer_issue_stats(gacer_ctx *ctx, double *host_ms, int *launches);
 
 #ifdef __cplusplus
 }

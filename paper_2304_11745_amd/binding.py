@@ -6,6 +6,10 @@ The shared library must have been built (``python -m paper_2304_11745_amd.build`
 import ctypes as C
 import os
 
+# The library runs on streams and memory that PyTorch creates, so both must use ONE HIP runtime in the
+# process: import torch first, then libgacer.so binds to the runtime torch has already loaded.
+import torch  # noqa: F401  (load order matters)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgacer.so")
 
@@ -19,7 +23,7 @@ GACER_MODE_PLAN, GACER_MODE_SEQUENTIAL, GACER_MODE_STREAM_PARALLEL = range(3)
 
 EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_plan", "gacer_plan_from_pointers",
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
-           "gacer_last_error", "gacer_launch_count", "gacer_trace_run"]
+           "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats"]
 
 
 class gacer_tensor(C.Structure):
@@ -86,6 +90,7 @@ def _load():
     lib.gacer_last_error.restype = C.c_char_p
     lib.gacer_launch_count.argtypes = [ctx, C.c_int, C.POINTER(C.c_int)]
     lib.gacer_trace_run.argtypes = [ctx, C.c_int, C.c_int, C.POINTER(gacer_launch_stat), C.c_size_t, C.POINTER(C.c_size_t)]
+    lib.gacer_issue_stats.argtypes = [ctx, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     return lib
 
 
@@ -104,6 +109,7 @@ gacer_plan_free = lib.gacer_plan_free
 gacer_last_error = lib.gacer_last_error
 gacer_launch_count = lib.gacer_launch_count
 gacer_trace_run = lib.gacer_trace_run
+gacer_issue_stats = lib.gacer_issue_stats
 
 
 class GacerError(RuntimeError):

@@ -54,6 +54,8 @@ struct Ctx {
     size_t n_sync_events = 0;                       // events the current plan needs
     std::vector<hipEvent_t> join_events;            // one per tenant
     std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
+    double last_issue_ms = 0;                       // host time the last gacer_run spent enqueueing
+    int last_issue_launches = 0;
     std::string err;
 };
 
@@ -63,7 +65,7 @@ bool axis_legal(gacer_opkind kind, gacer_axis axis);
 void chunk_range(int extent, int factor, int j, int *lo, int *hi);
 // builds the launch of operator `op` restricted to batch items [b_lo,b_hi) and channels [c_lo,c_hi)
 Launch make_launch(const Tenant &t, int op, int b_lo, int b_hi, int c_lo, int c_hi);
-LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry);
+LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase = 0);
 
 }  // namespace gacer
 

@@ -6,6 +6,7 @@
 // round, so the GPU does not idle while the CPU synchronises (the overhead analysed around Eq. 8
 // shrinks to the device-side wait).
 #include <algorithm>
+#include <chrono>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -165,10 +166,10 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
     return l;
 }
 
-LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry)
+LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase)
 {
     switch (l.kind) {
-    case LK_IGEMM: return launch_igemm(l.g, s, dry);
+    case LK_IGEMM: return launch_igemm(l.g, s, dry, phase);
     case LK_DWCONV: return launch_dwconv(l.s, s, dry);
     case LK_MAXPOOL: return launch_maxpool(l.s, s, dry);
     case LK_GAVGPOOL: return launch_gavgpool(l.s, s, dry);
@@ -602,6 +603,7 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
         c->join_events.push_back(e);
     }
     hipStream_t s0 = c->tenants[0].stream;
+    const auto host_t0 = std::chrono::steady_clock::now();
     for (int r = 0; r < rounds; ++r) {
         HIPCHK(c, hipEventRecord(c->t_start[r], s0));
         if (mode == GACER_MODE_SEQUENTIAL) {
@@ -628,6 +630,10 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
         }
         HIPCHK(c, hipEventRecord(c->t_end[r], s0));
     }
+    c->last_issue_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - host_t0).count();
+    c->last_issue_launches = 0;
+    gacer_launch_count(c, mode, &c->last_issue_launches);
+    c->last_issue_launches *= rounds;
     HIPCHK(c, hipStreamSynchronize(s0));
     HIPCHK(c, hipGetLastError());
     if (ms_per_round)
@@ -677,8 +683,9 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
         for (int t = 0; t < NT; ++t)
             for (int i = 0; i < (int)c->tenants[t].ops.size(); ++i) order.push_back({t, i});
     } else order = plan ? c->plan_order : c->par_order;
-    size_t total = 0;
-    for (const auto &to : order) total += ex[to.first][to.second].chunks.size();
+    size_t total = 0;                          // kernels per round (a split-K chunk is two kernels)
+    for (const auto &to : order)
+        for (const Launch &l : ex[to.first][to.second].chunks) total += (size_t)enqueue(l, nullptr, true).phases;
     *n_out = total;
     if (cap == 0 || !out) return GACER_OK;
     if (cap < total) return fail(c, GACER_EINVAL, "trace buffer too small (%zu rows needed)", total);
@@ -711,16 +718,20 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
             if (plan)
                 for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
             for (size_t j = 0; j < e.chunks.size(); ++j) {
-                HIPCHK(c, hipEventRecord(ev[k++], s));
-                const LaunchInfo li = enqueue(e.chunks[j], s, false);
-                HIPCHK(c, hipEventRecord(ev[k++], s));
-                if (r == 0) {
-                    gacer_launch_stat &st = out[row];
-                    st.tenant = to.first; st.op = to.second; st.chunk = (int)j; st.ms = 0.f; st.workgroups = li.workgroups;
-                    launch_work(e.chunks[j], &st.flops, &st.bytes);
-                    std::snprintf(st.kernel, sizeof st.kernel, "%s", li.kernel);
+                const int phases = enqueue(e.chunks[j], s, true).phases;
+                for (int ph = 1; ph <= phases; ++ph) {
+                    HIPCHK(c, hipEventRecord(ev[k++], s));
+                    const LaunchInfo li = enqueue(e.chunks[j], s, false, phases == 1 ? 0 : ph);
+                    HIPCHK(c, hipEventRecord(ev[k++], s));
+                    if (r == 0) {
+                        gacer_launch_stat &st = out[row];
+                        st.tenant = to.first; st.op = to.second; st.chunk = (int)j; st.ms = 0.f; st.workgroups = li.workgroups;
+                        st.flops = st.bytes = 0.0;
+                        if (ph == 1) launch_work(e.chunks[j], &st.flops, &st.bytes);   // the operator's work is booked on its main kernel
+                        std::snprintf(st.kernel, sizeof st.kernel, "%s", li.kernel);
+                    }
+                    ++row;
                 }
-                ++row;
             }
             if (plan && e.record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.record], s));
         }
@@ -742,6 +753,14 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
         }
     for (hipEvent_t e : ev) (void)hipEventDestroy(e);
     (void)hipEventDestroy(fork);
+    return GACER_OK;
+}
+
+gacer_status gacer_issue_stats(gacer_ctx *c, double *host_ms, int *launches)
+{
+    if (!c || !host_ms || !launches) return GACER_EINVAL;
+    *host_ms = c->last_issue_ms;
+    *launches = c->last_issue_launches;
     return GACER_OK;
 }
 

@@ -468,7 +468,7 @@ __global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
 
 // ------------------------------------------------------------------------------------------------
 template <int DT, int BM, int BN, int WM, int WN, int KV>
-static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok)
+static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, int phase)
 {
     typedef typename El<DT>::T T;
     constexpr int ROWB = KV * 16 + 16;
@@ -483,11 +483,21 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok)
     li.wg_per_cu = by_lds < 8 ? by_lds : 8;     // 8 wave slots per SIMD, one wave of each workgroup per SIMD
     static const std::string shape = std::string(DT == DT_BF16 ? "bf16_" : "f32_") + std::to_string(BM) + "x" + std::to_string(BN) +
                                      "x" + std::to_string(KV * El<DT>::VEC);
-    static const std::string n_vec = "igemm_" + shape, n_bt = "igemm_bt_" + shape, n_gather = "igemm_gather_" + shape;
-    li.kernel = a.b_trans ? n_bt.c_str() : (vec_ok ? n_vec.c_str() : n_gather.c_str());
+    static const std::string n_vec = "igemm_" + shape, n_bt = "igemm_bt_" + shape, n_gather = "igemm_gather_" + shape,
+                             n_taps = "igemm_taps_" + shape;
+    const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
+    li.kernel = a.b_trans ? n_bt.c_str() : (!vec_ok ? n_gather.c_str() : (taps ? n_taps.c_str() : n_vec.c_str()));
+    li.phases = ks > 1 ? 2 : 1;
+    if (phase == 2) li.kernel = "splitk_finish";
     if (dry || li.workgroups == 0) return li;
     dim3 grid(tiles_m * tiles_n, ks, z), block(THREADS);
-    const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
+    if (phase == 2) {
+        if (ks > 1) {
+            const int64_t total = (int64_t)(a.m_hi - a.m_lo) * (a.n_hi - a.n_lo);
+            hipLaunchKernelGGL((splitk_finish<T>), dim3((unsigned)((total + THREADS - 1) / THREADS)), block, 0, s, a);
+        }
+        return li;
+    }
     if (a.b_trans)
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, a);
     else if (!vec_ok)
@@ -496,7 +506,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok)
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
-    if (ks > 1) {
+    if (ks > 1 && phase == 0) {
         const int64_t total = (int64_t)(a.m_hi - a.m_lo) * (a.n_hi - a.n_lo);
         hipLaunchKernelGGL((splitk_finish<T>), dim3((unsigned)((total + THREADS - 1) / THREADS)), block, 0, s, a);
     }
@@ -504,7 +514,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok)
 }
 
 template <int DT>
-static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry)
+static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
 {
     constexpr int VEC = El<DT>::VEC;
     const bool vec_ok = (a.Cin % VEC == 0) && (a.x_pix % VEC == 0) && (a.x_img % VEC == 0) && (a.w_row % VEC == 0) &&
@@ -520,25 +530,27 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry)
     if (waste(32) < waste(bn) - 1e-9) bn = 32;
     auto wgs = [&](int bm, int bnn) { return (int64_t)((M + bm - 1) / bm) * ((N + bnn - 1) / bnn) * z; };
     const int64_t want = 512;
+    // fp32: the 128x128 tile needs so many registers that only one wave fits per SIMD; 128x64 is faster.
+    const bool big = DT == DT_BF16;
     if (a.b_trans || a.K <= 16 * VEC) {          // short K: 64-byte blocks
-        if (bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 4>(a, s, dry, vec_ok);
+        if (big && bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 4>(a, s, dry, vec_ok, phase);
         if (bn >= 64) {
-            if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 4>(a, s, dry, vec_ok);
-            return go<DT, 64, 64, 2, 2, 4>(a, s, dry, vec_ok);
+            if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
+            return go<DT, 64, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
         }
-        return go<DT, 128, 32, 4, 1, 4>(a, s, dry, vec_ok);
+        return go<DT, 128, 32, 4, 1, 4>(a, s, dry, vec_ok, phase);
     }
-    if (bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 8>(a, s, dry, vec_ok);
+    if (big && bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 8>(a, s, dry, vec_ok, phase);
     if (bn >= 64) {
-        if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 8>(a, s, dry, vec_ok);
-        return go<DT, 64, 64, 2, 2, 8>(a, s, dry, vec_ok);
+        if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 8>(a, s, dry, vec_ok, phase);
+        return go<DT, 64, 64, 2, 2, 8>(a, s, dry, vec_ok, phase);
     }
-    return go<DT, 128, 32, 4, 1, 8>(a, s, dry, vec_ok);
+    return go<DT, 128, 32, 4, 1, 8>(a, s, dry, vec_ok, phase);
 }
 
-LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry)
+LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry, int phase)
 {
-    return a.dtype == DT_BF16 ? pick<DT_BF16>(a, s, dry) : pick<DT_F32>(a, s, dry);
+    return a.dtype == DT_BF16 ? pick<DT_BF16>(a, s, dry, phase) : pick<DT_F32>(a, s, dry, phase);
 }
 
 }  // namespace gacer

@@ -62,9 +62,11 @@ struct StreamArgs {
     int64_t rows_per_item;     // row operators: rows (positions) per batch item
 };
 
-struct LaunchInfo { int workgroups; int threads; int lds_bytes; int wg_per_cu; const char *kernel; };
+// phases: 1 = one kernel; 2 = a split-K operator (slice kernel, then the ordered finishing pass)
+struct LaunchInfo { int workgroups; int threads; int lds_bytes; int wg_per_cu; const char *kernel; int phases; };
 
-LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry);
+// phase 0 enqueues everything the operator needs; 1 only the slice / main kernel; 2 only the finishing pass
+LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry, int phase = 0);
 LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_maxpool(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry);

@@ -218,6 +218,7 @@ static LaunchInfo info(int64_t wgs, const char *kernel)
 {
     LaunchInfo li;
     li.kernel = kernel;
+    li.phases = 1;
     li.workgroups = (int)wgs;
     li.threads = TPB;
     li.lds_bytes = 0;

@@ -134,6 +134,12 @@ class Session:
         B.check(self.ctx, B.gacer_run(self.ctx, mode, rounds, ms))
         return list(ms)
 
+    def issue_stats(self):
+        """(host milliseconds spent enqueueing, operator launches enqueued) of the last run()."""
+        ms, n = C.c_double(), C.c_int()
+        B.check(self.ctx, B.gacer_issue_stats(self.ctx, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
+
     def launch_count(self, mode=B.GACER_MODE_PLAN):
         n = C.c_int()
         B.check(self.ctx, B.gacer_launch_count(self.ctx, mode, C.byref(n)))
