@@ -116,9 +116,12 @@ typedef struct {
 
 /* mask + list_B (Section 4.2): operator (tenant, op) is decomposed `factor` ways on `axis`. */
 typedef struct { int tenant, op; gacer_axis axis; int factor; } gacer_split;
-/* One ordering constraint between streams: (dst_tenant,dst_op) starts only after every chunk
- * of (src_tenant,src_op) has finished.  Cluster barriers of Matrix_P expand into such edges. */
-typedef struct { int src_tenant, src_op, dst_tenant, dst_op; } gacer_sync;
+/* One ordering constraint between streams.  when == 0: (dst_tenant,dst_op) starts only after every chunk of
+ * (src_tenant,src_op) has finished.  when == 1: it starts once everything (src_tenant,src_op) itself has to wait
+ * for is done (its stream predecessors and its own when-0 edges) -- the source operator then acts as the hub of a
+ * barrier: it gathers the other streams and releases them without making them wait for its own execution.
+ * Cluster barriers of Matrix_P expand into such edges. */
+typedef struct { int src_tenant, src_op, dst_tenant, dst_op, when; } gacer_sync;
 typedef struct { int n_split; const gacer_split *split; int n_sync; const gacer_sync *sync; } gacer_plan;
 
 /* One row of the lookup table of Section 4.1: operator (tenant, op) decomposed `factor` ways on
@@ -161,10 +164,13 @@ gacer_status gacer_set_plan(gacer_ctx *ctx, const gacer_plan *plan);
 /*
  * Matrix_P -> sync edges (Eq. 6 / Eq. 7).  P holds n_tenants rows of n_ptr sorted pointer
  * values; value p cuts after the p-th operator (1-based; 0 and n_ops give empty segments).
- * Same-index segments form a cluster; the edges make the first operator of every tenant's
- * segment k+1 wait for the last operator of every other tenant's segments <= k.  The split
- * part of the returned plan is empty.  Free with gacer_plan_free.  GACER_EPLAN if a row is
- * unsorted or out of range.
+ * Same-index segments form a cluster; after the edges, the first operator of every tenant's
+ * segment k+1 is ordered behind the last operator of every other tenant's segments <= k.  Each
+ * barrier is built around a hub (the lowest-numbered tenant whose next segment is not empty): the hub's next
+ * operator waits for the last operators of all other tenants (when = 0 edges) and the other tenants'
+ * next operators wait for the hub to be released (when = 1 edges) -- 2(N-1) edges per pointer instead
+ * of N(N-1).  The split part of the returned plan is empty.  Free with gacer_plan_free.
+ * GACER_EPLAN if a row is unsorted or out of range.
  */
 gacer_status gacer_plan_from_pointers(gacer_ctx *ctx, const int *P, int n_ptr, gacer_plan **out);
 
@@ -215,6 +221,19 @@ void gacer_plan_free(gacer_plan *plan);
 const char *gacer_last_error(const gacer_ctx *ctx);
 /* Number of kernel launches one round issues in the given mode under the current plan. */
 gacer_status gacer_launch_count(gacer_ctx *ctx, int mode, int *count);
+
+/*
+ * Captures one round of `mode` under the current plan into a HIP graph (fork from tenant 0's stream, every
+ * operator on its tenant's stream with its event edges, join); later gacer_run calls in that mode replay the
+ * graph instead of issuing launch by launch, which removes the per-launch host cost (the issuing overhead
+ * discussed in Section 4.2 and Section 5.5).  Outputs are identical to the uncaptured run.  The capture is
+ * dropped by gacer_set_plan, gacer_load_tenants and gacer_release_graphs.  Tensor pointers are baked in.
+ * HIP runtimes older than 7.2 crash inside hipStreamEndCapture when three or more captured streams wait on
+ * each other's events mutually; on such a runtime the call refuses (GACER_EPLAN) a plan in which operators of
+ * more than one tenant wait on two or more events.  Hub barriers from gacer_plan_from_pointers are accepted.
+ */
+gacer_status gacer_capture(gacer_ctx *ctx, int mode);
+gacer_status gacer_release_graphs(gacer_ctx *ctx);
 
 /* Host cost of the issue loop (Section 4.2, "more operators ... more CPU operators issuing overhead"): wall time
  * the last gacer_run spent enqueueing its rounds, before it started to wait, and the number of operator

@@ -23,7 +23,8 @@ GACER_MODE_PLAN, GACER_MODE_SEQUENTIAL, GACER_MODE_STREAM_PARALLEL = range(3)
 
 EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_plan", "gacer_plan_from_pointers",
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
-           "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats"]
+           "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats", "gacer_capture",
+           "gacer_release_graphs"]
 
 
 class gacer_tensor(C.Structure):
@@ -48,7 +49,8 @@ class gacer_split(C.Structure):
 
 
 class gacer_sync(C.Structure):
-    _fields_ = [("src_tenant", C.c_int), ("src_op", C.c_int), ("dst_tenant", C.c_int), ("dst_op", C.c_int)]
+    _fields_ = [("src_tenant", C.c_int), ("src_op", C.c_int), ("dst_tenant", C.c_int), ("dst_op", C.c_int),
+                ("when", C.c_int)]
 
 
 class gacer_plan(C.Structure):
@@ -90,6 +92,8 @@ def _load():
     lib.gacer_last_error.restype = C.c_char_p
     lib.gacer_launch_count.argtypes = [ctx, C.c_int, C.POINTER(C.c_int)]
     lib.gacer_trace_run.argtypes = [ctx, C.c_int, C.c_int, C.POINTER(gacer_launch_stat), C.c_size_t, C.POINTER(C.c_size_t)]
+    lib.gacer_capture.argtypes = [ctx, C.c_int]
+    lib.gacer_release_graphs.argtypes = [ctx]
     lib.gacer_issue_stats.argtypes = [ctx, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     return lib
 
@@ -110,6 +114,8 @@ gacer_last_error = lib.gacer_last_error
 gacer_launch_count = lib.gacer_launch_count
 gacer_trace_run = lib.gacer_trace_run
 gacer_issue_stats = lib.gacer_issue_stats
+gacer_capture = lib.gacer_capture
+gacer_release_graphs = lib.gacer_release_graphs
 
 
 class GacerError(RuntimeError):

@@ -34,6 +34,7 @@ struct OpExec {
     std::vector<Launch> chunks;
     std::vector<int> waits;     // indices into Ctx::sync_events
     int record = -1;            // event recorded after the last chunk, -1 = none
+    int pre_record = -1;        // event recorded after the waits and before the first chunk (barrier hub)
 };
 
 struct Ctx {
@@ -54,6 +55,7 @@ struct Ctx {
     size_t n_sync_events = 0;                       // events the current plan needs
     std::vector<hipEvent_t> join_events;            // one per tenant
     std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
+    hipGraphExec_t graph_exec[3] = {nullptr, nullptr, nullptr};   // captured round per mode (optional)
     double last_issue_ms = 0;                       // host time the last gacer_run spent enqueueing
     int last_issue_launches = 0;
     std::string err;
@@ -66,6 +68,7 @@ void chunk_range(int extent, int factor, int j, int *lo, int *hi);
 // builds the launch of operator `op` restricted to batch items [b_lo,b_hi) and channels [c_lo,c_hi)
 Launch make_launch(const Tenant &t, int op, int b_lo, int b_hi, int c_lo, int c_hi);
 LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase = 0);
+void drop_graphs(Ctx *c);
 
 }  // namespace gacer
 

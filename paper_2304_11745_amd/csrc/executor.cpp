@@ -13,6 +13,7 @@
 #include <map>
 #include <new>
 #include <set>
+#include <tuple>
 #include "ctx.h"
 
 using namespace gacer;
@@ -364,6 +365,7 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
             e.dst_op < 0 || e.dst_op >= (int)c->tenants[e.dst_tenant].ops.size())
             return fail(c, GACER_EPLAN, "sync edge names a missing operator");
         if (e.src_tenant == e.dst_tenant) return fail(c, GACER_EPLAN, "sync edge inside one tenant (stream order already holds)");
+        if (e.when != 0 && e.when != 1) return fail(c, GACER_EPLAN, "sync edge: when must be 0 or 1");
     }
     // topological issue order over (stream order U sync edges); round-robin over tenants so that
     // every stream receives work early.  No progress in a sweep means a cycle.
@@ -387,10 +389,10 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
         }
         if (!progress) return fail(c, GACER_EPLAN, "sync edges form a cycle with the stream order (would deadlock)");
     }
-    // events: one per distinct source operator
-    std::map<std::pair<int, int>, int> ev_of;
+    // events: one per distinct (source operator, when)
+    std::map<std::tuple<int, int, int>, int> ev_of;
     for (const gacer_sync &e : syncs)
-        if (!ev_of.count({e.src_tenant, e.src_op})) { const int id = (int)ev_of.size(); ev_of[{e.src_tenant, e.src_op}] = id; }
+        if (!ev_of.count({e.src_tenant, e.src_op, e.when})) { const int id = (int)ev_of.size(); ev_of[{e.src_tenant, e.src_op, e.when}] = id; }
     std::vector<std::vector<OpExec>> ex(NT);
     for (int t = 0; t < NT; ++t) {
         const Tenant &T = c->tenants[t];
@@ -415,11 +417,14 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
         }
     }
     for (const gacer_sync &e : syncs) {
-        const int id = ev_of[{e.src_tenant, e.src_op}];
-        ex[e.src_tenant][e.src_op].record = id;
+        const int id = ev_of[{e.src_tenant, e.src_op, e.when}];
+        if (e.when == 0) ex[e.src_tenant][e.src_op].record = id;
+        else ex[e.src_tenant][e.src_op].pre_record = id;
         auto &w = ex[e.dst_tenant][e.dst_op].waits;
         if (std::find(w.begin(), w.end(), id) == w.end()) w.push_back(id);
     }
+    for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    drop_graphs(c);                      // captured rounds belong to the plan they were captured under
     c->splits = splits;
     c->syncs = syncs;
     c->plan_exec.swap(ex);
@@ -452,6 +457,7 @@ void gacer_destroy(gacer_ctx *c)
 {
     if (!c) return;
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    drop_graphs(c);
     release_workspaces(c->tenants);
     for (hipEvent_t e : c->sync_events) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->join_events) (void)hipEventDestroy(e);
@@ -500,6 +506,7 @@ gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n
         T.stream = (hipStream_t)t.stream;
     }
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    drop_graphs(c);
     release_workspaces(c->tenants);
     c->ws_missing = false;
     plan_workspaces(c, fresh);
@@ -538,17 +545,30 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *c, const int *P, int n_ptr, gac
                 return fail(c, GACER_EPLAN, "tenant %d: pointers must be sorted and lie in [0, n_ops]", t);
         }
     std::vector<gacer_sync> edges;
-    for (int j = 0; j < n_ptr; ++j)
+    for (int j = 0; j < n_ptr; ++j) {
+        // Barrier j separates clusters j and j+1.  Only tenants with a non-empty segment j+1 take part on the
+        // release side; the hub is the lowest of them, so every barrier has its own hub operator.  An empty
+        // cluster j+1 needs no barrier of its own: barrier j+1 orders everything before it.
+        auto seg_begin = [&](int t) { return P[t * n_ptr + j]; };
+        auto seg_end = [&](int t) { return j + 1 < n_ptr ? P[t * n_ptr + j + 1] : (int)c->tenants[t].ops.size(); };
+        int hub = -1;
+        for (int t = 0; t < NT && hub < 0; ++t)
+            if (seg_begin(t) < seg_end(t)) hub = t;
+        if (hub < 0) continue;
+        const int hub_first = seg_begin(hub);
+        bool gathers = false;
         for (int a = 0; a < NT; ++a) {
             const int last = P[a * n_ptr + j] - 1;               // 0-based last operator of a's segments <= j
-            if (last < 0) continue;
-            for (int b = 0; b < NT; ++b) {
-                if (a == b) continue;
-                const int first = P[b * n_ptr + j];              // 0-based first operator after the pointer
-                if (first >= (int)c->tenants[b].ops.size()) continue;
-                edges.push_back({a, last, b, first});
-            }
+            if (a == hub || last < 0) continue;
+            edges.push_back({a, last, hub, hub_first, 0});
+            gathers = true;
         }
+        if (!gathers && hub_first == 0) continue;                // nothing has run before this barrier
+        for (int b = 0; b < NT; ++b) {
+            if (b == hub || seg_begin(b) >= seg_end(b)) continue;
+            edges.push_back({hub, hub_first, b, seg_begin(b), 1});
+        }
+    }
     gacer_plan *pl = new (std::nothrow) gacer_plan();
     if (!pl) return fail(c, GACER_ENOMEM, "out of memory");
     pl->n_split = 0; pl->split = nullptr;
@@ -573,17 +593,14 @@ static gacer_status issue_op(Ctx *c, const OpExec &e, hipStream_t s, bool with_e
 {
     if (with_events)
         for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
+    if (with_events && e.pre_record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.pre_record], s));
     for (const Launch &l : e.chunks) enqueue(l, s, false);
     if (with_events && e.record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.record], s));
     return GACER_OK;
 }
 
-gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
+static gacer_status ensure_events(Ctx *c, int rounds)
 {
-    if (!c) return GACER_EINVAL;
-    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_run before gacer_load_tenants");
-    if (mode < 0 || mode > 2 || rounds < 1) return fail(c, GACER_EINVAL, "bad mode or rounds");
-    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
     const int NT = (int)c->tenants.size();
     while ((int)c->t_start.size() < rounds) {
         hipEvent_t a, b;
@@ -597,36 +614,125 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
         HIPCHK(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
         c->sync_events.push_back(ev);
     }
-    while ((int)c->join_events.size() < NT) {
+    while ((int)c->join_events.size() < NT + 1) {          // [NT] is the fork event
         hipEvent_t e;
         HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
         c->join_events.push_back(e);
     }
+    return GACER_OK;
+}
+
+// Enqueues one round: fork from tenant 0's stream, every operator in issue order, join back.
+static gacer_status issue_round(Ctx *c, int mode)
+{
+    const int NT = (int)c->tenants.size();
+    hipStream_t s0 = c->tenants[0].stream;
+    if (mode == GACER_MODE_SEQUENTIAL) {
+        for (int t = 0; t < NT; ++t)
+            for (const OpExec &e : c->plain_exec[t]) {
+                gacer_status st = issue_op(c, e, s0, false);
+                if (st != GACER_OK) return st;
+            }
+        return GACER_OK;
+    }
+    hipEvent_t fork = c->join_events[NT];
+    HIPCHK(c, hipEventRecord(fork, s0));
+    for (int t = 1; t < NT; ++t)
+        if (c->tenants[t].stream != s0) HIPCHK(c, hipStreamWaitEvent(c->tenants[t].stream, fork, 0));
+    const bool plan = (mode == GACER_MODE_PLAN);
+    const auto &order = plan ? c->plan_order : c->par_order;
+    const auto &ex = plan ? c->plan_exec : c->plain_exec;
+    for (const auto &to : order) {
+        gacer_status st = issue_op(c, ex[to.first][to.second], c->tenants[to.first].stream, plan);
+        if (st != GACER_OK) return st;
+    }
+    for (int t = 1; t < NT; ++t)
+        if (c->tenants[t].stream != s0) {
+            HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
+            HIPCHK(c, hipStreamWaitEvent(s0, c->join_events[t], 0));
+        }
+    return GACER_OK;
+}
+
+}  // extern "C"
+namespace gacer {
+void drop_graphs(Ctx *c)
+{
+    for (int m = 0; m < 3; ++m)
+        if (c->graph_exec[m]) { (void)hipGraphExecDestroy(c->graph_exec[m]); c->graph_exec[m] = nullptr; }
+}
+}  // namespace gacer
+extern "C" {
+
+gacer_status gacer_capture(gacer_ctx *c, int mode)
+{
+    if (!c) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_capture before gacer_load_tenants");
+    if (mode < 0 || mode > 2) return fail(c, GACER_EINVAL, "bad mode");
+    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
+    if (mode == GACER_MODE_PLAN) {
+        // HIP runtimes before 7.2 crash in hipStreamEndCapture on mutual multi-stream event waits
+        int rt = 0;
+        if (hipRuntimeGetVersion(&rt) != hipSuccess || rt < 70200000) {
+            int multi_wait_tenants = 0;
+            for (const auto &t : c->plan_exec) {
+                bool multi = false;
+                for (const OpExec &e : t) multi = multi || e.waits.size() >= 2;
+                multi_wait_tenants += multi ? 1 : 0;
+            }
+            if (multi_wait_tenants > 1)
+                return fail(c, GACER_EPLAN, "this HIP runtime (%d) cannot capture a plan in which operators of several tenants wait on "
+                                            "two or more events; use hub barriers or run uncaptured", rt);
+        }
+    }
+    gacer_status st = ensure_events(c, 1);
+    if (st != GACER_OK) return st;
+    if (c->graph_exec[mode]) { (void)hipGraphExecDestroy(c->graph_exec[mode]); c->graph_exec[mode] = nullptr; }
+    hipStream_t s0 = c->tenants[0].stream;
+    for (Tenant &t : c->tenants) HIPCHK(c, hipStreamSynchronize(t.stream));
+    HIPCHK(c, hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
+    st = issue_round(c, mode);
+    hipGraph_t graph = nullptr;
+    const hipError_t e_end = hipStreamEndCapture(s0, &graph);
+    if (st != GACER_OK || e_end != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        (void)hipGetLastError();
+        if (st == GACER_OK) return fail(c, GACER_EHIP, "stream capture failed: %s", hipGetErrorString(e_end));
+        return st;
+    }
+    hipGraphExec_t exec = nullptr;
+    const hipError_t e_inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e_inst != hipSuccess) return fail(c, GACER_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e_inst));
+    c->graph_exec[mode] = exec;
+    return GACER_OK;
+}
+
+gacer_status gacer_release_graphs(gacer_ctx *c)
+{
+    if (!c) return GACER_EINVAL;
+    for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
+    drop_graphs(c);
+    return GACER_OK;
+}
+
+gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
+{
+    if (!c) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_run before gacer_load_tenants");
+    if (mode < 0 || mode > 2 || rounds < 1) return fail(c, GACER_EINVAL, "bad mode or rounds");
+    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
+    gacer_status st = ensure_events(c, rounds);
+    if (st != GACER_OK) return st;
     hipStream_t s0 = c->tenants[0].stream;
     const auto host_t0 = std::chrono::steady_clock::now();
     for (int r = 0; r < rounds; ++r) {
         HIPCHK(c, hipEventRecord(c->t_start[r], s0));
-        if (mode == GACER_MODE_SEQUENTIAL) {
-            for (int t = 0; t < NT; ++t)
-                for (const OpExec &e : c->plain_exec[t]) {
-                    gacer_status st = issue_op(c, e, s0, false);
-                    if (st != GACER_OK) return st;
-                }
+        if (c->graph_exec[mode]) {
+            HIPCHK(c, hipGraphLaunch(c->graph_exec[mode], s0));
         } else {
-            for (int t = 1; t < NT; ++t)
-                if (c->tenants[t].stream != s0) HIPCHK(c, hipStreamWaitEvent(c->tenants[t].stream, c->t_start[r], 0));
-            const bool plan = (mode == GACER_MODE_PLAN);
-            const auto &order = plan ? c->plan_order : c->par_order;
-            const auto &ex = plan ? c->plan_exec : c->plain_exec;
-            for (const auto &to : order) {
-                gacer_status st = issue_op(c, ex[to.first][to.second], c->tenants[to.first].stream, plan);
-                if (st != GACER_OK) return st;
-            }
-            for (int t = 1; t < NT; ++t)
-                if (c->tenants[t].stream != s0) {
-                    HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
-                    HIPCHK(c, hipStreamWaitEvent(s0, c->join_events[t], 0));
-                }
+            st = issue_round(c, mode);
+            if (st != GACER_OK) return st;
         }
         HIPCHK(c, hipEventRecord(c->t_end[r], s0));
     }
@@ -689,15 +795,9 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
     *n_out = total;
     if (cap == 0 || !out) return GACER_OK;
     if (cap < total) return fail(c, GACER_EINVAL, "trace buffer too small (%zu rows needed)", total);
-    while (c->sync_events.size() < c->n_sync_events) {
-        hipEvent_t ev;
-        HIPCHK(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
-        c->sync_events.push_back(ev);
-    }
-    while ((int)c->join_events.size() < NT) {
-        hipEvent_t e;
-        HIPCHK(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        c->join_events.push_back(e);
+    {
+        gacer_status st = ensure_events(c, 1);
+        if (st != GACER_OK) return st;
     }
     std::vector<hipEvent_t> ev(2 * total * rounds);
     for (hipEvent_t &e : ev) HIPCHK(c, hipEventCreate(&e));
@@ -715,8 +815,10 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
         for (const auto &to : order) {
             const OpExec &e = ex[to.first][to.second];
             hipStream_t s = mode == GACER_MODE_SEQUENTIAL ? s0 : c->tenants[to.first].stream;
-            if (plan)
+            if (plan) {
                 for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
+                if (e.pre_record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.pre_record], s));
+            }
             for (size_t j = 0; j < e.chunks.size(); ++j) {
                 const int phases = enqueue(e.chunks[j], s, true).phases;
                 for (int ph = 1; ph <= phases; ++ph) {

@@ -189,6 +189,22 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         ksx = tap - kr * a.kw;
     }
 
+    // gather variant, short K: decode k -> (byte offset inside the window, tap row, tap col) once per workgroup
+    constexpr int KTAB = LOAD == LOAD_GATHER ? 256 : 1;
+    __shared__ int ktab_delta[KTAB], ktab_rq[KTAB];
+    const bool use_ktab = LOAD == LOAD_GATHER && a.K <= KTAB;
+    if constexpr (LOAD == LOAD_GATHER) {
+        if (use_ktab) {
+            for (int k = tid; k < a.K; k += THREADS) {
+                const int tap = k / a.Cin, ci = k - tap * a.Cin;
+                const int r = tap / a.kw, q = tap - r * a.kw;
+                ktab_delta[k] = (int)((((int64_t)r * a.W + q) * a.x_pix + ci) * ESZ);
+                ktab_rq[k] = (r << 8) | q;
+            }
+            __syncthreads();
+        }
+    }
+
     uint4 ra[2][AV], rb[2][BREG];
 
     // loads the next K block of this thread (blocks are requested in ascending order, one call per block)
@@ -199,10 +215,20 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 const int k = kv + e;
-                const int tap = k / a.Cin, ci = k - tap * a.Cin;
-                const int r = (tap / a.kw) & 31, q = (tap - (tap / a.kw) * a.kw) & 31;
                 const bool k_ok = k < k_end;
-                const unsigned delta = (unsigned)((((int64_t)r * a.W + q) * a.x_pix + ci) * ESZ);
+                int r, q;
+                unsigned delta;
+                if (use_ktab) {                 // short K (stem convolutions): k -> (offset, taps) from the LDS table
+                    const int kc = k < KTAB ? k : KTAB - 1;
+                    delta = (unsigned)ktab_delta[kc];
+                    r = ktab_rq[kc] >> 8;
+                    q = ktab_rq[kc] & 255;
+                } else {
+                    const int tap = k / a.Cin, ci = k - tap * a.Cin;
+                    r = (tap / a.kw) & 31;
+                    q = (tap - (tap / a.kw) * a.kw) & 31;
+                    delta = (unsigned)((((int64_t)r * a.W + q) * a.x_pix + ci) * ESZ);
+                }
 #pragma unroll
                 for (int i = 0; i < AV; ++i) {
                     const bool ok = k_ok && ((a_hm[i] >> r) & (a_wm[i] >> q) & 1u);
@@ -458,8 +484,13 @@ __global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
     const int64_t idx = (int64_t)blockIdx.x * THREADS + threadIdx.x;
     if (idx >= total) return;
     const int m = a.m_lo + (int)(idx / Nl), n = a.n_lo + (int)(idx % Nl);
-    float v = a.ws[idx];
-    for (int q = 1; q < a.ksplit; ++q) v = __fadd_rn(v, a.ws[q * total + idx]);
+    float p[16];                               // all slice loads are issued before the first add (ksplit <= 16)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) p[q] = q < a.ksplit ? a.ws[q * total + idx] : 0.f;
+    float v = p[0];
+#pragma unroll
+    for (int q = 1; q < 16; ++q)
+        if (q < a.ksplit) v = __fadd_rn(v, p[q]);
     v = __fmaf_rn(v, a.alpha, a.bias ? a.bias[n] : 0.f);
     const int64_t o = (int64_t)m * a.y_row + n;
     if (a.res) v = __fadd_rn(v, load_in((const T *)a.res, o));

@@ -95,7 +95,7 @@ class Session:
 
     # -- plan ------------------------------------------------------------------------------------
     def set_plan(self, splits=(), syncs=()):
-        """splits: iterable of (tenant, op, axis-name, factor); syncs: (src_t, src_op, dst_t, dst_op)."""
+        """splits: iterable of (tenant, op, axis-name, factor); syncs: (src_t, src_op, dst_t, dst_op[, when])."""
         sp = (B.gacer_split * max(1, len(splits)))(*[B.gacer_split(t, o, AXIS[a], f) for (t, o, a, f) in splits])
         sy = (B.gacer_sync * max(1, len(syncs)))(*[B.gacer_sync(*e) for e in syncs])
         plan = B.gacer_plan(len(splits), sp, len(syncs), sy)
@@ -110,7 +110,7 @@ class Session:
         out = C.POINTER(B.gacer_plan)()
         B.check(self.ctx, B.gacer_plan_from_pointers(self.ctx, flat, n_ptr, C.byref(out)))
         edges = [(out.contents.sync[i].src_tenant, out.contents.sync[i].src_op, out.contents.sync[i].dst_tenant,
-                  out.contents.sync[i].dst_op) for i in range(out.contents.n_sync)]
+                  out.contents.sync[i].dst_op, out.contents.sync[i].when) for i in range(out.contents.n_sync)]
         B.gacer_plan_free(out)
         return edges
 
@@ -133,6 +133,13 @@ class Session:
         ms = (C.c_float * rounds)()
         B.check(self.ctx, B.gacer_run(self.ctx, mode, rounds, ms))
         return list(ms)
+
+    def capture(self, mode=B.GACER_MODE_PLAN):
+        """Capture one round of ``mode`` into a HIP graph; later run(mode) calls replay it."""
+        B.check(self.ctx, B.gacer_capture(self.ctx, mode))
+
+    def release_graphs(self):
+        B.check(self.ctx, B.gacer_release_graphs(self.ctx))
 
     def issue_stats(self):
         """(host milliseconds spent enqueueing, operator launches enqueued) of the last run()."""
@@ -190,7 +197,8 @@ class Session:
         pl = out.contents
         inv = {v: k for k, v in AXIS.items()}
         splits = [(pl.split[i].tenant, pl.split[i].op, inv[pl.split[i].axis], pl.split[i].factor) for i in range(pl.n_split)]
-        syncs = [(pl.sync[i].src_tenant, pl.sync[i].src_op, pl.sync[i].dst_tenant, pl.sync[i].dst_op) for i in range(pl.n_sync)]
+        syncs = [(pl.sync[i].src_tenant, pl.sync[i].src_op, pl.sync[i].dst_tenant, pl.sync[i].dst_op, pl.sync[i].when)
+                 for i in range(pl.n_sync)]
         B.gacer_plan_free(out)
         P = [[ptrs[t * n_ptr.value + j] for j in range(n_ptr.value)] for t in range(len(self.tenants))]
         return splits, syncs, P, R.value
