@@ -235,6 +235,14 @@ gacer_status gacer_launch_count(gacer_ctx *ctx, int mode, int *count);
 gacer_status gacer_capture(gacer_ctx *ctx, int mode);
 gacer_status gacer_release_graphs(gacer_ctx *ctx);
 
+/*
+ * Multi-tenant deployment model of Section 2.1: with enable != 0, gacer_run in the plan and stream-parallel
+ * modes enqueues every tenant's stream from its own host thread (the caller's thread takes tenant 0), which
+ * multiplies the launch rate when many small-kernel tenants make the issue loop the bottleneck.  Results and
+ * ordering guarantees are unchanged.  Needs a distinct stream per tenant (otherwise the call runs single-threaded).
+ */
+gacer_status gacer_set_issue_threads(gacer_ctx *ctx, int enable);
+
 /* Host cost of the issue loop (Section 4.2, "more operators ... more CPU operators issuing overhead"): wall time
  * the last gacer_run spent enqueueing its rounds, before it started to wait, and the number of operator
  * launches it enqueued. */

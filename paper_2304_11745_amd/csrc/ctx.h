@@ -56,6 +56,7 @@ struct Ctx {
     std::vector<hipEvent_t> join_events;            // one per tenant
     std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
     hipGraphExec_t graph_exec[3] = {nullptr, nullptr, nullptr};   // captured round per mode (optional)
+    bool issue_threads = false;                     // one host thread per tenant enqueues that tenant's stream
     double last_issue_ms = 0;                       // host time the last gacer_run spent enqueueing
     int last_issue_launches = 0;
     std::string err;

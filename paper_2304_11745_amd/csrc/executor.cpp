@@ -6,7 +6,11 @@
 // round, so the GPU does not idle while the CPU synchronises (the overhead analysed around Eq. 8
 // shrinks to the device-side wait).
 #include <algorithm>
+#include <atomic>
 #include <chrono>
+#include <memory>
+#include <mutex>
+#include <thread>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -716,6 +720,120 @@ gacer_status gacer_release_graphs(gacer_ctx *c)
     return GACER_OK;
 }
 
+// One host thread per tenant (Section 2.1: every tenant's DFG is wrapped into a processing thread that feeds
+// its own stream).  Threads enqueue independently; the only host-side coupling is that an event must have been
+// recorded (by its owner thread) before another thread may enqueue a wait on it, tracked with generation counters.
+namespace {
+struct ThreadedIssue {
+    Ctx *c;
+    int mode, rounds;
+    std::atomic<long> fork_gen{0};
+    std::unique_ptr<std::atomic<long>[]> ev_gen, join_gen;
+    std::atomic<int> failed{0};
+    std::mutex err_mu;
+    std::string err;
+
+    void fail_with(const char *what, hipError_t e)
+    {
+        std::lock_guard<std::mutex> g(err_mu);
+        if (!failed.exchange(1)) err = std::string(what) + " failed: " + hipGetErrorString(e);
+    }
+    bool wait_gen(const std::atomic<long> &g, long need) const
+    {
+        while (g.load(std::memory_order_acquire) < need) {
+            if (failed.load(std::memory_order_relaxed)) return false;
+            std::this_thread::yield();
+        }
+        return true;
+    }
+#define TI_CHK(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { fail_with(#call, e_); return false; } } while (0)
+    // enqueues tenant t's operators of round r on its stream
+    bool issue_tenant(int t, int r)
+    {
+        const bool plan = (mode == GACER_MODE_PLAN);
+        const auto &ex = plan ? c->plan_exec[t] : c->plain_exec[t];
+        hipStream_t s = c->tenants[t].stream;
+        for (const OpExec &e : ex) {
+            if (plan) {
+                for (int w : e.waits) {
+                    if (!wait_gen(ev_gen[w], r + 1)) return false;
+                    TI_CHK(hipStreamWaitEvent(s, c->sync_events[w], 0));
+                }
+                if (e.pre_record >= 0) {
+                    TI_CHK(hipEventRecord(c->sync_events[e.pre_record], s));
+                    ev_gen[e.pre_record].store(r + 1, std::memory_order_release);
+                }
+            }
+            for (const Launch &l : e.chunks) enqueue(l, s, false);
+            if (plan && e.record >= 0) {
+                TI_CHK(hipEventRecord(c->sync_events[e.record], s));
+                ev_gen[e.record].store(r + 1, std::memory_order_release);
+            }
+        }
+        return true;
+    }
+    void worker(int t)
+    {
+        if (hipSetDevice(c->device) != hipSuccess) { fail_with("hipSetDevice", hipGetLastError()); return; }
+        const int NT = (int)c->tenants.size();
+        for (int r = 0; r < rounds; ++r) {
+            if (!wait_gen(fork_gen, r + 1)) return;
+            hipError_t e = hipStreamWaitEvent(c->tenants[t].stream, c->join_events[NT], 0);
+            if (e != hipSuccess) { fail_with("hipStreamWaitEvent(fork)", e); return; }
+            if (!issue_tenant(t, r)) return;
+            e = hipEventRecord(c->join_events[t], c->tenants[t].stream);
+            if (e != hipSuccess) { fail_with("hipEventRecord(join)", e); return; }
+            join_gen[t].store(r + 1, std::memory_order_release);
+        }
+    }
+    // the calling thread plays tenant 0 and owns the fork / join of every round
+    bool lead()
+    {
+        const int NT = (int)c->tenants.size();
+        hipStream_t s0 = c->tenants[0].stream;
+        for (int r = 0; r < rounds; ++r) {
+            TI_CHK(hipEventRecord(c->t_start[r], s0));
+            TI_CHK(hipEventRecord(c->join_events[NT], s0));
+            fork_gen.store(r + 1, std::memory_order_release);
+            if (!issue_tenant(0, r)) return false;
+            for (int t = 1; t < NT; ++t) {
+                if (!wait_gen(join_gen[t], r + 1)) return false;
+                TI_CHK(hipStreamWaitEvent(s0, c->join_events[t], 0));
+            }
+            TI_CHK(hipEventRecord(c->t_end[r], s0));
+        }
+        return true;
+    }
+#undef TI_CHK
+};
+}  // namespace
+
+static gacer_status run_threaded(Ctx *c, int mode, int rounds)
+{
+    const int NT = (int)c->tenants.size();
+    ThreadedIssue ti;
+    ti.c = c; ti.mode = mode; ti.rounds = rounds;
+    const size_t ne = std::max<size_t>(1, c->sync_events.size());
+    ti.ev_gen.reset(new std::atomic<long>[ne]);
+    ti.join_gen.reset(new std::atomic<long>[NT]);
+    for (size_t i = 0; i < ne; ++i) ti.ev_gen[i].store(0);
+    for (int t = 0; t < NT; ++t) ti.join_gen[t].store(0);
+    std::vector<std::thread> workers;
+    for (int t = 1; t < NT; ++t) workers.emplace_back([&ti, t] { ti.worker(t); });
+    const bool ok = ti.lead();
+    if (!ok) ti.failed.store(1);
+    for (std::thread &w : workers) w.join();
+    if (ti.failed.load()) return fail(c, GACER_EHIP, "%s", ti.err.empty() ? "threaded issue failed" : ti.err.c_str());
+    return GACER_OK;
+}
+
+gacer_status gacer_set_issue_threads(gacer_ctx *c, int enable)
+{
+    if (!c) return GACER_EINVAL;
+    c->issue_threads = enable != 0;
+    return GACER_OK;
+}
+
 gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
 {
     if (!c) return GACER_EINVAL;
@@ -726,7 +844,15 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
     if (st != GACER_OK) return st;
     hipStream_t s0 = c->tenants[0].stream;
     const auto host_t0 = std::chrono::steady_clock::now();
-    for (int r = 0; r < rounds; ++r) {
+    bool threaded = c->issue_threads && mode != GACER_MODE_SEQUENTIAL && !c->graph_exec[mode] && c->tenants.size() > 1;
+    for (size_t a = 0; threaded && a < c->tenants.size(); ++a)          // threads need one stream per tenant
+        for (size_t b = a + 1; b < c->tenants.size(); ++b)
+            if (c->tenants[a].stream == c->tenants[b].stream) threaded = false;
+    if (threaded) {
+        st = run_threaded(c, mode, rounds);
+        if (st != GACER_OK) { (void)hipDeviceSynchronize(); return st; }
+    }
+    for (int r = 0; r < rounds && !threaded; ++r) {
         HIPCHK(c, hipEventRecord(c->t_start[r], s0));
         if (c->graph_exec[mode]) {
             HIPCHK(c, hipGraphLaunch(c->graph_exec[mode], s0));

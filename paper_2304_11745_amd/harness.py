@@ -138,6 +138,10 @@ class Session:
         """Capture one round of ``mode`` into a HIP graph; later run(mode) calls replay it."""
         B.check(self.ctx, B.gacer_capture(self.ctx, mode))
 
+    def set_issue_threads(self, enable=True):
+        """One host thread per tenant enqueues that tenant's stream (Section 2.1 deployment model)."""
+        B.check(self.ctx, B.gacer_set_issue_threads(self.ctx, 1 if enable else 0))
+
     def release_graphs(self):
         B.check(self.ctx, B.gacer_release_graphs(self.ctx))
 
@@ -202,6 +206,43 @@ class Session:
         B.gacer_plan_free(out)
         P = [[ptrs[t * n_ptr.value + j] for j in range(n_ptr.value)] for t in range(len(self.tenants))]
         return splits, syncs, P, R.value
+
+    def refine_plan(self, rows, base_splits=(), base_syncs=(), rounds=12, min_gain=0.005, log=None):
+        """Measured greedy refinement of a plan (the spatial step of Section 4.2 with the GPU as the judge):
+        tenants in order of profiled time; for each, decompose its heaviest operators (top quartile of isolated
+        time) batch x2, batch x4 or Cout x2 and keep the option that lowers the measured makespan by more than
+        ``min_gain``.  Returns (splits, syncs, makespan_ms).  Every candidate is a valid plan, so outputs stay
+        bit-identical; only the schedule changes."""
+        import statistics
+        T = [[0.0] * len(t.ops) for t in self.tenants]
+        for r in rows:
+            if r.tenant >= 0 and r.factor == 1:
+                T[r.tenant][r.op] = r.ms
+
+        def measure(splits, syncs):
+            self.set_plan(splits, syncs)
+            self.run(B.GACER_MODE_PLAN, 3)
+            return statistics.median(self.run(B.GACER_MODE_PLAN, rounds))
+        best_sp, best_sy = list(base_splits), list(base_syncs)
+        best = measure(best_sp, best_sy)
+        order = sorted(range(len(self.tenants)), key=lambda i: -sum(T[i]))
+        for ti in order:
+            taken = {(t, o) for (t, o, _, _) in best_sp}
+            thr = sorted(T[ti])[int(len(T[ti]) * 0.75)] if T[ti] else 0.0
+            options = []
+            for axis, f in (("batch", 2), ("batch", 4), ("cout", 2)):
+                sp = [x for x in self.uniform_splits(axis, f, tenants=[ti]) if T[ti][x[1]] >= thr and (x[0], x[1]) not in taken]
+                if sp:
+                    options.append((f"{self.tenants[ti].name}[{ti}] {axis}x{f}", sp))
+            for name, sp in options:
+                ms = measure(best_sp + sp, best_sy)
+                if log:
+                    log(f"refine: {name}: {ms:.4f} ms (best {best:.4f})")
+                if ms < best * (1.0 - min_gain):
+                    best, best_sp = ms, best_sp + sp
+                    break
+        self.set_plan(best_sp, best_sy)
+        return best_sp, best_sy, best
 
     def close(self):
         if self.ctx:

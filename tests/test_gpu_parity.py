@@ -137,3 +137,26 @@ def test_captured_round_replays_bit_exact(gpu):
     for i in range(len(tenants)):
         assert sess.output_bytes(i) == base[i]
     sess.close()
+
+
+def test_threaded_issue_bit_exact(gpu):
+    """One host thread per tenant (8 tenants, pointers + decomposition): same bits as the single-threaded run."""
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(4, "small")
+    sess = gpu.Session(tenants, data)
+    n_ops = [len(t.ops) for t in tenants]
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    base = [sess.output_bytes(i) for i in range(len(tenants))]
+    sess.set_issue_threads(True)
+    for plan in ("unsplit", "regulated"):
+        if plan == "regulated":
+            sess.set_plan(sess.uniform_splits("cout", 2), sess.edges_from_pointers([[n // 4, n // 2, 3 * n // 4] for n in n_ops]))
+        for mode in (B.GACER_MODE_STREAM_PARALLEL, B.GACER_MODE_PLAN):
+            for rounds in (1, 5):
+                sess.poison_outputs()
+                sess.run(mode, rounds)
+                for i in range(len(tenants)):
+                    assert sess.output_bytes(i) == base[i], f"{plan} mode {mode} rounds {rounds}: tenant {i} differs"
+    sess.set_issue_threads(False)
+    sess.close()
