@@ -69,4 +69,43 @@ template <typename T, int V> __device__ __forceinline__ void st_vec(T *p, int64_
     *(decltype(v.raw) *)(p + i) = v.raw;
 }
 
+
+// Buffer descriptors let every global load be unconditional: a masked element gets an offset beyond the
+// descriptor's range and the hardware returns zero (zero padding of the image border, of the K tail and of
+// ragged tile edges), so the main loop has no branches and loads can stay in flight across MFMA blocks.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+static constexpr unsigned OOB = 0x80000000u;     // tensors are smaller than 2 GiB (checked when tenants load)
+
+// The descriptor must live in scalar registers: its inputs are wave-uniform by construction, which
+// readfirstlane makes visible to the compiler (integer divisions are otherwise computed per lane).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, int64_t bytes)
+{
+    int rec = bytes > 0x7FFFFFFF ? 0x7FFFFFFF : (bytes < 0 ? 0 : (int)bytes);
+    rec = __builtin_amdgcn_readfirstlane(rec);
+    const uint64_t u = (uint64_t)p;
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)u);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(u >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)hi << 32) | lo), 0, rec, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0);
+    return make_uint4((unsigned)v.x, (unsigned)v.y, (unsigned)v.z, (unsigned)v.w);
+}
+__device__ __forceinline__ uint2 buf_load8(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    typedef int i32x2 __attribute__((ext_vector_type(2)));
+    const i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)off, 0, 0);
+    return make_uint2((unsigned)v.x, (unsigned)v.y);
+}
+template <typename T> __device__ __forceinline__ T buf_load1(__amdgpu_buffer_rsrc_t r, unsigned off);
+template <> __device__ __forceinline__ float buf_load1<float>(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    return __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+}
+template <> __device__ __forceinline__ unsigned short buf_load1<unsigned short>(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    return (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(r, (int)off, 0, 0);
+}
+
 }  // namespace gacer

@@ -280,8 +280,19 @@ static void decide_split(int64_t M, int64_t N, int K, gacer_dtype dtype, int *S,
     const int nkb = (K + bk - 1) / bk;
     const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
     int64_t s = 1;
-    if (tiles < 256) s = std::min<int64_t>(std::min<int64_t>((512 + tiles - 1) / tiles, 16), nkb / 4);
-    if (s < 1) s = 1;
+    if (tiles < 256) {
+        // all workgroups of such a launch are resident at once, so its duration follows the fullest compute unit:
+        // prefer the slice count whose workgroup total sits just below a multiple of the 256 compute units
+        const int64_t smax = std::min<int64_t>(16, nkb / 4);
+        double best = -1.0;
+        for (int64_t q = 1; q <= smax; ++q) {
+            const int64_t wgs = tiles * q;
+            if (wgs > 1024) break;
+            const double fill = (double)wgs / (double)(((wgs + 255) / 256) * 256);
+            const double score = (wgs >= 256 ? 1.0 : (double)wgs / 256.0) * fill - 0.01 * (double)q;   // mild bias to fewer slices
+            if (score > best) { best = score; s = q; }
+        }
+    }
     int per = (int)((nkb + s - 1) / s);
     per += per & 1;
     *kbps = s == 1 ? (1 << 28) : per;

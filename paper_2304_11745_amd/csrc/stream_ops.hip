@@ -63,10 +63,56 @@ __global__ __launch_bounds__(TPB) void dwconv_kernel(StreamArgs a)
 // The 3 x ((TW-1)*S + 3) input window and the 9 weight vectors are loaded once and reused by the TW outputs, which
 // cuts load instructions about three-fold.  Every output is still the same chain of nine fused multiply-adds over
 // taps (r, s) ascending (zero fill outside the image adds exact zeros), so results equal the generic kernel's.
+template <typename T, int V> struct Unpack;
+template <> struct Unpack<float, 4> {
+    static __device__ __forceinline__ void run(const uint4 &r, float *f)
+    {
+        f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float *f)
+    {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+};
+template <> struct Unpack<unsigned short, 8> {
+    static __device__ __forceinline__ void run(const uint4 &r, float *f)
+    {
+        const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { f[2 * q] = __uint_as_float(w[q] << 16); f[2 * q + 1] = __uint_as_float(w[q] & 0xFFFF0000u); }
+    }
+    static __device__ __forceinline__ uint4 pack(const float *f)
+    {
+        uint4 o;
+        o.x = (unsigned)to_bf16(f[0]) | ((unsigned)to_bf16(f[1]) << 16);
+        o.y = (unsigned)to_bf16(f[2]) | ((unsigned)to_bf16(f[3]) << 16);
+        o.z = (unsigned)to_bf16(f[4]) | ((unsigned)to_bf16(f[5]) << 16);
+        o.w = (unsigned)to_bf16(f[6]) | ((unsigned)to_bf16(f[7]) << 16);
+        return o;
+    }
+};
+
+// outputs per thread along W: as many as fit 128 registers (four waves per SIMD keep enough loads in flight)
+template <int V, int S> struct DW_TW { static constexpr int value = S == 2 ? 2 : 4; };
+
+template <> struct Unpack<unsigned short, 4> {
+    static __device__ __forceinline__ void run(const uint2 &r, float *f)
+    {
+        f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xFFFF0000u);
+        f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ uint2 pack(const float *f)
+    {
+        return make_uint2((unsigned)to_bf16(f[0]) | ((unsigned)to_bf16(f[1]) << 16), (unsigned)to_bf16(f[2]) | ((unsigned)to_bf16(f[3]) << 16));
+    }
+};
+template <typename T, int V> struct Raw { typedef uint4 type; static __device__ __forceinline__ uint4 load(__amdgpu_buffer_rsrc_t r, unsigned o) { return buf_load16(r, o); } };
+template <> struct Raw<unsigned short, 4> { typedef uint2 type; static __device__ __forceinline__ uint2 load(__amdgpu_buffer_rsrc_t r, unsigned o) { return buf_load8(r, o); } };
+
 template <typename T, int V, int S>
-__global__ __launch_bounds__(TPB) void dwconv3_kernel(StreamArgs a)
+__global__ __launch_bounds__(TPB, 4) void dwconv3_kernel(StreamArgs a)
 {
-    constexpr int TW = 4, NC = (TW - 1) * S + 3;
+    constexpr int TW = DW_TW<V, S>::value, NC = (TW - 1) * S + 3, ESZ = (int)sizeof(T);
     const int CV = (a.c_hi - a.c_lo) / V;
     const int WT = (a.Wo + TW - 1) / TW;
     const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * WT * CV;
@@ -80,52 +126,65 @@ __global__ __launch_bounds__(TPB) void dwconv3_kernel(StreamArgs a)
     const int n = a.n_lo + (int)(p / a.Ho);
     const int c = a.c_lo + cv * V;
     const int ow0 = wt * TW;
-    const T *x = (const T *)a.x;
-    const T *w = (const T *)a.w;
-    float acc[TW][V];
-#pragma unroll
-    for (int t = 0; t < TW; ++t)
-#pragma unroll
-        for (int q = 0; q < V; ++q) acc[t][q] = 0.f;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, (int64_t)a.N * a.H * a.W * a.C * ESZ);
+    // all loads are issued up front, without branches: positions outside the image read as zero
+    typedef typename Raw<T, V>::type R;
+    R raw[3][NC], wraw[9];
     const int iw0 = ow0 * S - a.pad;
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
         const int ih = oh * S - a.pad + r;
         const bool row_ok = ih >= 0 && ih < a.H;
-        Vec<T, V> in[NC], wv[3];
+        const unsigned row_off = (unsigned)((((int64_t)n * a.H + ih) * a.W * a.C + c) * ESZ);
 #pragma unroll
         for (int j = 0; j < NC; ++j) {
             const int iw = iw0 + j;
-            if (row_ok && iw >= 0 && iw < a.W) in[j] = ld_vec<T, V>(x, (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c);
-            else {
-#pragma unroll
-                for (int q = 0; q < V; ++q) in[j].set(q, 0.f);
-            }
+            const bool ok = row_ok && iw >= 0 && iw < a.W;
+            raw[r][j] = Raw<T, V>::load(xr, ok ? row_off + (unsigned)(iw * a.C * ESZ) : OOB);
         }
+    }
+    const T *w = (const T *)a.w;
 #pragma unroll
-        for (int q3 = 0; q3 < 3; ++q3) wv[q3] = ld_vec<T, V>(w, (int64_t)(r * 3 + q3) * a.C + c);
+    for (int t = 0; t < 9; ++t) wraw[t] = *(const R *)(w + (int64_t)t * a.C + c);
+    float acc[TW][V];
+#pragma unroll
+    for (int t = 0; t < TW; ++t)
+#pragma unroll
+        for (int q = 0; q < V; ++q) acc[t][q] = 0.f;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        float wf[3][V];
+#pragma unroll
+        for (int q3 = 0; q3 < 3; ++q3) Unpack<T, V>::run(wraw[r * 3 + q3], wf[q3]);
+        float in[NC][V];
+#pragma unroll
+        for (int j = 0; j < NC; ++j) Unpack<T, V>::run(raw[r][j], in[j]);
 #pragma unroll
         for (int q3 = 0; q3 < 3; ++q3)
 #pragma unroll
             for (int t = 0; t < TW; ++t)
 #pragma unroll
-                for (int q = 0; q < V; ++q) acc[t][q] = __fmaf_rn(in[t * S + q3].get(q), wv[q3].get(q), acc[t][q]);
+                for (int q = 0; q < V; ++q) acc[t][q] = __fmaf_rn(in[t * S + q3][q], wf[q3][q], acc[t][q]);
     }
+    float bias[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) bias[q] = a.bias ? a.bias[c + q] : 0.f;
 #pragma unroll
     for (int t = 0; t < TW; ++t) {
         const int ow = ow0 + t;
         if (ow >= a.Wo) break;
         const int64_t o = (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.C + c;
-        Vec<T, V> rv, yv;
-        if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
+        float rf[V];
+        if (a.res) Unpack<T, V>::run(*(const R *)((const T *)a.res + o), rf);
+        float out[V];
 #pragma unroll
         for (int q = 0; q < V; ++q) {
             float v = acc[t][q];
-            if (a.bias) v = __fadd_rn(v, a.bias[c + q]);
-            if (a.res) v = __fadd_rn(v, rv.get(q));
-            yv.set(q, activate(v, a.act));
+            if (a.bias) v = __fadd_rn(v, bias[q]);
+            if (a.res) v = __fadd_rn(v, rf[q]);
+            out[q] = activate(v, a.act);
         }
-        st_vec<T, V>((T *)a.y, o, yv);
+        *(R *)((T *)a.y + o) = Unpack<T, V>::pack(out);
     }
 }
 
@@ -321,16 +380,19 @@ static LaunchInfo info(int64_t wgs, const char *kernel)
 LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
 {
     if (a.k == 3 && (a.stride == 1 || a.stride == 2)) {
-        const int64_t tiles = (int64_t)(a.n_hi - a.n_lo) * a.Ho * ((a.Wo + 3) / 4);
-        if (a.dtype == DT_BF16 && vec_ok<unsigned short, 8>(a)) {
-            const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 8) + TPB - 1) / TPB;
+        auto tiles_for = [&](int tw) { return (int64_t)(a.n_hi - a.n_lo) * a.Ho * ((a.Wo + tw - 1) / tw); };
+        if (a.dtype == DT_BF16 && a.C % 4 == 0 && a.c_lo % 4 == 0 && (a.c_hi - a.c_lo) % 4 == 0 && vec_ok<unsigned short, 1>(a)) {
+            // bfloat16: 8-byte vectors (4 channels per lane) keep the window in registers without spilling
+            const int64_t tiles = tiles_for(a.stride == 1 ? DW_TW<4, 1>::value : DW_TW<4, 2>::value);
+            const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 4) + TPB - 1) / TPB;
             if (!dry && g) {
-                if (a.stride == 1) hipLaunchKernelGGL((dwconv3_kernel<unsigned short, 8, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-                else hipLaunchKernelGGL((dwconv3_kernel<unsigned short, 8, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                if (a.stride == 1) hipLaunchKernelGGL((dwconv3_kernel<unsigned short, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                else hipLaunchKernelGGL((dwconv3_kernel<unsigned short, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
             }
             return info(g, "dwconv3x3");
         }
         if (a.dtype == DT_F32 && vec_ok<float, 4>(a)) {
+            const int64_t tiles = tiles_for(a.stride == 1 ? DW_TW<4, 1>::value : DW_TW<4, 2>::value);
             const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 4) + TPB - 1) / TPB;
             if (!dry && g) {
                 if (a.stride == 1) hipLaunchKernelGGL((dwconv3_kernel<float, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
