@@ -28,12 +28,9 @@ static constexpr int THREADS = 256;
 enum { LOAD_VEC = 0, LOAD_GATHER = 1, LOAD_BT = 2, LOAD_TAPS = 3 };
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
-__device__ __forceinline__ unsigned short f32_to_bf16(float f)
+__device__ __forceinline__ unsigned short f32_to_bf16(float f)     // round to nearest even (hardware conversion)
 {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (unsigned short)((u >> 16) | 0x40u);   // NaN stays NaN
-    u += 0x7FFFu + ((u >> 16) & 1u);                                                     // nearest even
-    return (unsigned short)(u >> 16);
+    return __builtin_bit_cast(unsigned short, (__bf16)f);
 }
 
 // exact (erf) GELU; kept out of line so that the unrolled epilogues stay small
@@ -69,6 +66,86 @@ template <> __device__ __forceinline__ void store_out<float>(float *y, int64_t o
 template <> __device__ __forceinline__ void store_out<unsigned short>(unsigned short *y, int64_t o, float v) { y[o] = f32_to_bf16(v); }
 __device__ __forceinline__ float load_in(const float *p, int64_t o) { return p[o]; }
 __device__ __forceinline__ float load_in(const unsigned short *p, int64_t o) { return bf16_to_f32(p[o]); }
+
+// two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
+{
+    const f32x2 f = {lo, hi};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f, bf16x2));
+}
+
+// Activation of EV values; `act` is uniform over the launch, so the branch is taken once per vector.
+template <int EV> __device__ __forceinline__ void act_vec(float *v, int act)
+{
+    if (act == ACT_RELU) {
+#pragma unroll
+        for (int q = 0; q < EV; ++q) v[q] = v[q] > 0.f ? v[q] : 0.f;
+    } else if (act == ACT_RELU6) {
+#pragma unroll
+        for (int q = 0; q < EV; ++q) v[q] = v[q] < 0.f ? 0.f : (v[q] > 6.f ? 6.f : v[q]);
+    } else if (act == ACT_GELU) {
+#pragma unroll
+        for (int q = 0; q < EV; ++q) v[q] = gelu_erf(v[q]);
+    }
+}
+
+// Epilogue of EV consecutive output channels of one row, all inside the launched range and 16-byte aligned:
+// y = act(alpha * v + bias + res), vector loads of bias and residual, one vector store.
+template <int DT>
+__device__ __forceinline__ void finish_vec(const GemmArgs &a, float *v, const typename El<DT>::T *rg, typename El<DT>::T *yg, int64_t o, int n)
+{
+    constexpr int EV = DT == DT_BF16 ? 8 : 4;
+    if (a.bias) {
+#pragma unroll
+        for (int q = 0; q < EV; q += 4) {
+            const float4 b4 = *(const float4 *)(a.bias + n + q);
+            v[q] = __fmaf_rn(v[q], a.alpha, b4.x); v[q + 1] = __fmaf_rn(v[q + 1], a.alpha, b4.y);
+            v[q + 2] = __fmaf_rn(v[q + 2], a.alpha, b4.z); v[q + 3] = __fmaf_rn(v[q + 3], a.alpha, b4.w);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < EV; ++q) v[q] = __fmaf_rn(v[q], a.alpha, 0.f);
+    }
+    if (rg) {
+        if constexpr (DT == DT_BF16) {
+            const uint4 rv = *(const uint4 *)(rg + o);
+            const unsigned rw[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                v[2 * q] = __fadd_rn(v[2 * q], __uint_as_float(rw[q] << 16));
+                v[2 * q + 1] = __fadd_rn(v[2 * q + 1], __uint_as_float(rw[q] & 0xFFFF0000u));
+            }
+        } else {
+            const float4 rv = *(const float4 *)(rg + o);
+            v[0] = __fadd_rn(v[0], rv.x); v[1] = __fadd_rn(v[1], rv.y); v[2] = __fadd_rn(v[2], rv.z); v[3] = __fadd_rn(v[3], rv.w);
+        }
+    }
+    act_vec<EV>(v, a.act);
+    if constexpr (DT == DT_BF16)
+        *(uint4 *)(yg + o) = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    else
+        *(float4 *)(yg + o) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+// Ragged or unaligned tail: element by element (rare: odd channel counts, unaligned channel chunks).
+template <int DT>
+__device__ __noinline__ void finish_one(float v, float alpha, const float *bias, int act, const typename El<DT>::T *rg,
+                                        typename El<DT>::T *yg, int64_t o, int n, int n_hi)
+{
+    if (n >= n_hi) return;
+    float t = __fmaf_rn(v, alpha, bias ? bias[n] : 0.f);
+    if (rg) t = __fadd_rn(t, load_in(rg, o));
+    store_out<typename El<DT>::T>(yg, o, act_apply(t, act));
+}
+template <int DT>
+__device__ __forceinline__ void finish_scalar(const GemmArgs &a, const float *v, const typename El<DT>::T *rg, typename El<DT>::T *yg, int64_t o, int n)
+{
+    constexpr int EV = DT == DT_BF16 ? 8 : 4;
+#pragma unroll
+    for (int q = 0; q < EV; ++q) finish_one<DT>(v[q], a.alpha, a.bias, a.act, rg, yg, o + q, n + q, a.n_hi);
+}
 
 template <int DT, int BM, int BN, int WM, int WN, int KV, int LOAD>
 __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
@@ -338,17 +415,19 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     store_lds(0, ra[0], rb[0]);
     load_global(ra[1], rb[1]);
     __syncthreads();
-    for (int kb = kb_lo; kb < nkb; kb += 2) {
+    int kb = kb_lo;
+    for (; kb + 1 < nkb; kb += 2) {             // whole pairs of blocks; a single loop exit keeps one accumulator set
         load_global(ra[0], rb[0]);
         compute(0);
         store_lds(1, ra[1], rb[1]);
         __syncthreads();
-        if (kb + 1 >= nkb) break;
         load_global(ra[1], rb[1]);
         compute(1);
         store_lds(0, ra[0], rb[0]);
         __syncthreads();
     }
+    if (kb < nkb) compute(0);                   // odd block count: the last block already sits in LDS buffer 0
+    __syncthreads();                            // the epilogue reuses the tile buffers
 
     // ---- epilogue ----
     // MFMA leaves element e of a 32x32 tile at row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.  Each wave
@@ -375,7 +454,7 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) stage[((e >> 2) * 8 + lhalf * 4 + (e & 3)) * SROW + lrow] = acc[i][j][e];
             __builtin_amdgcn_wave_barrier();
-#pragma unroll
+#pragma unroll 1
             for (int g = 0; g < GROUPS; ++g) {
                 const int row = erow + g * (64 / LPR);
                 const int m = m0 + wm * (BM / WM) + i * 32 + row;
@@ -400,47 +479,156 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                     continue;
                 }
                 const int64_t o = (int64_t)m * a.y_row + n;
-                if (vec_out && n + EV <= a.n_hi) {
-                    float r[EV];
-                    if (rg) {
-                        if constexpr (DT == DT_BF16) {
-                            const uint4 rv = *(const uint4 *)(rg + o);
-                            const unsigned rw[4] = {rv.x, rv.y, rv.z, rv.w};
-#pragma unroll
-                            for (int q = 0; q < 4; ++q) { r[2 * q] = __uint_as_float(rw[q] << 16); r[2 * q + 1] = __uint_as_float(rw[q] & 0xFFFF0000u); }
-                        } else {
-                            const float4 rv = *(const float4 *)(rg + o);
-                            r[0] = rv.x; r[1] = rv.y; r[2] = rv.z; r[3] = rv.w;
-                        }
-                    }
-#pragma unroll
-                    for (int q = 0; q < EV; ++q) {
-                        float t = __fmaf_rn(v[q], a.alpha, a.bias ? a.bias[n + q] : 0.f);
-                        if (rg) t = __fadd_rn(t, r[q]);
-                        v[q] = act_apply(t, a.act);
-                    }
-                    if constexpr (DT == DT_BF16) {
-                        uint4 ov;
-                        ov.x = (unsigned)f32_to_bf16(v[0]) | ((unsigned)f32_to_bf16(v[1]) << 16);
-                        ov.y = (unsigned)f32_to_bf16(v[2]) | ((unsigned)f32_to_bf16(v[3]) << 16);
-                        ov.z = (unsigned)f32_to_bf16(v[4]) | ((unsigned)f32_to_bf16(v[5]) << 16);
-                        ov.w = (unsigned)f32_to_bf16(v[6]) | ((unsigned)f32_to_bf16(v[7]) << 16);
-                        *(uint4 *)(yg + o) = ov;
-                    } else {
-                        *(float4 *)(yg + o) = make_float4(v[0], v[1], v[2], v[3]);
-                    }
-                } else {
-#pragma unroll
-                    for (int q = 0; q < EV; ++q) {
-                        if (n + q >= a.n_hi) continue;
-                        float t = __fmaf_rn(v[q], a.alpha, a.bias ? a.bias[n + q] : 0.f);
-                        if (rg) t = __fadd_rn(t, load_in(rg, o + q));
-                        store_out<T>(yg, o + q, act_apply(t, a.act));
-                    }
-                }
+                if (vec_out && n + EV <= a.n_hi) finish_vec<DT>(a, v, rg, yg, o, n);
+                else finish_scalar<DT>(a, v, rg, yg, o, n);
             }
             __builtin_amdgcn_wave_barrier();
         }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Row-streaming variant for pointwise (1x1, unpadded) convolutions and plain GEMMs with a short K: these
+// are bound by HBM traffic, not by the matrix cores.  A wavefront owns 32 complete output rows: it reads
+// its A fragments straight from global memory in MFMA operand layout (no LDS round trip, no workgroup
+// barrier in the loop), takes the B fragments of all 32*TN output channels from an LDS copy made once per
+// workgroup, and turns the accumulators through a private LDS patch so that residual loads and output
+// stores are contiguous 16-byte vectors along the channel axis, written back to back by the same wave.
+// Every accumulator is the same MFMA chain over ascending 32-byte k groups as in igemm_kernel, so both
+// kernels produce the same bits.
+template <int DT, int TN>
+__global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
+{
+    typedef typename El<DT>::T T;
+    constexpr int VEC = El<DT>::VEC;
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int EV = DT == DT_BF16 ? 8 : 4;
+    constexpr int HALF = 64;                          // staged columns per pass
+    constexpr int SROW = HALF + 4;                    // floats per staged row
+    extern __shared__ __align__(16) unsigned char dyn_smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int kg = (a.K * ESZ + 31) / 32;             // 32-byte k groups
+    const int kg4 = (kg + 3) & ~3;
+    const int rowb = kg4 * 32 + 16;                   // LDS bytes per B row
+    unsigned char *Bs = dyn_smem;
+    float *stage = (float *)(dyn_smem + 32 * TN * rowb) + wave * (32 * SROW);
+
+    const int n0 = a.n_lo + (int)blockIdx.y * (32 * TN);
+    const int m0 = a.m_lo + (int)blockIdx.x * 128 + wave * 32;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, a.x_bytes);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
+
+    // B rows of this channel group -> LDS (zero beyond K and beyond the launched channel range)
+    {
+        const int vpr = kg4 * 2;                      // 16-byte vectors per row
+        for (int idx = tid; idx < 32 * TN * vpr; idx += THREADS) {
+            const int r = idx / vpr, v = idx - r * vpr;
+            const int n = n0 + r, k = v * VEC;
+            const bool ok = n < a.n_hi && k < a.K;
+            *(uint4 *)(Bs + r * rowb + v * 16) = buf_load16(wr, ok ? (unsigned)(((int64_t)n * a.w_row + k) * ESZ) : OOB);
+        }
+    }
+    // this lane's A row
+    unsigned a_off;
+    {
+        const int m = m0 + lrow;
+        const bool ok = m < a.m_hi;
+        const int mm = ok ? m : a.m_lo;
+        const int HoWo = a.Ho * a.Wo;
+        const int img = mm / HoWo, rem = mm - img * HoWo;
+        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        const int64_t e0 = (int64_t)img * a.x_img + ((int64_t)oh * a.stride * a.W + ow * a.stride) * a.x_pix;
+        a_off = ok ? (unsigned)(e0 * ESZ) : OOB;
+    }
+    const unsigned k_bytes = (unsigned)(a.K * ESZ);
+    auto load4 = [&](uint4 *f, int g0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const unsigned kb = (unsigned)((g0 + q) * 32 + lhalf * 16);
+            f[q] = buf_load16(xr, (a_off != OOB && kb < k_bytes) ? a_off + kb : OOB);
+        }
+    };
+
+    f32x16 acc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+    auto compute4 = [&](const uint4 *f, int g0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            uint4 fb[TN];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *(const uint4 *)(Bs + (j * 32 + lrow) * rowb + (g0 + q) * 32 + lhalf * 16);
+            if constexpr (DT == DT_BF16) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[q]), __builtin_bit_cast(bf16x8, fb[j]),
+                                                                     acc[j], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const float av = __uint_as_float(e == 0 ? f[q].x : e == 1 ? f[q].y : e == 2 ? f[q].z : f[q].w);
+                        const float bv = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
+                        acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[j], 0, 0, 0);
+                    }
+            }
+        }
+    };
+
+    uint4 fa[2][4];
+    load4(fa[0], 0);
+    __syncthreads();
+    int g0 = 0;
+    for (; g0 + 4 < kg4; g0 += 8) {
+        load4(fa[1], g0 + 4);
+        compute4(fa[0], g0);
+        load4(fa[0], g0 + 8);
+        compute4(fa[1], g0 + 4);
+    }
+    if (g0 < kg4) compute4(fa[0], g0);
+
+    // ---- epilogue: 64 channels at a time through the wave's LDS patch ----
+    constexpr int CPR = HALF / EV;                    // 16-byte chunks per staged row
+    constexpr int RPI = 64 / CPR;                     // rows per pass of the wave
+    T *yg = (T *)a.y;
+    const T *rg = (const T *)a.res;
+    const bool vec_out = a.y_row % EV == 0 && a.n_lo % EV == 0 && (((uintptr_t)a.y) & 15) == 0 && (((uintptr_t)a.res) & 15) == 0 &&
+                         (((uintptr_t)a.bias) & 15) == 0;
+#pragma unroll
+    for (int hf = 0; hf < (TN + 1) / 2; ++hf) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = hf * 2 + jj;
+            if (j < TN) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) stage[((e >> 2) * 8 + lhalf * 4 + (e & 3)) * SROW + jj * 32 + lrow] = acc[j < TN ? j : 0][e];
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        constexpr int width_full = HALF;
+        const int width = (hf * 2 + 1 < TN) ? width_full : 32;
+#pragma unroll 1
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int row = it * RPI + lane / CPR, col = (lane % CPR) * EV;
+            const int m = m0 + row, n = n0 + hf * HALF + col;
+            float v[EV];
+#pragma unroll
+            for (int q = 0; q < EV; q += 4) {
+                const float4 t4 = *(const float4 *)(stage + row * SROW + col + q);
+                v[q] = t4.x; v[q + 1] = t4.y; v[q + 2] = t4.z; v[q + 3] = t4.w;
+            }
+            if (col >= width || m >= a.m_hi || n >= a.n_hi) continue;
+            const int64_t o = (int64_t)m * a.y_row + n;
+            if (vec_out && n + EV <= a.n_hi) finish_vec<DT>(a, v, rg, yg, o, n);
+            else finish_scalar<DT>(a, v, rg, yg, o, n);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // Second pass of a split-K operator: out = act(alpha * (s0 + s1 + ... ) + bias + res), slices added in
@@ -513,6 +701,57 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     return li;
 }
 
+// rowgemm_kernel is taken when the operator is a single-tap, unpadded, unsplit product whose rows are at most
+// 512 bytes of K: properties of the operator, not of the launched sub-range, so every chunk of an operator
+// takes the same path as its unsplit launch.
+static bool rows_eligible(const GemmArgs &a, int esz, bool vec_ok)
+{
+    return vec_ok && !a.b_trans && a.ksplit == 1 && a.kh == 1 && a.kw == 1 && a.pad == 0 && a.zb * a.zh == 1 && a.z_lo == 0 &&
+           (int64_t)a.K * esz <= 512;
+}
+static int rows_lds(int tn, int K, int esz)
+{
+    const int kg4 = (((K * esz + 31) / 32) + 3) & ~3;
+    return 32 * tn * (kg4 * 32 + 16) + 4 * 32 * 68 * 4;
+}
+
+template <int DT, int TN>
+static LaunchInfo go_rows(const GemmArgs &a, hipStream_t s, bool dry, int groups)
+{
+    LaunchInfo li;
+    const int M = a.m_hi - a.m_lo;
+    li.workgroups = ((M + 127) / 128) * groups;
+    li.threads = THREADS;
+    li.lds_bytes = rows_lds(TN, a.K, (int)sizeof(typename El<DT>::T));
+    const int by_lds = (160 * 1024) / li.lds_bytes;
+    li.wg_per_cu = by_lds < 8 ? by_lds : 8;
+    static const std::string name = std::string("rowgemm_") + (DT == DT_BF16 ? "bf16" : "f32") + "_x" + std::to_string(32 * TN);
+    li.kernel = name.c_str();
+    li.phases = 1;
+    if (dry || li.workgroups == 0) return li;
+    hipLaunchKernelGGL((rowgemm_kernel<DT, TN>), dim3((M + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, a);
+    return li;
+}
+
+template <int DT>
+static LaunchInfo pick_rows(const GemmArgs &a, hipStream_t s, bool dry)
+{
+    const int esz = (int)sizeof(typename El<DT>::T);
+    const int N = a.n_hi - a.n_lo, t32 = (N + 31) / 32;
+    int tn_max = 6;
+    while (tn_max > 1 && rows_lds(tn_max, a.K, esz) > 64 * 1024) --tn_max;
+    const int groups = (t32 + tn_max - 1) / tn_max;
+    const int tn = (t32 + groups - 1) / groups;
+    switch (tn) {
+    case 1: return go_rows<DT, 1>(a, s, dry, groups);
+    case 2: return go_rows<DT, 2>(a, s, dry, groups);
+    case 3: return go_rows<DT, 3>(a, s, dry, groups);
+    case 4: return go_rows<DT, 4>(a, s, dry, groups);
+    case 5: return go_rows<DT, 5>(a, s, dry, groups);
+    default: return go_rows<DT, 6>(a, s, dry, groups);
+    }
+}
+
 template <int DT>
 static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
 {
@@ -520,6 +759,10 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
     const bool vec_ok = (a.Cin % VEC == 0) && (a.x_pix % VEC == 0) && (a.x_img % VEC == 0) && (a.w_row % VEC == 0) &&
                         (a.x_zb % VEC == 0) && (a.x_zh % VEC == 0) && (a.w_zb % VEC == 0) && (a.w_zh % VEC == 0) &&
                         (((uintptr_t)a.x) % 16 == 0) && (((uintptr_t)a.w) % 16 == 0);
+    if (rows_eligible(a, (int)sizeof(typename El<DT>::T), vec_ok)) {
+        if (phase == 2) { LaunchInfo li = pick_rows<DT>(a, s, true); return li; }
+        return pick_rows<DT>(a, s, dry);
+    }
     const int M = a.m_hi - a.m_lo, N = a.n_hi - a.n_lo;
     const int64_t z = (int64_t)a.zb * a.zh * (a.b_trans ? 1 : a.ksplit);
     // Tile choice is free (it never changes the bits): narrowest N padding first, then the largest
