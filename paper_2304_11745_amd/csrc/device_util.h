@@ -8,20 +8,17 @@ namespace gacer {
 __device__ __forceinline__ float ld_f32(const float *p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float ld_f32(const unsigned short *p, int64_t i) { return __uint_as_float(((unsigned)p[i]) << 16); }
 
-__device__ __forceinline__ unsigned short to_bf16(float f)
+__device__ __forceinline__ unsigned short to_bf16(float f)      // round to nearest even (hardware conversion)
 {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (unsigned short)((u >> 16) | 0x40u);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
+    return __builtin_bit_cast(unsigned short, (__bf16)f);
 }
 __device__ __forceinline__ void st_f32(float *p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void st_f32(unsigned short *p, int64_t i, float v) { p[i] = to_bf16(v); }
 
 __device__ __forceinline__ float activate(float v, int act)
 {
-    if (act == ACT_RELU) return v > 0.f ? v : 0.f;
-    if (act == ACT_RELU6) return v < 0.f ? 0.f : (v > 6.f ? 6.f : v);
+    if (act == ACT_RELU) return __builtin_fmaxf(v, 0.f);
+    if (act == ACT_RELU6) return __builtin_amdgcn_fmed3f(v, 0.f, 6.f);
     if (act == ACT_GELU) return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
     return v;
 }

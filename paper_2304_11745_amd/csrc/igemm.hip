@@ -41,8 +41,8 @@ __device__ __attribute__((noinline)) float gelu_erf(float v)
 
 __device__ __forceinline__ float act_apply(float v, int act)
 {
-    if (act == ACT_RELU) return v > 0.f ? v : 0.f;
-    if (act == ACT_RELU6) return v < 0.f ? 0.f : (v > 6.f ? 6.f : v);
+    if (act == ACT_RELU) return __builtin_fmaxf(v, 0.f);
+    if (act == ACT_RELU6) return __builtin_amdgcn_fmed3f(v, 0.f, 6.f);
     if (act == ACT_GELU) return gelu_erf(v);
     return v;
 }
@@ -79,12 +79,12 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
 // Activation of EV values; `act` is uniform over the launch, so the branch is taken once per vector.
 template <int EV> __device__ __forceinline__ void act_vec(float *v, int act)
 {
-    if (act == ACT_RELU) {
+    if (act == ACT_RELU) {                        // clamps as single v_max / v_med3 instructions, no divergent branches
 #pragma unroll
-        for (int q = 0; q < EV; ++q) v[q] = v[q] > 0.f ? v[q] : 0.f;
+        for (int q = 0; q < EV; ++q) v[q] = __builtin_fmaxf(v[q], 0.f);
     } else if (act == ACT_RELU6) {
 #pragma unroll
-        for (int q = 0; q < EV; ++q) v[q] = v[q] < 0.f ? 0.f : (v[q] > 6.f ? 6.f : v[q]);
+        for (int q = 0; q < EV; ++q) v[q] = __builtin_amdgcn_fmed3f(v[q], 0.f, 6.f);
     } else if (act == ACT_GELU) {
 #pragma unroll
         for (int q = 0; q < EV; ++q) v[q] = gelu_erf(v[q]);
@@ -495,7 +495,7 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 // stores are contiguous 16-byte vectors along the channel axis, written back to back by the same wave.
 // Every accumulator is the same MFMA chain over ascending 32-byte k groups as in igemm_kernel, so both
 // kernels produce the same bits.
-template <int DT, int TN>
+template <int DT, int TN, int G>
 __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
 {
     typedef typename El<DT>::T T;
@@ -509,7 +509,8 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int kg = (a.K * ESZ + 31) / 32;             // 32-byte k groups
-    const int kg4 = (kg + 3) & ~3;
+    const int kg4 = (kg + 3) & ~3;                // LDS rows hold whole groups of four
+    const int kgr = (kg + G - 1) / G * G;          // groups walked: G at a time (G = 1 for very short K)
     const int rowb = kg4 * 32 + 16;                   // LDS bytes per B row
     unsigned char *Bs = dyn_smem;
     float *stage = (float *)(dyn_smem + 32 * TN * rowb) + wave * (32 * SROW);
@@ -520,31 +521,33 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
     const __amdgpu_buffer_rsrc_t wr = make_rsrc(a.w, a.w_bytes);
 
     // B rows of this channel group -> LDS (zero beyond K and beyond the launched channel range)
-    {
-        const int vpr = kg4 * 2;                      // 16-byte vectors per row
-        for (int idx = tid; idx < 32 * TN * vpr; idx += THREADS) {
-            const int r = idx / vpr, v = idx - r * vpr;
+    for (int r = tid >> 3; r < 32 * TN; r += THREADS / 8)
+        for (int v = tid & 7; v < kg4 * 2; v += 8) {
             const int n = n0 + r, k = v * VEC;
             const bool ok = n < a.n_hi && k < a.K;
             *(uint4 *)(Bs + r * rowb + v * 16) = buf_load16(wr, ok ? (unsigned)(((int64_t)n * a.w_row + k) * ESZ) : OOB);
         }
-    }
     // this lane's A row
     unsigned a_off;
     {
         const int m = m0 + lrow;
         const bool ok = m < a.m_hi;
         const int mm = ok ? m : a.m_lo;
-        const int HoWo = a.Ho * a.Wo;
-        const int img = mm / HoWo, rem = mm - img * HoWo;
-        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
-        const int64_t e0 = (int64_t)img * a.x_img + ((int64_t)oh * a.stride * a.W + ow * a.stride) * a.x_pix;
+        int64_t e0;
+        if (a.stride == 1 && a.x_img == (int64_t)a.Ho * a.Wo * a.x_pix) {      // dense rows: no index arithmetic
+            e0 = (int64_t)mm * a.x_pix;
+        } else {
+            const int HoWo = a.Ho * a.Wo;
+            const int img = mm / HoWo, rem = mm - img * HoWo;
+            const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+            e0 = (int64_t)img * a.x_img + ((int64_t)oh * a.stride * a.W + ow * a.stride) * a.x_pix;
+        }
         a_off = ok ? (unsigned)(e0 * ESZ) : OOB;
     }
     const unsigned k_bytes = (unsigned)(a.K * ESZ);
     auto load4 = [&](uint4 *f, int g0) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < G; ++q) {
             const unsigned kb = (unsigned)((g0 + q) * 32 + lhalf * 16);
             f[q] = buf_load16(xr, (a_off != OOB && kb < k_bytes) ? a_off + kb : OOB);
         }
@@ -558,7 +561,7 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
 
     auto compute4 = [&](const uint4 *f, int g0) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < G; ++q) {
             uint4 fb[TN];
 #pragma unroll
             for (int j = 0; j < TN; ++j) fb[j] = *(const uint4 *)(Bs + (j * 32 + lrow) * rowb + (g0 + q) * 32 + lhalf * 16);
@@ -580,17 +583,17 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
         }
     };
 
-    uint4 fa[2][4];
+    uint4 fa[2][G];
     load4(fa[0], 0);
     __syncthreads();
     int g0 = 0;
-    for (; g0 + 4 < kg4; g0 += 8) {
-        load4(fa[1], g0 + 4);
+    for (; g0 + G < kgr; g0 += 2 * G) {
+        load4(fa[1], g0 + G);
         compute4(fa[0], g0);
-        load4(fa[0], g0 + 8);
-        compute4(fa[1], g0 + 4);
+        load4(fa[0], g0 + 2 * G);
+        compute4(fa[1], g0 + G);
     }
-    if (g0 < kg4) compute4(fa[0], g0);
+    if (g0 < kgr) compute4(fa[0], g0);
 
     // ---- epilogue: 64 channels at a time through the wave's LDS patch ----
     constexpr int CPR = HALF / EV;                    // 16-byte chunks per staged row
@@ -715,6 +718,13 @@ static int rows_lds(int tn, int K, int esz)
     return 32 * tn * (kg4 * 32 + 16) + 4 * 32 * 68 * 4;
 }
 
+template <int DT, int TN, int G>
+static LaunchInfo go_rows_g(const GemmArgs &a, hipStream_t s, const LaunchInfo &li, int groups)
+{
+    hipLaunchKernelGGL((rowgemm_kernel<DT, TN, G>), dim3((a.m_hi - a.m_lo + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, a);
+    return li;
+}
+
 template <int DT, int TN>
 static LaunchInfo go_rows(const GemmArgs &a, hipStream_t s, bool dry, int groups)
 {
@@ -729,8 +739,8 @@ static LaunchInfo go_rows(const GemmArgs &a, hipStream_t s, bool dry, int groups
     li.kernel = name.c_str();
     li.phases = 1;
     if (dry || li.workgroups == 0) return li;
-    hipLaunchKernelGGL((rowgemm_kernel<DT, TN>), dim3((M + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, a);
-    return li;
+    const int kg = (a.K * (int)sizeof(typename El<DT>::T) + 31) / 32;
+    return kg < 4 ? go_rows_g<DT, TN, 1>(a, s, li, groups) : go_rows_g<DT, TN, 4>(a, s, li, groups);
 }
 
 template <int DT>
@@ -740,8 +750,12 @@ static LaunchInfo pick_rows(const GemmArgs &a, hipStream_t s, bool dry)
     const int N = a.n_hi - a.n_lo, t32 = (N + 31) / 32;
     int tn_max = 6;
     while (tn_max > 1 && rows_lds(tn_max, a.K, esz) > 64 * 1024) --tn_max;
-    const int groups = (t32 + tn_max - 1) / tn_max;
+    int groups = (t32 + tn_max - 1) / tn_max;
+    // few rows: spread the channels over more workgroups until every compute unit has one (A is then re-read from L2)
+    const int wgs_m = (a.m_hi - a.m_lo + 127) / 128;
+    while (groups < t32 && wgs_m * groups < 256) ++groups;
     const int tn = (t32 + groups - 1) / groups;
+    groups = (t32 + tn - 1) / tn;
     switch (tn) {
     case 1: return go_rows<DT, 1>(a, s, dry, groups);
     case 2: return go_rows<DT, 2>(a, s, dry, groups);
