@@ -280,10 +280,12 @@ static void decide_split(int64_t M, int64_t N, int K, gacer_dtype dtype, int *S,
     const int nkb = (K + bk - 1) / bk;
     const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
     int64_t s = 1;
-    if (tiles < 256) {
+    // Measured on whole concurrent rounds: splitting pays only when the unsplit launch would leave more than half of
+    // the compute units empty, and only with slices of at least 8 blocks (the finishing pass costs a kernel boundary).
+    if (tiles < 128) {
         // all workgroups of such a launch are resident at once, so its duration follows the fullest compute unit:
         // prefer the slice count whose workgroup total sits just below a multiple of the 256 compute units
-        const int64_t smax = std::min<int64_t>(16, nkb / 4);
+        const int64_t smax = std::min<int64_t>(16, nkb / 8);
         double best = -1.0;
         for (int64_t q = 1; q <= smax; ++q) {
             const int64_t wgs = tiles * q;

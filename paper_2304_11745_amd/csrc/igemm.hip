@@ -635,26 +635,63 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
 }
 
 // Second pass of a split-K operator: out = act(alpha * (s0 + s1 + ... ) + bias + res), slices added in
-// ascending order.  One thread per output element of the launched sub-range, coalesced along n.
-template <typename T>
+// ascending order.  One thread per FV consecutive output channels of the launched sub-range (FV = 4 when
+// the range and the pointers allow 16-byte accesses), coalesced along n.
+template <typename T, int FV>
 __global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
 {
     const int Nl = a.n_hi - a.n_lo;
     const int64_t total = (int64_t)(a.m_hi - a.m_lo) * Nl;
-    const int64_t idx = (int64_t)blockIdx.x * THREADS + threadIdx.x;
+    const int64_t idx = ((int64_t)blockIdx.x * THREADS + threadIdx.x) * FV;
     if (idx >= total) return;
     const int m = a.m_lo + (int)(idx / Nl), n = a.n_lo + (int)(idx % Nl);
-    float p[16];                               // all slice loads are issued before the first add (ksplit <= 16)
+    float v[FV];
+    if constexpr (FV == 4) {
+        float4 p[16];                          // all slice loads are issued before the first add (ksplit <= 16)
 #pragma unroll
-    for (int q = 0; q < 16; ++q) p[q] = q < a.ksplit ? a.ws[q * total + idx] : 0.f;
-    float v = p[0];
+        for (int q = 0; q < 16; ++q) p[q] = q < a.ksplit ? *(const float4 *)(a.ws + q * total + idx) : make_float4(0.f, 0.f, 0.f, 0.f);
+        v[0] = p[0].x; v[1] = p[0].y; v[2] = p[0].z; v[3] = p[0].w;
 #pragma unroll
-    for (int q = 1; q < 16; ++q)
-        if (q < a.ksplit) v = __fadd_rn(v, p[q]);
-    v = __fmaf_rn(v, a.alpha, a.bias ? a.bias[n] : 0.f);
+        for (int q = 1; q < 16; ++q)
+            if (q < a.ksplit) {
+                v[0] = __fadd_rn(v[0], p[q].x); v[1] = __fadd_rn(v[1], p[q].y);
+                v[2] = __fadd_rn(v[2], p[q].z); v[3] = __fadd_rn(v[3], p[q].w);
+            }
+    } else {
+        float p[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) p[q] = q < a.ksplit ? a.ws[q * total + idx] : 0.f;
+        v[0] = p[0];
+#pragma unroll
+        for (int q = 1; q < 16; ++q)
+            if (q < a.ksplit) v[0] = __fadd_rn(v[0], p[q]);
+    }
     const int64_t o = (int64_t)m * a.y_row + n;
-    if (a.res) v = __fadd_rn(v, load_in((const T *)a.res, o));
-    store_out<T>((T *)a.y, o, act_apply(v, a.act));
+#pragma unroll
+    for (int e = 0; e < FV; ++e) {
+        float t = __fmaf_rn(v[e], a.alpha, a.bias ? a.bias[n + e] : 0.f);
+        if (a.res) t = __fadd_rn(t, load_in((const T *)a.res, o + e));
+        v[e] = act_apply(t, a.act);
+    }
+    if constexpr (FV == 4 && sizeof(T) == 4) {
+        *(float4 *)((float *)a.y + o) = make_float4(v[0], v[1], v[2], v[3]);
+    } else if constexpr (FV == 4) {
+        *(uint2 *)((unsigned short *)a.y + o) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+    } else {
+        store_out<T>((T *)a.y, o, v[0]);
+    }
+}
+
+template <typename T>
+static void launch_finish(const GemmArgs &a, hipStream_t s)
+{
+    const int Nl = a.n_hi - a.n_lo;
+    const int64_t total = (int64_t)(a.m_hi - a.m_lo) * Nl;
+    const bool v4 = Nl % 4 == 0 && a.n_lo % 4 == 0 && a.y_row % 4 == 0 && (((uintptr_t)a.ws) & 15) == 0 && (((uintptr_t)a.y) & 15) == 0;
+    if (v4)
+        hipLaunchKernelGGL((splitk_finish<T, 4>), dim3((unsigned)((total / 4 + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
+    else
+        hipLaunchKernelGGL((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -683,10 +720,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     if (dry || li.workgroups == 0) return li;
     dim3 grid(tiles_m * tiles_n, ks, z), block(THREADS);
     if (phase == 2) {
-        if (ks > 1) {
-            const int64_t total = (int64_t)(a.m_hi - a.m_lo) * (a.n_hi - a.n_lo);
-            hipLaunchKernelGGL((splitk_finish<T>), dim3((unsigned)((total + THREADS - 1) / THREADS)), block, 0, s, a);
-        }
+        if (ks > 1) launch_finish<T>(a, s);
         return li;
     }
     if (a.b_trans)
@@ -697,10 +731,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
-    if (ks > 1 && phase == 0) {
-        const int64_t total = (int64_t)(a.m_hi - a.m_lo) * (a.n_hi - a.n_lo);
-        hipLaunchKernelGGL((splitk_finish<T>), dim3((unsigned)((total + THREADS - 1) / THREADS)), block, 0, s, a);
-    }
+    if (ks > 1 && phase == 0) launch_finish<T>(a, s);
     return li;
 }
 
@@ -779,30 +810,42 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
     }
     const int M = a.m_hi - a.m_lo, N = a.n_hi - a.n_lo;
     const int64_t z = (int64_t)a.zb * a.zh * (a.b_trans ? 1 : a.ksplit);
-    // Tile choice is free (it never changes the bits): narrowest N padding first, then the largest
-    // tile that still gives every compute unit about two workgroups.
+    // Tile choice is free (it never changes the bits): narrowest N padding first, then the cheapest shape.
     auto waste = [&](int bn) { return (double)((N + bn - 1) / bn * bn) / (double)N; };
     int bn = 128;
     if (waste(64) < waste(bn) - 1e-9) bn = 64;
     if (waste(32) < waste(bn) - 1e-9) bn = 32;
     auto wgs = [&](int bm, int bnn) { return (int64_t)((M + bm - 1) / bm) * ((N + bnn - 1) / bnn) * z; };
-    const int64_t want = 512;
-    // fp32: the 128x128 tile needs so many registers that only one wave fits per SIMD; 128x64 is faster.
-    const bool big = DT == DT_BF16;
+    // Cost of a tile shape: workgroups landing on the busiest compute unit x outputs per workgroup / relative
+    // efficiency of the shape.  Measured: bf16 gains from the 128x128 tile (fewer LDS reads per MFMA), the two
+    // smaller shapes are equal; fp32 MFMAs are slow enough that all shapes are equal and only the fill counts.
+    // Fewer workgroups than compute units leaves units idle and hides no latency: penalised.
+    constexpr double e_small = DT == DT_BF16 ? 0.8 : 1.0, e_mid = e_small;
+    auto cost = [&](int bm, int bnn, double eff) {
+        const int64_t w = wgs(bm, bnn);
+        return (double)((w + 255) / 256) * bm * bnn / eff * (w < 256 ? 1.25 : 1.0);
+    };
+    int shape = 0;                               // 0: 64x64, 1: 128x64, 2: 128x128, 3: 128x32
+    if (bn < 64) shape = 3;
+    else {
+        double best = cost(64, 64, e_small);
+        if (cost(128, 64, e_mid) < best * 0.999) { best = cost(128, 64, e_mid); shape = 1; }
+        if (bn == 128 && cost(128, 128, 1.0) < best * 0.999) shape = 2;
+    }
     if (a.b_trans || a.K <= 16 * VEC) {          // short K: 64-byte blocks
-        if (big && bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 4>(a, s, dry, vec_ok, phase);
-        if (bn >= 64) {
-            if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
-            return go<DT, 64, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
+        switch (shape) {
+        case 2: return go<DT, 128, 128, 2, 2, 4>(a, s, dry, vec_ok, phase);
+        case 1: return go<DT, 128, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
+        case 0: return go<DT, 64, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
+        default: return go<DT, 128, 32, 4, 1, 4>(a, s, dry, vec_ok, phase);
         }
-        return go<DT, 128, 32, 4, 1, 4>(a, s, dry, vec_ok, phase);
     }
-    if (big && bn == 128 && wgs(128, 128) >= want) return go<DT, 128, 128, 2, 2, 8>(a, s, dry, vec_ok, phase);
-    if (bn >= 64) {
-        if (wgs(128, 64) >= want) return go<DT, 128, 64, 2, 2, 8>(a, s, dry, vec_ok, phase);
-        return go<DT, 64, 64, 2, 2, 8>(a, s, dry, vec_ok, phase);
+    switch (shape) {
+    case 2: return go<DT, 128, 128, 2, 2, 8>(a, s, dry, vec_ok, phase);
+    case 1: return go<DT, 128, 64, 2, 2, 8>(a, s, dry, vec_ok, phase);
+    case 0: return go<DT, 64, 64, 2, 2, 8>(a, s, dry, vec_ok, phase);
+    default: return go<DT, 128, 32, 4, 1, 8>(a, s, dry, vec_ok, phase);
     }
-    return go<DT, 128, 32, 4, 1, 8>(a, s, dry, vec_ok, phase);
 }
 
 LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry, int phase)
