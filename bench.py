@@ -23,6 +23,32 @@ PEAK = {"f32": 157.3e12, "bf16": 2.5e15}        # dense MFMA FLOP/s, MI355X
 HBM_PEAK = 8.0e12
 
 
+# HBM traffic of the dominant kernel per launch, from two rocprofv3 counter passes (FETCH_SIZE, WRITE_SIZE, KiB per
+# dispatch, scaled by what the same counters read for a plain copy of known size: 2.0 and 1.0).  Valid only for the
+# kernel sources the counters were taken with: the digest below covers them, any change resets `traffic` to null.
+TRAFFIC = {
+    2: {"kernel": "igemm_taps_f32_64x64x32", "fetch_bytes": int(9089.4 * 2.0 * 1024), "write_bytes": int(6076.0 * 1024),
+        "sources_sha256": "1cf520484f7fd9e4a098d524d6a0f031207ee6ebd22472d68bfd996ce22c7dcd"},
+}
+TRAFFIC_SOURCES = ["igemm.hip", "device_util.h", "kernels.h", "executor.cpp"]
+
+
+def sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        with open(os.path.join(ROOT, "paper_2304_11745_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def measured_traffic(config, kernel):
+    t = TRAFFIC.get(config)
+    if not t or t["kernel"] != kernel or t["fetch_bytes"] is None or t["sources_sha256"] != sources_digest():
+        return None
+    return t["fetch_bytes"] + t["write_bytes"]
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -97,10 +123,16 @@ def main():
     ap.add_argument("--scale", default="full", choices=["full", "small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan", default="auto", help="auto | unsplit")
+    ap.add_argument("--only-regulated", action="store_true",
+                    help="time the regulated mode only (profiling runs: every dispatch then belongs to the reported mode)")
+    ap.add_argument("--print-sources-digest", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain copy of known size (256 MiB in, 256 MiB out) three times, as the "
                          "reference dispatch for scaling hardware traffic counters")
     args = ap.parse_args()
+    if args.print_sources_digest:
+        print(sources_digest())
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (tenants shard across GPUs with no exchange); use --gpus 1")
 
@@ -131,8 +163,12 @@ def main():
         plan_info = choose_plan(sess, B, 10)
         log("plan selection:", json.dumps(plan_info))
 
-    seq_ms, seq_rounds = timed_rounds(sess, B.GACER_MODE_SEQUENTIAL, args.steps, args.warmup)
-    par_ms, par_rounds = timed_rounds(sess, B.GACER_MODE_STREAM_PARALLEL, args.steps, args.warmup)
+    if args.only_regulated:
+        seq_ms = par_ms = None
+        seq_rounds = par_rounds = [float("nan")]
+    else:
+        seq_ms, seq_rounds = timed_rounds(sess, B.GACER_MODE_SEQUENTIAL, args.steps, args.warmup)
+        par_ms, par_rounds = timed_rounds(sess, B.GACER_MODE_STREAM_PARALLEL, args.steps, args.warmup)
     reg_ms, reg_rounds = timed_rounds(sess, B.GACER_MODE_PLAN, args.steps, args.warmup)
 
     # per-launch durations of the regulated round, on the streams the kernels run on
@@ -147,11 +183,11 @@ def main():
     if d["flops"] > 0:
         achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": None}
+                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": measured_traffic(args.config, dom)}
     else:
         achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": achieved / (HBM_PEAK / 1e9), "traffic": None}
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": measured_traffic(args.config, dom)}
     roof.update({"kernel": dom, "launches_per_round": d["launches"], "avg_launch_us": avg_ms * 1e3,
                  "share_of_kernel_time": d["ms"] / sum(k["ms"] for k in per_kernel.values())})
 
@@ -166,14 +202,14 @@ def main():
         "config": {"workload": f"configs[{args.config - 1}]: {synth.CONFIG_NAMES[args.config]}" + (" (small)" if args.scale == "small" else ""),
                    "items_per_round": items, "tenants": [f"{t.name}({t.batch})" for t in tenants],
                    "plan": plan_info.get("chosen"), "launches_per_round": sess.launch_count(B.GACER_MODE_PLAN)},
-        "sequential_images_per_s": items / (seq_ms * 1e-3),
-        "stream_parallel_images_per_s": items / (par_ms * 1e-3),
-        "speedup_vs_sequential": seq_ms / reg_ms,
-        "speedup_vs_stream_parallel": par_ms / reg_ms,
+        "sequential_images_per_s": items / (seq_ms * 1e-3) if seq_ms else None,
+        "stream_parallel_images_per_s": items / (par_ms * 1e-3) if par_ms else None,
+        "speedup_vs_sequential": seq_ms / reg_ms if seq_ms else None,
+        "speedup_vs_stream_parallel": par_ms / reg_ms if par_ms else None,
         "makespan_ms_median": {"sequential": statistics.median(seq_rounds), "stream_parallel": statistics.median(par_rounds),
                                "regulated": statistics.median(reg_rounds)},
-        "mfma_frac_of_peak": {"sequential": 2 * macs / (seq_ms * 1e-3) / PEAK[dtype],
-                              "stream_parallel": 2 * macs / (par_ms * 1e-3) / PEAK[dtype],
+        "mfma_frac_of_peak": {"sequential": 2 * macs / (seq_ms * 1e-3) / PEAK[dtype] if seq_ms else None,
+                              "stream_parallel": 2 * macs / (par_ms * 1e-3) / PEAK[dtype] if par_ms else None,
                               "regulated": 2 * macs / (reg_ms * 1e-3) / PEAK[dtype]},
         "plan_selection": plan_info,
         "kernels": {k: {"launches": v["launches"], "ms_per_round": round(v["ms"], 4),

@@ -188,7 +188,9 @@ gacer_status gacer_run(gacer_ctx *ctx, int mode, int rounds, float *ms_per_round
 /*
  * Measurement aid: like gacer_run, but every kernel launch is bracketed by a hipEvent pair on the
  * stream it runs on, so that per-launch durations under the chosen mode (including contention from
- * the other tenants' streams) can be read back.  out[k].ms is the mean over `rounds`.  Writes up to
+ * the other tenants' streams) can be read back.  out[k].ms is the mean over `rounds` of the bracket
+ * time minus what an event pair reads with nothing between its two records (marker processing, about
+ * 4 us, measured at the start of the call behind pending work on the same queue).  Writes up to
  * `cap` rows (launch order of one round; an operator whose K range is cut into slices contributes its
  * slice kernel and its finishing pass as two rows) and the row count to *n; cap = 0 sizes.  The event pairs
  * perturb the schedule slightly; throughput must be taken from gacer_run.
