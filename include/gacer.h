@@ -114,8 +114,12 @@ typedef struct {
     void *stream; /* hipStream_t created by the caller (default priority); NULL = null stream */
 } gacer_tenant;
 
-/* mask + list_B (Section 4.2): operator (tenant, op) is decomposed `factor` ways on `axis`. */
-typedef struct { int tenant, op; gacer_axis axis; int factor; } gacer_split;
+/* mask + list_B (Section 4.2, Eq. 5): operator (tenant, op) is decomposed into `factor` chunks on `axis`.
+ * sizes == NULL: even chunks, factor in {1,2,4,8}, chunk j holds floor(E/factor) + (j < E mod factor) elements of the
+ * axis extent E.  sizes != NULL: list_B itself -- `factor` (1..8) positive chunk sizes in launch order whose sum must
+ * equal E (e.g. {24, 8} on a batch of 32); the array is copied by gacer_set_plan.  Chunks are contiguous ascending
+ * sub-ranges and run in that order on the tenant's stream. */
+typedef struct { int tenant, op; gacer_axis axis; int factor; const int *sizes; } gacer_split;
 /* One ordering constraint between streams.  when == 0: (dst_tenant,dst_op) starts only after every chunk of
  * (src_tenant,src_op) has finished.  when == 1: it starts once everything (src_tenant,src_op) itself has to wait
  * for is done (its stream predecessors and its own when-0 edges) -- the source operator then acts as the hub of a

@@ -49,9 +49,17 @@ def round_bf16(a):
 
 
 def chunk_ranges(extent, factor):
-    """Even decomposition of an extent into ``factor`` contiguous chunks whose
-    sizes sum to the extent (Eq. 5); the first ``extent % factor`` chunks are
-    one element longer."""
+    """Decomposition of an extent into contiguous chunks whose sizes sum to the
+    extent (Eq. 5).  ``factor`` is a chunk count (even chunks; the first
+    ``extent % factor`` are one element longer) or the list of chunk sizes
+    itself (list_B of Section 4.2)."""
+    if isinstance(factor, (list, tuple)):
+        assert sum(factor) == extent and all(sz >= 1 for sz in factor)
+        out, lo = [], 0
+        for sz in factor:
+            out.append((lo, lo + sz))
+            lo += sz
+        return out
     out, lo = [], 0
     for i in range(factor):
         sz = extent // factor + (1 if i < extent % factor else 0)

@@ -45,7 +45,7 @@ class gacer_tenant(C.Structure):
 
 
 class gacer_split(C.Structure):
-    _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("axis", C.c_int), ("factor", C.c_int)]
+    _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("axis", C.c_int), ("factor", C.c_int), ("sizes", C.POINTER(C.c_int))]
 
 
 class gacer_sync(C.Structure):

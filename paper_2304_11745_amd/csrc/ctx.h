@@ -44,7 +44,8 @@ struct Ctx {
     bool loaded = false;
     bool ws_missing = false;                        // split-K workspace allocation failed at load
     // current plan (copied)
-    std::vector<gacer_split> splits;
+    std::vector<gacer_split> splits;              // installed plan (sizes pointers refer to split_sizes)
+    std::vector<std::vector<int>> split_sizes;
     std::vector<gacer_sync> syncs;
     // expansion: [tenant][op]
     std::vector<std::vector<OpExec>> plan_exec;     // decomposed + edges

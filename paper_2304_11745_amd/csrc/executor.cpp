@@ -361,7 +361,10 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
     for (const gacer_split &s : splits) {
         if (s.tenant < 0 || s.tenant >= NT || s.op < 0 || s.op >= (int)c->tenants[s.tenant].ops.size())
             return fail(c, GACER_EPLAN, "split names a missing operator (tenant %d op %d)", s.tenant, s.op);
-        if (s.factor != 1 && s.factor != 2 && s.factor != 4 && s.factor != 8)
+        if (s.sizes) {
+            if (s.factor < 1 || s.factor > 8)
+                return fail(c, GACER_EPLAN, "tenant %d op %d: a chunk list holds 1..8 sizes, not %d", s.tenant, s.op, s.factor);
+        } else if (s.factor != 1 && s.factor != 2 && s.factor != 4 && s.factor != 8)
             return fail(c, GACER_EPLAN, "tenant %d op %d: factor %d not in {1,2,4,8}", s.tenant, s.op, s.factor);
         if (smap.count({s.tenant, s.op})) return fail(c, GACER_EPLAN, "tenant %d op %d: split listed twice", s.tenant, s.op);
         if (s.factor > 1) {
@@ -373,6 +376,17 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
             if (s.factor > axis_extent(T, s.op, s.axis))
                 return fail(c, GACER_EPLAN, "tenant %d op %d: factor %d exceeds the axis extent %d", s.tenant, s.op, s.factor,
                             axis_extent(T, s.op, s.axis));
+        }
+        if (s.sizes) {                       // list_B: positive sizes that sum to the extent (Eq. 5)
+            int64_t sum = 0;
+            for (int j = 0; j < s.factor; ++j) {
+                if (s.sizes[j] < 1) return fail(c, GACER_EPLAN, "tenant %d op %d: chunk %d has size %d", s.tenant, s.op, j, s.sizes[j]);
+                sum += s.sizes[j];
+            }
+            const int ext = s.factor > 1 ? axis_extent(c->tenants[s.tenant], s.op, s.axis) : (int)sum;
+            if (sum != ext)
+                return fail(c, GACER_EPLAN, "tenant %d op %d: chunk sizes sum to %lld, the axis extent is %d", s.tenant, s.op,
+                            (long long)sum, ext);
         }
         smap[{s.tenant, s.op}] = s;
     }
@@ -419,13 +433,15 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
             auto it = smap.find({t, i});
             const int f = (it == smap.end()) ? 1 : it->second.factor;
             const gacer_axis ax = (it == smap.end() || f == 1) ? GACER_AXIS_NONE : it->second.axis;
+            const int *sizes = (it == smap.end() || f == 1) ? nullptr : it->second.sizes;
+            int next = 0;
             for (int j = 0; j < f; ++j) {
                 int lo, hi;
                 if (ax == GACER_AXIS_BATCH) {
-                    chunk_range(T.batch, f, j, &lo, &hi);
+                    if (sizes) { lo = next; hi = next += sizes[j]; } else chunk_range(T.batch, f, j, &lo, &hi);
                     ex[t][i].chunks.push_back(make_launch(T, i, lo, hi, 0, cout));
                 } else if (ax == GACER_AXIS_COUT) {
-                    chunk_range(cout, f, j, &lo, &hi);
+                    if (sizes) { lo = next; hi = next += sizes[j]; } else chunk_range(cout, f, j, &lo, &hi);
                     ex[t][i].chunks.push_back(make_launch(T, i, 0, T.batch, lo, hi));
                 } else {
                     ex[t][i].chunks.push_back(make_launch(T, i, 0, T.batch, 0, cout));
@@ -443,6 +459,12 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
     drop_graphs(c);                      // captured rounds belong to the plan they were captured under
     c->splits = splits;
+    c->split_sizes.assign(splits.size(), {});
+    for (size_t k = 0; k < splits.size(); ++k)
+        if (splits[k].sizes) {
+            c->split_sizes[k].assign(splits[k].sizes, splits[k].sizes + splits[k].factor);
+            c->splits[k].sizes = c->split_sizes[k].data();
+        }
     c->syncs = syncs;
     c->plan_exec.swap(ex);
     c->plan_order.swap(order);

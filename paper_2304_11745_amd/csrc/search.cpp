@@ -250,7 +250,7 @@ gacer_plan *to_plan(Ctx *c, const Splits &sp, const Pointers &P)
     std::vector<gacer_split> list;
     for (int t = 0; t < NT; ++t)
         for (int i = 0; i < (int)sp[t].size(); ++i)
-            if (sp[t][i].f > 1) list.push_back({t, i, (gacer_axis)sp[t][i].axis, sp[t][i].f});
+            if (sp[t][i].f > 1) list.push_back({t, i, (gacer_axis)sp[t][i].axis, sp[t][i].f, nullptr});
     gacer_split *arr = list.empty() ? nullptr : new (std::nothrow) gacer_split[list.size()];
     if (!list.empty() && !arr) { gacer_plan_free(edges); return nullptr; }
     std::copy(list.begin(), list.end(), arr);
@@ -317,6 +317,7 @@ gacer_status gacer_model_residue(gacer_ctx *c, const gacer_prof *prof, size_t n,
     for (int t = 0; t < NT; ++t) sp[t].assign(m.n_ops[t], Split());
     for (int k = 0; k < n_split; ++k) {
         const gacer_split &s = split[k];
+        if (s.sizes) { c->err = "the model covers even decompositions only (the lookup table has no rows for chunk lists)"; return GACER_EPLAN; }
         if (s.tenant < 0 || s.tenant >= NT || s.op < 0 || s.op >= m.n_ops[s.tenant] || (int)s.axis < 0 || (int)s.axis > 2 ||
             (s.factor != 1 && s.factor != 2 && s.factor != 4 && s.factor != 8) ||
             !m.tab[s.tenant][s.op].c[s.factor > 1 ? (int)s.axis : 0][lg(s.factor)].have) {

@@ -95,8 +95,17 @@ class Session:
 
     # -- plan ------------------------------------------------------------------------------------
     def set_plan(self, splits=(), syncs=()):
-        """splits: iterable of (tenant, op, axis-name, factor); syncs: (src_t, src_op, dst_t, dst_op[, when])."""
-        sp = (B.gacer_split * max(1, len(splits)))(*[B.gacer_split(t, o, AXIS[a], f) for (t, o, a, f) in splits])
+        """splits: iterable of (tenant, op, axis-name, factor) for even chunks, or (tenant, op, axis-name, [sizes...])
+        for an explicit chunk list; syncs: (src_t, src_op, dst_t, dst_op[, when])."""
+        rows, keep = [], []
+        for (t, o, a, f) in splits:
+            if isinstance(f, (list, tuple)):
+                arr = (C.c_int * len(f))(*f)
+                keep.append(arr)
+                rows.append(B.gacer_split(t, o, AXIS[a], len(f), arr))
+            else:
+                rows.append(B.gacer_split(t, o, AXIS[a], f, None))
+        sp = (B.gacer_split * max(1, len(rows)))(*rows)
         sy = (B.gacer_sync * max(1, len(syncs)))(*[B.gacer_sync(*e) for e in syncs])
         plan = B.gacer_plan(len(splits), sp, len(syncs), sy)
         B.check(self.ctx, B.gacer_set_plan(self.ctx, C.byref(plan)))

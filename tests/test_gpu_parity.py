@@ -66,6 +66,16 @@ def _sweep_plans(sess):
             sp = sess.uniform_splits(axis, f)
             if sp:
                 plans[f"{axis}x{f}"] = (sp, None)
+    # explicit chunk lists (list_B, Section 4.2): uneven sizes, channel chunks that start at unaligned offsets
+    uneven = []
+    for ti, t in enumerate(sess.tenants):
+        for oi, op in enumerate(t.ops):
+            cout = t.tensors[op.out][1]
+            if op.kind in ("conv", "dwconv", "gemm") and cout >= 6 and oi % 2 == 0:
+                uneven.append((ti, oi, "cout", [cout - 5, 3, 2]))
+            elif t.batch >= 3:
+                uneven.append((ti, oi, "batch", [t.batch - 2, 2] if oi % 3 else [1, t.batch - 1]))
+    plans["uneven-lists"] = (uneven, None)
     n_ops = [len(t.ops) for t in sess.tenants]
     plans["pointers1"] = ([], [[n // 2] for n in n_ops])
     plans["pointers3+cout2"] = (sess.uniform_splits("cout", 2), [[0, n // 3, n] for n in n_ops])

@@ -139,6 +139,46 @@ def test_plan_validation(ctx):
     assert B.gacer_set_plan(ctx, None) == B.GACER_OK
 
 
+def test_chunk_list_validation(ctx):
+    """list_B of Section 4.2: explicit chunk sizes must be positive, at most 8, and sum to the axis extent (Eq. 5)."""
+    tenants = [synth.small_resnet("f32", 6), synth.small_bert("f32", 3)]
+    st, keep = load(ctx, tenants)
+    assert st == B.GACER_OK
+    cout0 = tenants[0].ops[0].cout
+
+    def split(t, o, axis, sizes):
+        arr = (C.c_int * len(sizes))(*sizes)
+        return B.gacer_split(t, o, axis, len(sizes), arr), arr
+
+    def set_plan(rows):
+        sp = (B.gacer_split * len(rows))(*[r[0] for r in rows])
+        plan = B.gacer_plan(len(rows), sp, 0, None)
+        return B.gacer_set_plan(ctx, C.byref(plan))
+
+    bad = [
+        [split(0, 0, B.GACER_AXIS_BATCH, [4, 1])],                        # sums to 5, batch is 6
+        [split(0, 0, B.GACER_AXIS_BATCH, [6, 0])],                        # empty chunk
+        [split(0, 0, B.GACER_AXIS_BATCH, [7, -1])],                       # negative size
+        [split(0, 0, B.GACER_AXIS_COUT, [1] * 9)],                        # more than 8 chunks
+        [split(0, 0, B.GACER_AXIS_COUT, [cout0 - 1, 2])],                 # sums past the extent
+        [split(0, 0, B.GACER_AXIS_NONE, [5, 1])],                         # chunks need an axis
+    ]
+    for rows in bad:
+        assert set_plan(rows) == B.GACER_EPLAN, [list(r[1]) for r in rows]
+    good = [split(0, 0, B.GACER_AXIS_BATCH, [5, 1]), split(0, 1, B.GACER_AXIS_COUT, [cout0 - 3, 2, 1]),
+            split(1, 0, B.GACER_AXIS_BATCH, [3])]                        # a single chunk is the unsplit operator
+    assert set_plan(good) == B.GACER_OK
+    n = C.c_int()
+    B.gacer_launch_count(ctx, B.GACER_MODE_PLAN, C.byref(n))
+    assert n.value == sum(len(t.ops) for t in tenants) + 1 + 2
+    for r in good:                                                        # the library copied the lists
+        for j in range(len(r[1])):
+            r[1][j] = 0
+    B.gacer_launch_count(ctx, B.GACER_MODE_PLAN, C.byref(n))
+    assert n.value == sum(len(t.ops) for t in tenants) + 3
+    assert B.gacer_set_plan(ctx, None) == B.GACER_OK
+
+
 def _edges(ctx, matrix_P):
     n_ptr = len(matrix_P[0])
     flat = (C.c_int * max(1, len(matrix_P) * n_ptr))(*[p for P in matrix_P for p in P])

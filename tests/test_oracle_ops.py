@@ -249,7 +249,23 @@ def test_oracle_split_invariance(maker, dtype):
             assert np.array_equal(F.run_tenant(t, x, p, splits), base)
 
 
+def test_oracle_chunk_list_invariance():
+    """Uneven chunk lists (list_B such as [24, 8], Section 4.2) leave the oracle's result unchanged, bit for bit."""
+    for dtype in ("f32", "bf16"):
+        t = synth.small_mbv2(dtype, 5)
+        x, p = synth.materialise(t, 8)
+        base = F.run_tenant(t, x, p)
+        splits = {}
+        for i, op in enumerate(t.ops):
+            if op.kind in ("conv", "dwconv", "gemm") and op.cout >= 4:
+                splits[i] = ("cout", [op.cout - 3, 1, 2]) if i % 2 else ("batch", [1, 4])
+        assert len(splits) > 4
+        assert np.array_equal(F.run_tenant(t, x, p, splits), base)
+
+
 def test_chunk_ranges():
+    assert F.chunk_ranges(32, [24, 8]) == [(0, 24), (24, 32)]        # the paper's list_B example sizes
+    assert F.chunk_ranges(7, [1, 1, 5]) == [(0, 1), (1, 2), (2, 7)]
     assert F.chunk_ranges(10, 4) == [(0, 3), (3, 6), (6, 8), (8, 10)]
     assert F.chunk_ranges(8, 2) == [(0, 4), (4, 8)]
     assert sum(b - a for a, b in F.chunk_ranges(1000, 8)) == 1000
