@@ -219,7 +219,7 @@ class Session:
     def refine_plan(self, rows, base_splits=(), base_syncs=(), rounds=12, min_gain=0.005, log=None):
         """Measured greedy refinement of a plan (the spatial step of Section 4.2 with the GPU as the judge):
         tenants in order of profiled time; for each, decompose its heaviest operators (top quartile of isolated
-        time) batch x2, batch x4 or Cout x2 and keep the option that lowers the measured makespan by more than
+        time) batch x2, batch x4, Cout x2 or batch [3/4, 1/4] and keep the option that lowers the measured makespan by more than
         ``min_gain``.  Returns (splits, syncs, makespan_ms).  Every candidate is a valid plan, so outputs stay
         bit-identical; only the schedule changes."""
         import statistics
@@ -243,6 +243,12 @@ class Session:
                 sp = [x for x in self.uniform_splits(axis, f, tenants=[ti]) if T[ti][x[1]] >= thr and (x[0], x[1]) not in taken]
                 if sp:
                     options.append((f"{self.tenants[ti].name}[{ti}] {axis}x{f}", sp))
+            bt = self.tenants[ti].batch
+            if bt >= 4:                          # an uneven chunk list (Section 4.2: a chunk sized to the gap it should fill)
+                sp = [(x[0], x[1], "batch", [bt - bt // 4, bt // 4]) for x in self.uniform_splits("batch", 2, tenants=[ti])
+                      if T[ti][x[1]] >= thr and (x[0], x[1]) not in taken]
+                if sp:
+                    options.append((f"{self.tenants[ti].name}[{ti}] batch [{bt - bt // 4},{bt // 4}]", sp))
             for name, sp in options:
                 ms = measure(best_sp + sp, best_sy)
                 if log:
