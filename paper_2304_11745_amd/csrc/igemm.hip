@@ -735,13 +735,14 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     return li;
 }
 
-// rowgemm_kernel is taken when the operator is a single-tap, unpadded, unsplit product whose rows are at most
-// 512 bytes of K: properties of the operator, not of the launched sub-range, so every chunk of an operator
-// takes the same path as its unsplit launch.
+// rowgemm_kernel is taken when the operator is a single-tap, unpadded, unsplit bf16 product whose rows are at most
+// 192 bytes of K (measured: beyond that, and for fp32 at any K, the tiled kernel is as fast or faster): properties
+// of the operator, not of the launched sub-range, so every chunk of an operator takes the same path as its
+// unsplit launch.
 static bool rows_eligible(const GemmArgs &a, int esz, bool vec_ok)
 {
     return vec_ok && !a.b_trans && a.ksplit == 1 && a.kh == 1 && a.kw == 1 && a.pad == 0 && a.zb * a.zh == 1 && a.z_lo == 0 &&
-           (int64_t)a.K * esz <= 512;
+           esz == 2 && (int64_t)a.K * esz <= 192;
 }
 static int rows_lds(int tn, int K, int esz)
 {
@@ -804,9 +805,8 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
     const bool vec_ok = (a.Cin % VEC == 0) && (a.x_pix % VEC == 0) && (a.x_img % VEC == 0) && (a.w_row % VEC == 0) &&
                         (a.x_zb % VEC == 0) && (a.x_zh % VEC == 0) && (a.w_zb % VEC == 0) && (a.w_zh % VEC == 0) &&
                         (((uintptr_t)a.x) % 16 == 0) && (((uintptr_t)a.w) % 16 == 0);
-    if (rows_eligible(a, (int)sizeof(typename El<DT>::T), vec_ok)) {
-        if (phase == 2) { LaunchInfo li = pick_rows<DT>(a, s, true); return li; }
-        return pick_rows<DT>(a, s, dry);
+    if constexpr (DT == DT_BF16) {
+        if (rows_eligible(a, (int)sizeof(typename El<DT>::T), vec_ok)) return pick_rows<DT>(a, s, dry || phase == 2);
     }
     const int M = a.m_hi - a.m_lo, N = a.n_hi - a.n_lo;
     const int64_t z = (int64_t)a.zb * a.zh * (a.b_trans ? 1 : a.ksplit);
