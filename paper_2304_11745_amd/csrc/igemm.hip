@@ -205,6 +205,12 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         for (int q = 0; q < a.kw; ++q) wmk |= (unsigned)(iw0 + q >= 0 && iw0 + q < a.W) << q;
         a_hm[i] = ok ? hm : 0u;
         a_wm[i] = wmk;
+        if constexpr (TAPS) {                   // one validity bit per tap (kh*kw <= 31 on this path): bit r*kw + q
+            unsigned tm = 0;
+            for (int r = 0; r < a.kh; ++r)
+                for (int q = 0; q < a.kw; ++q) tm |= ((hm >> r) & (wmk >> q) & 1u) << (r * a.kw + q);
+            a_hm[i] = ok ? tm : 0u;
+        }
     }
     // ---- per-thread B rows: byte offset of the weight row, and whether the row exists ----
     unsigned b_off[BV];
@@ -291,12 +297,9 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
             const bool k_ok = kv < k_end;
             if constexpr (TAPS) {
                 const unsigned delta = (unsigned)((((int64_t)kr * a.W + ksx) * a.x_pix + kci) * ESZ);
-                const unsigned rr = k_ok ? (unsigned)kr : 31u, qq = (unsigned)ksx;
+                const unsigned tp = k_ok ? (unsigned)(kr * a.kw + ksx) : 31u;      // bit 31 is never set
 #pragma unroll
-                for (int i = 0; i < AV; ++i) {
-                    const bool ok = k_ok && ((a_hm[i] >> rr) & (a_wm[i] >> qq) & 1u);
-                    pa[i] = buf_load16(xr, ok ? a_off[i] + delta : OOB);
-                }
+                for (int i = 0; i < AV; ++i) pa[i] = buf_load16(xr, ((a_hm[i] >> tp) & 1u) ? a_off[i] + delta : OOB);
             } else {
                 const unsigned delta = (unsigned)(kv * ESZ);
 #pragma unroll
@@ -714,6 +717,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     static const std::string n_vec = "igemm_" + shape, n_bt = "igemm_bt_" + shape, n_gather = "igemm_gather_" + shape,
                              n_taps = "igemm_taps_" + shape;
     const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
+    if (taps && a.kh * a.kw > 31) vec_ok = false;      // the tapped loader keeps one validity bit per tap in a 32-bit mask
     li.kernel = a.b_trans ? n_bt.c_str() : (!vec_ok ? n_gather.c_str() : (taps ? n_taps.c_str() : n_vec.c_str()));
     li.phases = ks > 1 ? 2 : 1;
     if (phase == 2) li.kernel = "splitk_finish";
