@@ -128,6 +128,38 @@ def cpu_baseline(tenants, data, items):
     return out
 
 
+def granularity_table(dtype, rounds):
+    """The spatial-granularity experiment of Section 5.4 (its Table 3) on this executor: VGG-16(32) and ResNet-18(32)
+    share the GPU; the rows differ in how each model's batch is decomposed over streams (V16(16)+V16(16) is the batch
+    of 32 run as two half-batch instances on two streams).  Synthetic inputs, seeded weights (instances of one model
+    draw the same weights).  Prints one JSON line of its own."""
+    import synth
+    from synth import graphs as G
+    from paper_2304_11745_amd import binding as B
+    from paper_2304_11745_amd import harness
+    rows = {"1: V16(32) R18(32)": [("v", 32), ("r", 32)],
+            "2: V16(16) V16(16) R18(32)": [("v", 16), ("v", 16), ("r", 32)],
+            "3: V16(24) V16(8) R18(32)": [("v", 24), ("v", 8), ("r", 32)],
+            "4: V16(32) R18(16) R18(16)": [("v", 32), ("r", 16), ("r", 16)],
+            "5: V16(8)x4 R18(32)": [("v", 8)] * 4 + [("r", 32)]}
+    out = {}
+    for name, spec in rows.items():
+        tenants = [G.vgg16(dtype, b) if m == "v" else G.resnet18(dtype, b) for m, b in spec]
+        data = [G.materialise(t, 20230411, 0 if m == "v" else 1 << 20) for t, (m, b) in zip(tenants, spec)]
+        sess = harness.Session(tenants, data, "cuda:0")
+        sess.run(B.GACER_MODE_STREAM_PARALLEL, 5)
+        par = statistics.median(sess.run(B.GACER_MODE_STREAM_PARALLEL, rounds))
+        seq = statistics.median(sess.run(B.GACER_MODE_SEQUENTIAL, rounds))
+        sess.close()
+        out[name] = {"streams_ms": round(par, 4), "sequential_ms": round(seq, 4)}
+        log(f"granularity {name}: streams {par:.3f} ms, sequential {seq:.3f} ms")
+    base = out["1: V16(32) R18(32)"]["streams_ms"]
+    for v in out.values():
+        v["vs_row1"] = round(base / v["streams_ms"], 3)
+    print(json.dumps({"experiment": "spatial granularity (Section 5.4, Table 3)", "dtype": dtype, "unit": "ms per round of 64 images",
+                      "rows": out, "paper_context": "Titan V: 80 / 66 / 72 / 78 / 85 ms for rows 1-5; other hardware, context only"}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,12 +172,17 @@ def main():
     ap.add_argument("--only-regulated", action="store_true",
                     help="time the regulated mode only (profiling runs: every dispatch then belongs to the reported mode)")
     ap.add_argument("--print-sources-digest", action="store_true")
+    ap.add_argument("--granularity-table", choices=["f32", "bf16"], default=None,
+                    help="run the batch-decomposition-over-streams experiment (Section 5.4) instead of the benchmark")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain copy of known size (256 MiB in, 256 MiB out) three times, as the "
                          "reference dispatch for scaling hardware traffic counters")
     args = ap.parse_args()
     if args.print_sources_digest:
         print(sources_digest())
+        return
+    if args.granularity_table:
+        granularity_table(args.granularity_table, max(10, args.steps // 4))
         return
     if args.gpus != 1:
         sys.exit("bench.py: the executor runs on exactly one GPU (tenants shard across GPUs with no exchange); use --gpus 1")
