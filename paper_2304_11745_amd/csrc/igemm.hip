@@ -39,6 +39,11 @@ __device__ __attribute__((noinline)) float gelu_erf(float v)
     return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
 }
 
+__device__ __forceinline__ float gelu_erf_inl(float v)
+{
+    return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
+}
+
 __device__ __forceinline__ float act_apply(float v, int act)
 {
     if (act == ACT_RELU) return __builtin_fmaxf(v, 0.f);
@@ -92,34 +97,26 @@ template <int EV> __device__ __forceinline__ void act_vec(float *v, int act)
 }
 
 // Epilogue of EV consecutive output channels of one row, all inside the launched range and 16-byte aligned:
-// y = act(alpha * v + bias + res), vector loads of bias and residual, one vector store.
+// y = act(alpha * v + bias + res).  Bias and residual arrive preloaded (their loads are issued before the accumulators
+// are turned through LDS, so that no global round trip sits between the last MFMA and the output store).
 template <int DT>
-__device__ __forceinline__ void finish_vec(const GemmArgs &a, float *v, const typename El<DT>::T *rg, typename El<DT>::T *yg, int64_t o, int n)
+__device__ __forceinline__ void finish_vec(const GemmArgs &a, float *v, const float *bv, bool has_res, const uint4 &rv,
+                                           typename El<DT>::T *yg, int64_t o)
 {
     constexpr int EV = DT == DT_BF16 ? 8 : 4;
-    if (a.bias) {
 #pragma unroll
-        for (int q = 0; q < EV; q += 4) {
-            const float4 b4 = *(const float4 *)(a.bias + n + q);
-            v[q] = __fmaf_rn(v[q], a.alpha, b4.x); v[q + 1] = __fmaf_rn(v[q + 1], a.alpha, b4.y);
-            v[q + 2] = __fmaf_rn(v[q + 2], a.alpha, b4.z); v[q + 3] = __fmaf_rn(v[q + 3], a.alpha, b4.w);
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < EV; ++q) v[q] = __fmaf_rn(v[q], a.alpha, 0.f);
-    }
-    if (rg) {
+    for (int q = 0; q < EV; ++q) v[q] = __fmaf_rn(v[q], a.alpha, bv[q]);
+    if (has_res) {
+        const unsigned rw[4] = {rv.x, rv.y, rv.z, rv.w};
         if constexpr (DT == DT_BF16) {
-            const uint4 rv = *(const uint4 *)(rg + o);
-            const unsigned rw[4] = {rv.x, rv.y, rv.z, rv.w};
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 v[2 * q] = __fadd_rn(v[2 * q], __uint_as_float(rw[q] << 16));
                 v[2 * q + 1] = __fadd_rn(v[2 * q + 1], __uint_as_float(rw[q] & 0xFFFF0000u));
             }
         } else {
-            const float4 rv = *(const float4 *)(rg + o);
-            v[0] = __fadd_rn(v[0], rv.x); v[1] = __fadd_rn(v[1], rv.y); v[2] = __fadd_rn(v[2], rv.z); v[3] = __fadd_rn(v[3], rv.w);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = __fadd_rn(v[q], __uint_as_float(rw[q]));
         }
     }
     act_vec<EV>(v, a.act);
@@ -127,6 +124,20 @@ __device__ __forceinline__ void finish_vec(const GemmArgs &a, float *v, const ty
         *(uint4 *)(yg + o) = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
     else
         *(float4 *)(yg + o) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
+// bias of EV consecutive channels (zeros without a bias pointer); n is a multiple of 4 and the pointer 16-byte aligned
+template <int EV> __device__ __forceinline__ void load_bias_vec(const float *bias, int n, bool ok, float *bv)
+{
+#pragma unroll
+    for (int q = 0; q < EV; ++q) bv[q] = 0.f;
+    if (bias && ok) {
+#pragma unroll
+        for (int q = 0; q < EV; q += 4) {
+            const float4 b4 = *(const float4 *)(bias + n + q);
+            bv[q] = b4.x; bv[q + 1] = b4.y; bv[q + 2] = b4.z; bv[q + 3] = b4.w;
+        }
+    }
 }
 
 // Ragged or unaligned tail: element by element (rare: odd channel counts, unaligned channel chunks).
@@ -137,7 +148,11 @@ __device__ __noinline__ void finish_one(float v, float alpha, const float *bias,
     if (n >= n_hi) return;
     float t = __fmaf_rn(v, alpha, bias ? bias[n] : 0.f);
     if (rg) t = __fadd_rn(t, load_in(rg, o));
-    store_out<typename El<DT>::T>(yg, o, act_apply(t, act));
+    // leaf function (no nested call, hence no stack): the activation is expanded in place
+    if (act == ACT_RELU) t = __builtin_fmaxf(t, 0.f);
+    else if (act == ACT_RELU6) t = __builtin_amdgcn_fmed3f(t, 0.f, 6.f);
+    else if (act == ACT_GELU) t = gelu_erf_inl(t);
+    store_out<typename El<DT>::T>(yg, o, t);
 }
 template <int DT>
 __device__ __forceinline__ void finish_scalar(const GemmArgs &a, const float *v, const typename El<DT>::T *rg, typename El<DT>::T *yg, int64_t o, int n)
@@ -454,14 +469,25 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * (BN / WN) + j * 32 + ecol;
+            const bool n_vec = vec_out && n + EV <= a.n_hi;
+            // bias and residual loads first, then the LDS turn: one global round trip per tile, overlapped with the turn
+            float bv[EV];
+            load_bias_vec<EV>(a.bias, n, !split && n_vec, bv);
+            uint4 rv[GROUPS];
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int m = m0 + wm * (BM / WM) + i * 32 + erow + g * (64 / LPR);
+                rv[g] = make_uint4(0u, 0u, 0u, 0u);
+                if (!split && rg && n_vec && m < a.m_hi) rv[g] = *(const uint4 *)(rg + (int64_t)m * a.y_row + n);
+            }
 #pragma unroll
             for (int e = 0; e < 16; ++e) stage[((e >> 2) * 8 + lhalf * 4 + (e & 3)) * SROW + lrow] = acc[i][j][e];
             __builtin_amdgcn_wave_barrier();
-#pragma unroll 1
+#pragma unroll
             for (int g = 0; g < GROUPS; ++g) {
                 const int row = erow + g * (64 / LPR);
                 const int m = m0 + wm * (BM / WM) + i * 32 + row;
-                const int n = n0 + wn * (BN / WN) + j * 32 + ecol;
                 float v[EV];
 #pragma unroll
                 for (int q = 0; q < EV; q += 4) {
@@ -482,7 +508,7 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                     continue;
                 }
                 const int64_t o = (int64_t)m * a.y_row + n;
-                if (vec_out && n + EV <= a.n_hi) finish_vec<DT>(a, v, rg, yg, o, n);
+                if (n_vec) finish_vec<DT>(a, v, bv, rg != nullptr, rv[g], yg, o);
                 else finish_scalar<DT>(a, v, rg, yg, o, n);
             }
             __builtin_amdgcn_wave_barrier();
@@ -607,6 +633,21 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
                          (((uintptr_t)a.bias) & 15) == 0;
 #pragma unroll
     for (int hf = 0; hf < (TN + 1) / 2; ++hf) {
+        constexpr int ITER = 32 / RPI;
+        const int width = (hf * 2 + 1 < TN) ? HALF : 32;
+        const int col = (lane % CPR) * EV, n = n0 + hf * HALF + col;
+        const bool n_ok = col < width && n < a.n_hi;
+        const bool n_vec = n_ok && vec_out && n + EV <= a.n_hi;
+        // bias and residual loads before the LDS turn (see igemm_kernel)
+        float bv[EV];
+        load_bias_vec<EV>(a.bias, n, n_vec, bv);
+        uint4 rv[ITER];
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int m = m0 + it * RPI + lane / CPR;
+            rv[it] = make_uint4(0u, 0u, 0u, 0u);
+            if (rg && n_vec && m < a.m_hi) rv[it] = *(const uint4 *)(rg + (int64_t)m * a.y_row + n);
+        }
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int j = hf * 2 + jj;
@@ -616,21 +657,19 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
             }
         }
         __builtin_amdgcn_wave_barrier();
-        constexpr int width_full = HALF;
-        const int width = (hf * 2 + 1 < TN) ? width_full : 32;
-#pragma unroll 1
-        for (int it = 0; it < 32 / RPI; ++it) {
-            const int row = it * RPI + lane / CPR, col = (lane % CPR) * EV;
-            const int m = m0 + row, n = n0 + hf * HALF + col;
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int row = it * RPI + lane / CPR;
+            const int m = m0 + row;
             float v[EV];
 #pragma unroll
             for (int q = 0; q < EV; q += 4) {
                 const float4 t4 = *(const float4 *)(stage + row * SROW + col + q);
                 v[q] = t4.x; v[q + 1] = t4.y; v[q + 2] = t4.z; v[q + 3] = t4.w;
             }
-            if (col >= width || m >= a.m_hi || n >= a.n_hi) continue;
+            if (!n_ok || m >= a.m_hi) continue;
             const int64_t o = (int64_t)m * a.y_row + n;
-            if (vec_out && n + EV <= a.n_hi) finish_vec<DT>(a, v, rg, yg, o, n);
+            if (n_vec) finish_vec<DT>(a, v, bv, rg != nullptr, rv[it], yg, o);
             else finish_scalar<DT>(a, v, rg, yg, o, n);
         }
         __builtin_amdgcn_wave_barrier();
