@@ -333,6 +333,116 @@ __global__ __launch_bounds__(TPB) void softmax_kernel(StreamArgs a)
     for (int c = lane; c < a.C; c += 64) st_f32(y, c, __fdiv_rn(expf(__fsub_rn(ld_f32(x, c), m)), s));
 }
 
+// ---- row operators, vector form: the row is read once with 16-byte loads and stays in registers -------
+// Same definitions as the scalar kernels above; each lane first folds its own elements in order, then the lanes
+// are combined by the xor butterfly.  Which form an operator takes depends on C and on pointer alignment only, so
+// every batch chunk of an operator takes the same one.
+template <int G> __device__ __forceinline__ float group_sum(float v)
+{
+#pragma unroll
+    for (int o = G / 2; o > 0; o >>= 1) v = __fadd_rn(v, __shfl_xor(v, o, 64));
+    return v;
+}
+template <int G> __device__ __forceinline__ float group_max(float v)
+{
+#pragma unroll
+    for (int o = G / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// LayerNorm(x + res) over C features: one wavefront per row, NV 16-byte vectors per lane (C <= 64 * NV * V).
+template <typename T, int V, int NV>
+__global__ __launch_bounds__(TPB) void layernorm_vec_kernel(StreamArgs a)
+{
+    const int64_t row = (int64_t)a.n_lo * a.rows_per_item + (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= (int64_t)a.n_hi * a.rows_per_item) return;
+    const int lane = threadIdx.x & 63;
+    const int nvec = a.C / V;
+    const T *x = (const T *)a.x + row * a.C;
+    const T *r = a.res ? (const T *)a.res + row * a.C : nullptr;
+    Vec<T, V> xv[NV], rv[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int v = lane + 64 * i;
+        if (v < nvec) {
+            xv[i] = ld_vec<T, V>(x, (int64_t)v * V);
+            if (r) rv[i] = ld_vec<T, V>(r, (int64_t)v * V);
+        }
+    }
+    float z[NV][V];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int q = 0; q < V; ++q) {
+            const bool ok = lane + 64 * i < nvec;
+            z[i][q] = ok ? (r ? __fadd_rn(xv[i].get(q), rv[i].get(q)) : xv[i].get(q)) : 0.f;
+            s = __fadd_rn(s, z[i][q]);
+        }
+    const float mu = __fdiv_rn(group_sum<64>(s), (float)a.C);
+    float qq = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+        for (int q = 0; q < V; ++q) {
+            const float d = lane + 64 * i < nvec ? __fsub_rn(z[i][q], mu) : 0.f;
+            z[i][q] = d;
+            qq = __fmaf_rn(d, d, qq);
+        }
+    const float var = __fdiv_rn(group_sum<64>(qq), (float)a.C);
+    const float inv = __fdiv_rn(1.f, __fsqrt_rn(__fadd_rn(var, a.eps)));
+    T *y = (T *)a.y + row * a.C;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int v = lane + 64 * i;
+        if (v >= nvec) continue;
+        Vec<T, V> o;
+#pragma unroll
+        for (int q = 0; q < V; q += 4) {
+            const float4 sc = *(const float4 *)(a.scale + v * V + q), sh = *(const float4 *)(a.shift + v * V + q);
+            o.set(q, __fmaf_rn(__fmul_rn(z[i][q], inv), sc.x, sh.x));
+            o.set(q + 1, __fmaf_rn(__fmul_rn(z[i][q + 1], inv), sc.y, sh.y));
+            o.set(q + 2, __fmaf_rn(__fmul_rn(z[i][q + 2], inv), sc.z, sh.z));
+            o.set(q + 3, __fmaf_rn(__fmul_rn(z[i][q + 3], inv), sc.w, sh.w));
+        }
+        st_vec<T, V>(y, (int64_t)v * V, o);
+    }
+}
+
+// Softmax over C <= 64 * V features: G = lanes per row (a power of two >= C / V), 64 / G rows per wavefront.
+template <typename T, int V, int G>
+__global__ __launch_bounds__(TPB) void softmax_vec_kernel(StreamArgs a)
+{
+    constexpr int RPW = 64 / G;
+    const int lane = threadIdx.x & 63, sub = lane % G;
+    const int64_t row = (int64_t)a.n_lo * a.rows_per_item + ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / G;
+    const bool row_ok = row < (int64_t)a.n_hi * a.rows_per_item;
+    const bool ok = row_ok && sub < a.C / V;
+    const T *x = (const T *)a.x + row * a.C;
+    Vec<T, V> xv;
+    if (ok) xv = ld_vec<T, V>(x, (int64_t)sub * V);
+    float e[V];
+    float m = -INFINITY;
+#pragma unroll
+    for (int q = 0; q < V; ++q) {
+        e[q] = ok ? xv.get(q) : -INFINITY;
+        m = fmaxf(m, e[q]);
+    }
+    m = group_max<G>(m);
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < V; ++q) {
+        e[q] = ok ? expf(__fsub_rn(e[q], m)) : 0.f;
+        s = __fadd_rn(s, e[q]);
+    }
+    s = group_sum<G>(s);
+    if (!ok) return;
+    Vec<T, V> o;
+#pragma unroll
+    for (int q = 0; q < V; ++q) o.set(q, __fdiv_rn(e[q], s));
+    st_vec<T, V>((T *)a.y + row * a.C, (int64_t)sub * V, o);
+}
+
 // ---- launchers --------------------------------------------------------------------------------------
 static bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
 
@@ -427,20 +537,62 @@ LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry)
     return info(g, "gavgpool");
 }
 
+template <typename T, int V>
+static bool launch_layernorm_vec(const StreamArgs &a, hipStream_t s, int64_t g)
+{
+    if (a.C % V || !aligned16(a.x) || !aligned16(a.y) || !aligned16(a.res) || !aligned16(a.scale) || !aligned16(a.shift)) return false;
+    const int nv = (a.C / V + 63) / 64;
+    if (nv == 1) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else if (nv == 2) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else if (nv == 3) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 3>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else if (nv == 4) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else return false;
+    return true;
+}
+
 LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t rows = (int64_t)(a.n_hi - a.n_lo) * a.rows_per_item;
     const int64_t g = (rows + 3) / 4;
     if (!dry && g) {
-        if (a.dtype == DT_BF16) hipLaunchKernelGGL((layernorm_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-        else hipLaunchKernelGGL((layernorm_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        if (a.dtype == DT_BF16) {
+            if (!launch_layernorm_vec<unsigned short, 8>(a, s, g))
+                hipLaunchKernelGGL((layernorm_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        } else if (!launch_layernorm_vec<float, 4>(a, s, g)) {
+            hipLaunchKernelGGL((layernorm_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        }
     }
     return info(g, "layernorm");
+}
+
+// returns the workgroup count of the vector form, or 0 when the operator does not qualify
+template <typename T, int V>
+static int64_t launch_softmax_vec(const StreamArgs &a, hipStream_t s, bool dry, int64_t rows)
+{
+    if (a.C % V || a.C / V > 64 || !aligned16(a.x) || !aligned16(a.y)) return 0;
+    int G = 1;
+    while (G < a.C / V) G *= 2;
+    const int64_t g = (rows + 4 * (64 / G) - 1) / (4 * (64 / G));
+    if (dry || !g) return g;
+    switch (G) {
+    case 1: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 2: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 4: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 16: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 16>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 32: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 32>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    default: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 64>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    }
+    return g;
 }
 
 LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t rows = (int64_t)(a.n_hi - a.n_lo) * a.rows_per_item;
+    if (rows > 0) {
+        const int64_t gv = a.dtype == DT_BF16 ? launch_softmax_vec<unsigned short, 8>(a, s, dry, rows) : launch_softmax_vec<float, 4>(a, s, dry, rows);
+        if (gv) return info(gv, "softmax");
+    }
     const int64_t g = (rows + 3) / 4;
     if (!dry && g) {
         if (a.dtype == DT_BF16) hipLaunchKernelGGL((softmax_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
