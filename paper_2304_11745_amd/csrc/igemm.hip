@@ -875,7 +875,7 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
         if (cost(128, 64, e_mid) < best * 0.999) { best = cost(128, 64, e_mid); shape = 1; }
         if (bn == 128 && cost(128, 128, 1.0) < best * 0.999) shape = 2;
     }
-    if (a.b_trans || a.K <= 16 * VEC) {          // short K: 64-byte blocks
+    if (a.b_trans || a.K <= 16 * VEC || !vec_ok) {   // short K, or the latency-bound gather loader (more waves per unit): 64-byte blocks
         switch (shape) {
         case 2: return go<DT, 128, 128, 2, 2, 4>(a, s, dry, vec_ok, phase);
         case 1: return go<DT, 128, 64, 2, 2, 4>(a, s, dry, vec_ok, phase);
