@@ -120,6 +120,40 @@ def test_small_families_f32_all_kinds(gpu):
     _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_conv_shapes(gpu, dtype):
+    """Seeded random convolution / depthwise / FC shapes (ragged M, N and K tails, odd channel counts, strides, paddings,
+    residuals, every activation): parity with the oracle on every intermediate tensor, bit-exactness under uniform and
+    uneven decompositions."""
+    import random
+    from synth import graphs as G
+    rng = random.Random(20230411 if dtype == "f32" else 20230412)
+    tenants = []
+    for ti in range(6):
+        batch = rng.choice([1, 2, 3, 5])
+        hw = rng.choice([5, 8, 11, 14, 23])
+        cin = rng.choice([1, 3, 5, 8, 16, 24, 40])
+        b = G._B(f"rand{ti}", dtype, batch)
+        x = b.tensor(batch, cin, hw, hw)
+        y = x
+        for li in range(rng.choice([3, 4, 5])):
+            n, c, h, w = b.shape(y)
+            kind = rng.choice(["conv", "conv", "conv", "dw", "pw_res"])
+            if kind == "dw" and h >= 3:
+                y = b.conv(y, c, 3, rng.choice([1, 2]), 1, rng.choice(["relu6", "none"]), groups=c)
+            elif kind == "pw_res":
+                y = b.conv(y, c, 1, 1, 0, rng.choice(["relu", "gelu", "none"]), res=y)
+            else:
+                k = rng.choice([k for k in (1, 3, 5) if k <= h + 2])
+                pad = rng.choice([p for p in (0, 1, 2) if h + 2 * p >= k])
+                stride = rng.choice([1, 2])
+                y = b.conv(y, rng.choice([1, 7, 16, 33, 64, 100, 136]), k, stride, pad, rng.choice(["relu", "relu6", "gelu", "none"]))
+        y = b.gemm(b.gavgpool(y), rng.choice([3, 10, 17]), rng.choice(["none", "relu"]), flatten=True)
+        tenants.append(b.done(x, y))
+    data = [G.materialise(t, 99, i << 20) for i, t in enumerate(tenants)]
+    _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
+
+
 def test_captured_round_replays_bit_exact(gpu):
     """A round captured into a HIP graph must reproduce the eager round bit for bit, on every replay, with
     eager rounds and synchronisations in between, for all three modes and a decomposed, pointer-ordered plan."""
