@@ -687,6 +687,13 @@ __global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
     const int64_t idx = ((int64_t)blockIdx.x * THREADS + threadIdx.x) * FV;
     if (idx >= total) return;
     const int m = a.m_lo + (int)(idx / Nl), n = a.n_lo + (int)(idx % Nl);
+    const int64_t o = (int64_t)m * a.y_row + n;
+    // bias and residual are requested together with the slices: one global round trip for the whole kernel
+    float bv[FV], rv[FV];
+#pragma unroll
+    for (int e = 0; e < FV; ++e) bv[e] = a.bias ? a.bias[n + e] : 0.f;
+#pragma unroll
+    for (int e = 0; e < FV; ++e) rv[e] = a.res ? load_in((const T *)a.res, o + e) : 0.f;
     float v[FV];
     if constexpr (FV == 4) {
         float4 p[16];                          // all slice loads are issued before the first add (ksplit <= 16)
@@ -708,11 +715,10 @@ __global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
         for (int q = 1; q < 16; ++q)
             if (q < a.ksplit) v[0] = __fadd_rn(v[0], p[q]);
     }
-    const int64_t o = (int64_t)m * a.y_row + n;
 #pragma unroll
     for (int e = 0; e < FV; ++e) {
-        float t = __fmaf_rn(v[e], a.alpha, a.bias ? a.bias[n + e] : 0.f);
-        if (a.res) t = __fadd_rn(t, load_in((const T *)a.res, o + e));
+        float t = __fmaf_rn(v[e], a.alpha, bv[e]);
+        if (a.res) t = __fadd_rn(t, rv[e]);
         v[e] = act_apply(t, a.act);
     }
     if constexpr (FV == 4 && sizeof(T) == 4) {
