@@ -56,16 +56,6 @@ template <int DT> struct El;
 template <> struct El<DT_F32> { typedef float T; static constexpr int VEC = 4; };
 template <> struct El<DT_BF16> { typedef unsigned short T; static constexpr int VEC = 8; };
 
-// k -> (tap row r, tap col s, channel ci)
-__device__ __forceinline__ void split_k(int k, int Cin, int kw, bool one_tap, int &r, int &s, int &ci)
-{
-    if (one_tap) { r = 0; s = 0; ci = k; return; }
-    int tap = k / Cin;
-    ci = k - tap * Cin;
-    r = tap / kw;
-    s = tap - r * kw;
-}
-
 template <typename T> __device__ __forceinline__ void store_out(T *y, int64_t o, float v);
 template <> __device__ __forceinline__ void store_out<float>(float *y, int64_t o, float v) { y[o] = v; }
 template <> __device__ __forceinline__ void store_out<unsigned short>(unsigned short *y, int64_t o, float v) { y[o] = f32_to_bf16(v); }
