@@ -34,6 +34,14 @@ def test_config2_full_size_vs_oracle_and_split_sweep():
             sess.run(B.GACER_MODE_PLAN, 1)
             for i in range(2):
                 assert sess.output_bytes(i) == base[i], f"{axis} x{f}: tenant {i} not bit-identical"
+    # explicit chunk lists (list_B): uneven batch chunks on ResNet-18, an 8-channel tail chunk on MobileNetV2's convolutions
+    uneven = [(0, i, "batch", [5, 3]) for i in range(len(tenants[0].ops))]
+    uneven += [(1, i, "cout", [op.cout - 8, 8]) for i, op in enumerate(tenants[1].ops) if op.kind in ("conv", "dwconv") and op.cout > 8]
+    sess.set_plan(uneven, [])
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_PLAN, 1)
+    for i in range(2):
+        assert sess.output_bytes(i) == base[i], f"uneven chunk lists: tenant {i} not bit-identical"
     # one tenant only, plus pointers
     sess.set_plan(sess.uniform_splits("batch", 2, tenants=[0]), sess.edges_from_pointers([[5, 12], [10, 30]]))
     sess.poison_outputs()
