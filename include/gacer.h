@@ -249,6 +249,18 @@ gacer_status gacer_release_graphs(gacer_ctx *ctx);
  */
 gacer_status gacer_set_issue_threads(gacer_ctx *ctx, int enable);
 
+/*
+ * Stream placement aid.  The device runs the streams of a process on a small number of hardware queues, and kernels of
+ * two streams that landed on the same queue never overlap: tenants on such streams run one after the other however
+ * the plan orders them (Section 2.1's concurrent streams silently turn sequential).  This call finds out, by
+ * measurement, which of the caller's `n` streams (hipStream_t, n <= 64) share a queue: it starts a short spinning
+ * kernel (one wavefront, 100 us) on a pair of streams at the same time and checks whether the pair took one or two
+ * kernel times.  group[i] receives a small integer, equal for streams that serialise.  A caller with more candidate
+ * streams than tenants can then give every tenant a queue of its own, or balance tenants over the queues.  Uses only
+ * the given streams; returns after they are idle again.
+ */
+gacer_status gacer_probe_stream_queues(void *const *streams, int n, int *group);
+
 /* Host cost of the issue loop (Section 4.2, "more operators ... more CPU operators issuing overhead"): wall time
  * the last gacer_run spent enqueueing its rounds, before it started to wait, and the number of operator
  * launches it enqueued. */

@@ -1042,6 +1042,55 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
     return GACER_OK;
 }
 
+}  // extern "C"
+
+namespace {
+// true when a spin on `a` and a spin on `b`, released together, take about two kernel times instead of one
+bool streams_serialise(hipStream_t a, hipStream_t b, hipEvent_t ev[3], bool *ok)
+{
+    const unsigned long long ticks = 10000;    // 100 us
+    float worst = 0.f;
+    for (int rep = 0; rep < 3; ++rep) {        // the best of three decides (a slow launch can fake a serialisation)
+        *ok = hipEventRecord(ev[0], a) == hipSuccess && hipStreamWaitEvent(b, ev[0], 0) == hipSuccess;
+        if (!*ok) return false;
+        launch_spin(a, ticks);
+        launch_spin(b, ticks);
+        *ok = hipEventRecord(ev[1], a) == hipSuccess && hipEventRecord(ev[2], b) == hipSuccess &&
+              hipStreamSynchronize(a) == hipSuccess && hipStreamSynchronize(b) == hipSuccess;
+        if (!*ok) return false;
+        float ta = 0.f, tb = 0.f;
+        *ok = hipEventElapsedTime(&ta, ev[0], ev[1]) == hipSuccess && hipEventElapsedTime(&tb, ev[0], ev[2]) == hipSuccess;
+        if (!*ok) return false;
+        const float t = std::max(ta, tb);
+        worst = rep == 0 ? t : std::min(worst, t);
+    }
+    return worst > 0.15f;                      // one kernel: about 0.10 ms; two in a row: about 0.20 ms
+}
+}  // namespace
+
+extern "C" {
+
+gacer_status gacer_probe_stream_queues(void *const *streams, int n, int *group)
+{
+    if (!streams || !group || n < 1 || n > 64) return GACER_EINVAL;
+    hipEvent_t ev[3];
+    for (hipEvent_t &e : ev)
+        if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return GACER_EHIP; }
+    std::vector<int> rep;                      // first stream of every group found so far
+    bool ok = true;
+    for (int i = 0; i < n && ok; ++i) {
+        group[i] = -1;
+        for (int j = 0; j < i; ++j)
+            if (streams[j] == streams[i]) { group[i] = group[j]; break; }
+        for (size_t g = 0; g < rep.size() && group[i] < 0 && ok; ++g)
+            if (streams_serialise((hipStream_t)streams[rep[g]], (hipStream_t)streams[i], ev, &ok)) group[i] = (int)g;
+        if (group[i] < 0) { group[i] = (int)rep.size(); rep.push_back(i); }
+    }
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    if (!ok) { (void)hipGetLastError(); return GACER_EHIP; }
+    return GACER_OK;
+}
+
 gacer_status gacer_issue_stats(gacer_ctx *c, double *host_ms, int *launches)
 {
     if (!c || !host_ms || !launches) return GACER_EINVAL;

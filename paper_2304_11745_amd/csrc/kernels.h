@@ -73,5 +73,7 @@ LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry);   // affine / add / act
 LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry);
+// one wavefront that spins for `ticks` of the constant 100 MHz clock (stream placement probe)
+void launch_spin(hipStream_t s, unsigned long long ticks);
 
 }  // namespace gacer

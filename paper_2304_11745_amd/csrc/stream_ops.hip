@@ -601,4 +601,16 @@ LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry)
     return info(g, "softmax");
 }
 
+// ---- stream placement probe: a wavefront that keeps its queue busy for a known time and always ends --------------
+__global__ void spin_kernel(unsigned long long ticks)
+{
+    const unsigned long long t0 = wall_clock64();
+    for (int guard = 0; guard < (1 << 18) && wall_clock64() - t0 < ticks; ++guard) __builtin_amdgcn_s_sleep(8);   // two exit conditions
+}
+
+void launch_spin(hipStream_t s, unsigned long long ticks)
+{
+    hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, s, ticks);
+}
+
 }  // namespace gacer

@@ -26,7 +26,7 @@ def _ptr(t):
 class Session:
     """One gacer context with its tenants resident in HBM."""
 
-    def __init__(self, tenants, data, device="cuda:0", shared_stream=False):
+    def __init__(self, tenants, data, device="cuda:0", shared_stream=False, place_streams=True):
         if not torch.cuda.is_available():
             raise RuntimeError("a GPU is required: the library has no CPU fallback")
         self.dev = torch.device(device)
@@ -36,6 +36,7 @@ class Session:
         B.check(self.ctx, B.gacer_create(C.byref(self.ctx)))
         self._keep = []
         self.streams = []
+        placed = self._place_streams(tenants) if (place_streams and not shared_stream and len(tenants) > 1) else None
         self.acts = []          # per tenant: list of device tensors (channels-last)
         descs = (B.gacer_tenant * len(tenants))()
         for ti, (t, (x, params)) in enumerate(zip(tenants, data)):
@@ -82,6 +83,8 @@ class Session:
                                     op.groups, _ACT[op.act], alpha)
             if shared_stream and self.streams:
                 s = self.streams[0]
+            elif placed is not None:
+                s = placed[ti]
             else:
                 s = torch.cuda.Stream(device=self.dev)
             self.streams.append(s)
@@ -92,6 +95,34 @@ class Session:
         torch.cuda.synchronize(self.dev)
         self._descs = descs
         B.check(self.ctx, B.gacer_load_tenants(self.ctx, descs, len(tenants)))
+
+    # -- stream placement --------------------------------------------------------------------------
+    def _place_streams(self, tenants):
+        """One stream per tenant, chosen so that tenants spread over the device's hardware queues: streams that share a
+        queue serialise (see gacer_probe_stream_queues).  Candidates are probed, then tenants are placed longest first
+        on the least loaded queue, by a rough time estimate (MFMA time plus a per-launch cost)."""
+        from synth import gemm_macs
+        cands = [torch.cuda.Stream(device=self.dev) for _ in range(16)]
+        arr = (C.c_void_p * len(cands))(*[c.cuda_stream for c in cands])
+        grp = (C.c_int * len(cands))()
+        st = B.gacer_probe_stream_queues(arr, len(cands), grp)
+        if st != B.GACER_OK:
+            raise RuntimeError(f"gacer_probe_stream_queues failed with status {st}")
+        by_queue = {}
+        for c, g in zip(cands, grp):
+            by_queue.setdefault(g, []).append(c)
+        self.queue_groups = len(by_queue)
+        est = [2.0 * gemm_macs(t) / (4.0e14 if t.dtype == "bf16" else 1.0e14) + 6e-6 * len(t.ops) for t in tenants]
+        load = {g: 0.0 for g in by_queue}
+        first = {g: by_queue[g][0] for g in by_queue}
+        placed = [None] * len(tenants)
+        self.tenant_queue = [None] * len(tenants)
+        for ti in sorted(range(len(tenants)), key=lambda i: -est[i]):
+            g = min(load, key=lambda q: (load[q], q))
+            placed[ti] = by_queue[g].pop(0) if by_queue[g] else first[g]
+            self.tenant_queue[ti] = g
+            load[g] += est[ti]
+        return placed
 
     # -- plan ------------------------------------------------------------------------------------
     def set_plan(self, splits=(), syncs=()):

@@ -154,6 +154,36 @@ def test_random_conv_shapes(gpu, dtype):
     _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
 
 
+def test_stream_placement_over_hardware_queues(gpu):
+    """Streams that share a hardware queue serialise: the probe must give the same grouping twice, the harness must put
+    up to `queues` tenants on distinct queues, and placement must not change any output."""
+    import ctypes as C
+    import torch
+    from paper_2304_11745_amd import binding as B
+    streams = [torch.cuda.Stream() for _ in range(12)]
+    arr = (C.c_void_p * len(streams))(*[s.cuda_stream for s in streams])
+    g1, g2 = (C.c_int * len(streams))(), (C.c_int * len(streams))()
+    assert B.gacer_probe_stream_queues(arr, len(streams), g1) == B.GACER_OK
+    assert B.gacer_probe_stream_queues(arr, len(streams), g2) == B.GACER_OK
+    assert list(g1) == list(g2)
+    queues = len(set(g1))
+    assert 1 <= queues <= len(streams) and g1[0] == 0 and max(g1) == queues - 1
+    tenants, data = synth.build_config(4, "small")
+    outs = []
+    for place in (True, False):
+        sess = gpu.Session(tenants, data, place_streams=place)
+        if place:
+            assert sess.queue_groups == queues
+            used = [sess.tenant_queue.count(q) for q in range(queues)]
+            assert sum(used) == len(tenants) and max(used) - min(used) <= 1          # tenants spread evenly over the queues
+            assert len({s.cuda_stream for s in sess.streams}) == len(tenants)      # and still one stream each
+        sess.poison_outputs()
+        sess.run(B.GACER_MODE_STREAM_PARALLEL, 2)
+        outs.append([sess.output_bytes(i) for i in range(len(tenants))])
+        sess.close()
+    assert outs[0] == outs[1]
+
+
 def test_captured_round_replays_bit_exact(gpu):
     """A round captured into a HIP graph must reproduce the eager round bit for bit, on every replay, with
     eager rounds and synchronisations in between, for all three modes and a decomposed, pointer-ordered plan."""

@@ -179,6 +179,15 @@ def test_chunk_list_validation(ctx):
     assert B.gacer_set_plan(ctx, None) == B.GACER_OK
 
 
+def test_probe_stream_queues_rejects_bad_arguments():
+    grp = (C.c_int * 4)()
+    arr = (C.c_void_p * 4)()
+    assert B.gacer_probe_stream_queues(None, 4, grp) == B.GACER_EINVAL
+    assert B.gacer_probe_stream_queues(arr, 4, None) == B.GACER_EINVAL
+    assert B.gacer_probe_stream_queues(arr, 0, grp) == B.GACER_EINVAL
+    assert B.gacer_probe_stream_queues(arr, 65, grp) == B.GACER_EINVAL
+
+
 def _edges(ctx, matrix_P):
     n_ptr = len(matrix_P[0])
     flat = (C.c_int * max(1, len(matrix_P) * n_ptr))(*[p for P in matrix_P for p in P])
