@@ -93,7 +93,8 @@ def choose_plan(sess, B, trial_rounds):
     sp, sy = cands[best]
     # measured refinement on top of the best candidate (heaviest operators of the heaviest tenants)
     t0 = time.perf_counter()
-    sp2, sy2, ms2 = sess.refine_plan(rows, sp, sy, rounds=trial_rounds, log=log)
+    sess.set_plan(sp, sy)
+    sp2, sy2, ms2 = sess.refine_plan(rows, rounds=trial_rounds)
     t_refine = time.perf_counter() - t0
     results["refined"] = ms2
     chosen = best

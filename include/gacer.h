@@ -137,8 +137,17 @@ typedef struct { int tenant, op; gacer_axis axis; int factor; float ms; int work
 /* One kernel launch of a round, as measured by gacer_trace_run: average duration, algorithmic
  * work of the launched sub-range (flops = 2*MACs for conv/GEMM/attention launches, 0 otherwise;
  * bytes = inputs read once + parameters read once + output written once, at the tensor dtype),
- * grid size and the kernel variant that ran. */
-typedef struct { int tenant, op, chunk; float ms; double flops; double bytes; int workgroups; char kernel[40]; } gacer_launch_stat;
+ * grid size and the kernel variant that ran.  start_ms / end_ms place the kernel inside the LAST traced
+ * round: its begin and end on the device clock, counted from the moment that round was released on
+ * tenant 0's stream -- what a test needs to see that one cluster ends before the next begins (Eq. 6). */
+typedef struct {
+    int tenant, op, chunk;
+    float ms;
+    double flops, bytes;
+    int workgroups;
+    char kernel[40];
+    float start_ms, end_ms;
+} gacer_launch_stat;
 
 typedef enum { GACER_MODE_PLAN = 0, GACER_MODE_SEQUENTIAL = 1, GACER_MODE_STREAM_PARALLEL = 2 } gacer_mode;
 
@@ -190,14 +199,15 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *ctx, const int *P, int n_ptr, g
 gacer_status gacer_run(gacer_ctx *ctx, int mode, int rounds, float *ms_per_round);
 
 /*
- * Measurement aid: like gacer_run, but every kernel launch is bracketed by a hipEvent pair on the
- * stream it runs on, so that per-launch durations under the chosen mode (including contention from
- * the other tenants' streams) can be read back.  out[k].ms is the mean over `rounds` of the bracket
- * time minus what an event pair reads with nothing between its two records (marker processing, about
- * 4 us, measured at the start of the call behind pending work on the same queue).  Writes up to
- * `cap` rows (launch order of one round; an operator whose K range is cut into slices contributes its
- * slice kernel and its finishing pass as two rows) and the row count to *n; cap = 0 sizes.  The event pairs
- * perturb the schedule slightly; throughput must be taken from gacer_run.
+ * Measurement aid: like gacer_run (same issue loop, one thread or one per tenant as set), but every kernel
+ * is launched together with a start / stop event pair that the runtime stamps with the kernel's own begin
+ * and end on the device clock -- the interval a profiler's kernel trace reports for the dispatch -- so that
+ * per-launch durations under the chosen mode (including contention from the other tenants' streams) and
+ * the position of every launch inside the round can be read back.  out[k].ms is the mean duration over
+ * `rounds`; start_ms / end_ms are those of the last round.  Writes up to `cap` rows (issue order of one
+ * round; an operator whose K range is cut into slices contributes its slice kernel and its finishing pass
+ * as two rows) and the row count to *n; cap = 0 sizes.  Captured graphs are not replayed here.  The
+ * events cost host time per launch; throughput must be taken from gacer_run.
  */
 gacer_status gacer_trace_run(gacer_ctx *ctx, int mode, int rounds, gacer_launch_stat *out, size_t cap, size_t *n);
 
@@ -235,8 +245,9 @@ gacer_status gacer_launch_count(gacer_ctx *ctx, int mode, int *count);
  * discussed in Section 4.2 and Section 5.5).  Outputs are identical to the uncaptured run.  The capture is
  * dropped by gacer_set_plan, gacer_load_tenants and gacer_release_graphs.  Tensor pointers are baked in.
  * HIP runtimes older than 7.2 crash inside hipStreamEndCapture when three or more captured streams wait on
- * each other's events mutually; on such a runtime the call refuses (GACER_EPLAN) a plan in which operators of
- * more than one tenant wait on two or more events.  Hub barriers from gacer_plan_from_pointers are accepted.
+ * each other's events mutually; on such a runtime the call refuses (GACER_EPLAN) a plan whose edges, taken
+ * tenant by tenant, close a ring of three or more tenants (a waits on b, b on c, c on a).  Barriers from
+ * gacer_plan_from_pointers that all share one hub tenant only pair the hub with each member and are accepted.
  */
 gacer_status gacer_capture(gacer_ctx *ctx, int mode);
 gacer_status gacer_release_graphs(gacer_ctx *ctx);
@@ -261,9 +272,35 @@ gacer_status gacer_set_issue_threads(gacer_ctx *ctx, int enable);
  */
 gacer_status gacer_probe_stream_queues(void *const *streams, int n, int *group);
 
-/* Host cost of the issue loop (Section 4.2, "more operators ... more CPU operators issuing overhead"): wall time
- * the last gacer_run spent enqueueing its rounds, before it started to wait, and the number of operator
- * launches it enqueued. */
+/*
+ * Stream placement proper (the per-tenant streams of Section 2.1, spread over the hardware queues found by
+ * gacer_probe_stream_queues).  `tenants` are the n descriptors about to be loaded (their `stream` fields are ignored),
+ * `candidates` are n_cand streams created by the caller (n_cand <= 64; about 4 per expected queue is plenty).  The call
+ * probes the candidates, estimates every tenant's cost from its operator list (matrix-core work plus a per-launch
+ * cost) and places tenants longest first on the least loaded queue.  chosen[i] receives the index of the candidate
+ * stream for tenant i, queue_of[i] (may be NULL) its queue, *n_queues (may be NULL) the number of queues found.  Up
+ * to n_queues tenants get queues of their own; further tenants share, and once a queue has no unused candidate left
+ * its tenants share one stream.
+ */
+gacer_status gacer_place_streams(const gacer_tenant *tenants, int n, void *const *candidates, int n_cand, int *chosen,
+                                 int *queue_of, int *n_queues);
+
+/*
+ * Measured refinement of the installed plan: the greedy spatial step of Section 4.2 ("Overall Spatial Regulation")
+ * with the GPU instead of the residue model as the judge.  Tenants are visited in order of their profiled time
+ * (`prof`: the table of gacer_profile); for each, the heaviest quarter of its not yet decomposed operators is
+ * decomposed -- batch x2, batch x4, output channels x2, or the chunk list {3/4, 1/4} of the batch -- and the first
+ * option that lowers the median makespan of `trial_rounds` rounds by more than the fraction `min_gain` is kept.
+ * The plan's edges are left as they are.  The refined plan stays installed and is also returned in *out (free with
+ * gacer_plan_free); *ms_out (may be NULL) receives its measured makespan.  Outputs stay bit-identical: every
+ * candidate is a valid plan.  Runs 3 + trial_rounds rounds per candidate.
+ */
+gacer_status gacer_refine(gacer_ctx *ctx, const gacer_prof *prof, size_t n, int trial_rounds, float min_gain,
+                          gacer_plan **out, float *ms_out);
+
+/* Host cost of the issue loop (the spatial-granularity discussion of Section 5.4, Table 3: decomposition adds
+ * operators, and every operator costs the host an issue): wall time the last gacer_run spent enqueueing its
+ * rounds, before it started to wait, and the number of operator launches it enqueued. */
 gacer_status gacer_issue_stats(gacer_ctx *ctx, double *host_ms, int *launches);
 
 #ifdef __cplusplus

@@ -218,6 +218,20 @@ def _eval_op(t, op, T, P, y, n_rng, c_rng):
         raise ValueError(k)
 
 
+def run_op(t, i, tensors, params):
+    """Operator i of the tenant evaluated on the given tensor list (float32 NCHW arrays; only the operator's own
+    inputs are read), with bfloat16 storage of the result in bf16 tenants.  Lets a test check one operator on inputs
+    that did not come from the oracle's own earlier operators."""
+    op = t.ops[i]
+    P = [np.ascontiguousarray(p, dtype=np.float32) for p in params]
+    T = [None if a is None else np.ascontiguousarray(a, dtype=np.float32) for a in tensors]
+    y = np.zeros(t.tensors[op.out], np.float32)
+    _eval_op(t, op, T, P, y, None, None)
+    if t.dtype == "bf16":
+        lib().orc_round_bf16(_p(y), y.size)
+    return y
+
+
 def run_tenant(t, x, params, splits=None, keep_all=False):
     """Forward pass.  ``splits`` maps op index -> (axis, factor), axis in {'batch','cout'}.
     Returns the output tensor (or the list of all tensors with keep_all)."""

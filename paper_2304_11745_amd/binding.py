@@ -24,7 +24,8 @@ GACER_MODE_PLAN, GACER_MODE_SEQUENTIAL, GACER_MODE_STREAM_PARALLEL = range(3)
 EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_plan", "gacer_plan_from_pointers",
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
            "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats", "gacer_capture",
-           "gacer_release_graphs", "gacer_set_issue_threads", "gacer_probe_stream_queues"]
+           "gacer_release_graphs", "gacer_set_issue_threads", "gacer_probe_stream_queues", "gacer_place_streams",
+           "gacer_refine"]
 
 
 class gacer_tensor(C.Structure):
@@ -65,7 +66,8 @@ class gacer_prof(C.Structure):
 
 class gacer_launch_stat(C.Structure):
     _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("chunk", C.c_int), ("ms", C.c_float), ("flops", C.c_double),
-                ("bytes", C.c_double), ("workgroups", C.c_int), ("kernel", C.c_char * 40)]
+                ("bytes", C.c_double), ("workgroups", C.c_int), ("kernel", C.c_char * 40), ("start_ms", C.c_float),
+                ("end_ms", C.c_float)]
 
 
 def _load():
@@ -97,6 +99,10 @@ def _load():
     lib.gacer_release_graphs.argtypes = [ctx]
     lib.gacer_issue_stats.argtypes = [ctx, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.gacer_probe_stream_queues.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_int)]
+    lib.gacer_place_streams.argtypes = [C.POINTER(gacer_tenant), C.c_int, C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_int),
+                                        C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.gacer_refine.argtypes = [ctx, C.POINTER(gacer_prof), C.c_size_t, C.c_int, C.c_float, C.POINTER(C.POINTER(gacer_plan)),
+                                 C.POINTER(C.c_float)]
     return lib
 
 
@@ -120,6 +126,8 @@ gacer_capture = lib.gacer_capture
 gacer_set_issue_threads = lib.gacer_set_issue_threads
 gacer_release_graphs = lib.gacer_release_graphs
 gacer_probe_stream_queues = lib.gacer_probe_stream_queues
+gacer_place_streams = lib.gacer_place_streams
+gacer_refine = lib.gacer_refine
 
 
 class GacerError(RuntimeError):

@@ -37,8 +37,17 @@ struct OpExec {
     int pre_record = -1;        // event recorded after the waits and before the first chunk (barrier hub)
 };
 
+// Event pairs of a traced call: rounds x kernels-per-round x {start, stop}; row_of[tenant][op][chunk] is the row of
+// that chunk's first kernel within one round (a split-K chunk owns two consecutive rows).
+struct Trace {
+    size_t per_round = 0;
+    std::vector<hipEvent_t> ev;
+    std::vector<std::vector<std::vector<size_t>>> row_of;
+};
+
 struct Ctx {
     int device = 0;
+    bool has_device = false;
     int n_cu = 256;
     std::vector<Tenant> tenants;
     bool loaded = false;
@@ -58,6 +67,8 @@ struct Ctx {
     std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
     hipGraphExec_t graph_exec[3] = {nullptr, nullptr, nullptr};   // captured round per mode (optional)
     bool issue_threads = false;                     // one host thread per tenant enqueues that tenant's stream
+    std::vector<float *> ws_run;                    // split-K workspace each tenant uses in the call in progress
+    Trace *trace = nullptr;                         // set while gacer_trace_run issues its rounds
     double last_issue_ms = 0;                       // host time the last gacer_run spent enqueueing
     int last_issue_launches = 0;
     std::string err;
@@ -69,8 +80,11 @@ bool axis_legal(gacer_opkind kind, gacer_axis axis);
 void chunk_range(int extent, int factor, int j, int *lo, int *hi);
 // builds the launch of operator `op` restricted to batch items [b_lo,b_hi) and channels [c_lo,c_hi)
 Launch make_launch(const Tenant &t, int op, int b_lo, int b_hi, int c_lo, int c_hi);
-LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase = 0);
+// `ws` is the split-K workspace of the launch's tenant (only read when the operator's K range is cut into slices)
+LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase = 0, float *ws = nullptr);
 void drop_graphs(Ctx *c);
+// every plan the library hands out is built here (and released by gacer_plan_free)
+gacer_plan *make_plan(const std::vector<gacer_split> &splits, const std::vector<gacer_sync> &syncs);
 
 }  // namespace gacer
 

@@ -1,7 +1,18 @@
 // Small device helpers shared by the streaming kernels (element conversion, activations).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include "kernels.h"
+
+// every kernel of the library is enqueued through this macro (see LaunchTimer in kernels.h)
+#define GACER_LAUNCH(kernel, grid, block, shmem, stream, ...)                                                                \
+    do {                                                                                                                     \
+        if (gacer::launch_timer)                                                                                             \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, gacer::launch_timer->start, gacer::launch_timer->stop, \
+                                  0, __VA_ARGS__);                                                                           \
+        else                                                                                                                 \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                             \
+    } while (0)
 
 namespace gacer {
 

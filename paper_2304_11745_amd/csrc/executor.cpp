@@ -107,7 +107,7 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
         g.m_lo = b_lo * q_out * g.Ho * g.Wo; g.m_hi = b_hi * q_out * g.Ho * g.Wo;
         g.n_lo = c_lo; g.n_hi = c_hi;
         g.ksplit = t.ksplit[oi]; g.kb_per_slice = t.kb_per_slice[oi];
-        g.ws = t.ws;
+        g.ws = nullptr;                       // the workspace is chosen per call (see enqueue)
         break;
     }
     case GACER_BGEMM_QK: {
@@ -171,10 +171,17 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
     return l;
 }
 
-LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase)
+LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase, float *ws)
 {
     switch (l.kind) {
-    case LK_IGEMM: return launch_igemm(l.g, s, dry, phase);
+    case LK_IGEMM:
+        if (l.g.ksplit > 1 && !dry) {
+            if (!ws) return launch_igemm(l.g, s, true, phase);     // never launch slices without a workspace
+            GemmArgs g = l.g;
+            g.ws = ws;
+            return launch_igemm(g, s, dry, phase);
+        }
+        return launch_igemm(l.g, s, dry, phase);
     case LK_DWCONV: return launch_dwconv(l.s, s, dry);
     case LK_MAXPOOL: return launch_maxpool(l.s, s, dry);
     case LK_GAVGPOOL: return launch_gavgpool(l.s, s, dry);
@@ -182,6 +189,34 @@ LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase)
     case LK_SOFTMAX: return launch_softmax(l.s, s, dry);
     default: return launch_eltwise(l.s, s, dry);
     }
+}
+
+// Library-allocated plan.  The split array carries one extra trailing element whose `sizes` owns the pool that the
+// chunk lists of the real elements point into; gacer_plan_free releases it.
+gacer_plan *make_plan(const std::vector<gacer_split> &splits, const std::vector<gacer_sync> &syncs)
+{
+    size_t pool_n = 0;
+    for (const gacer_split &s : splits)
+        if (s.sizes) pool_n += (size_t)s.factor;
+    gacer_plan *pl = new (std::nothrow) gacer_plan();
+    gacer_split *sp = new (std::nothrow) gacer_split[splits.size() + 1];
+    gacer_sync *sy = new (std::nothrow) gacer_sync[syncs.size() + 1];
+    int *pool = new (std::nothrow) int[pool_n + 1];
+    if (!pl || !sp || !sy || !pool) { delete pl; delete[] sp; delete[] sy; delete[] pool; return nullptr; }
+    size_t used = 0;
+    for (size_t k = 0; k < splits.size(); ++k) {
+        sp[k] = splits[k];
+        if (splits[k].sizes) {
+            std::copy(splits[k].sizes, splits[k].sizes + splits[k].factor, pool + used);
+            sp[k].sizes = pool + used;
+            used += (size_t)splits[k].factor;
+        }
+    }
+    sp[splits.size()] = {-1, -1, GACER_AXIS_NONE, 0, pool};
+    std::copy(syncs.begin(), syncs.end(), sy);
+    pl->n_split = (int)splits.size(); pl->split = sp;
+    pl->n_sync = (int)syncs.size(); pl->sync = sy;
+    return pl;
 }
 
 }  // namespace gacer
@@ -353,6 +388,8 @@ static void expand_plain(Ctx *c)
             if (i < c->tenants[t].ops.size()) c->par_order.push_back({(int)t, (int)i});
 }
 
+namespace { gacer_status ensure_plan_events(Ctx *c); }
+
 // Validates and expands (splits, syncs) into c->plan_exec / plan_order.  On failure nothing changes.
 static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits, const std::vector<gacer_sync> &syncs)
 {
@@ -468,7 +505,8 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
     c->syncs = syncs;
     c->plan_exec.swap(ex);
     c->plan_order.swap(order);
-    c->n_sync_events = ev_of.size();     // the events themselves are created by the first run that needs them
+    c->n_sync_events = ev_of.size();
+    if (c->has_device) return ensure_plan_events(c);    // fork / join / edge events are created at set-up, not by a run
     return GACER_OK;
 }
 
@@ -483,6 +521,7 @@ gacer_status gacer_create(gacer_ctx **out)
     int dev = 0;
     if (hipGetDevice(&dev) == hipSuccess) {
         c->device = dev;
+        c->has_device = true;
         int cu = 0;
         if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cu > 0) c->n_cu = cu;
     } else {
@@ -608,14 +647,8 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *c, const int *P, int n_ptr, gac
             edges.push_back({hub, hub_first, b, seg_begin(b), 1});
         }
     }
-    gacer_plan *pl = new (std::nothrow) gacer_plan();
+    gacer_plan *pl = make_plan({}, edges);
     if (!pl) return fail(c, GACER_ENOMEM, "out of memory");
-    pl->n_split = 0; pl->split = nullptr;
-    pl->n_sync = (int)edges.size();
-    gacer_sync *arr = edges.empty() ? nullptr : new (std::nothrow) gacer_sync[edges.size()];
-    if (!edges.empty() && !arr) { delete pl; return fail(c, GACER_ENOMEM, "out of memory"); }
-    std::copy(edges.begin(), edges.end(), arr);
-    pl->sync = arr;
     *out = pl;
     return GACER_OK;
 }
@@ -623,31 +656,76 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *c, const int *P, int n_ptr, gac
 void gacer_plan_free(gacer_plan *p)
 {
     if (!p) return;
+    if (p->split) delete[] p->split[p->n_split].sizes;     // the chunk-list pool (see make_plan)
     delete[] p->split;
     delete[] p->sync;
     delete p;
 }
 
-static gacer_status issue_op(Ctx *c, const OpExec &e, hipStream_t s, bool with_events)
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------------
+// Issue loop.  One function enqueues an operator (its waits, its chunk launches, its records); it serves the
+// single-threaded loop, the per-tenant host threads and the traced runs alike.
+namespace {
+
+// Host-side ordering between issuing threads: an event must have been recorded by its owner thread before another
+// thread may enqueue a wait on it (a wait on an event that was never recorded returns at once).  Generation
+// counters, one per event, carry that; with one issuing thread the pointer is null.
+struct IssueGate {
+    std::unique_ptr<std::atomic<long>[]> ev_gen, join_gen;
+    std::atomic<long> fork_gen{0};
+    std::atomic<int> failed{0};
+    bool wait_gen(const std::atomic<long> &g, long need) const
+    {
+        while (g.load(std::memory_order_acquire) < need) {
+            if (failed.load(std::memory_order_relaxed)) return false;
+            std::this_thread::yield();
+        }
+        return true;
+    }
+};
+
+// Enqueues operator (t, i) of round `round` on stream s.  Returns the first HIP error, or hipErrorUnknown when another
+// issuing thread has failed.
+hipError_t issue_op(Ctx *c, int t, int i, const OpExec &e, hipStream_t s, bool with_events, int round, IssueGate *gate)
 {
-    if (with_events)
-        for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
-    if (with_events && e.pre_record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.pre_record], s));
-    for (const Launch &l : e.chunks) enqueue(l, s, false);
-    if (with_events && e.record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.record], s));
-    return GACER_OK;
+    hipError_t err;
+    if (with_events) {
+        for (int w : e.waits) {
+            if (gate && !gate->wait_gen(gate->ev_gen[w], round + 1)) return hipErrorUnknown;
+            if ((err = hipStreamWaitEvent(s, c->sync_events[w], 0)) != hipSuccess) return err;
+        }
+        if (e.pre_record >= 0) {
+            if ((err = hipEventRecord(c->sync_events[e.pre_record], s)) != hipSuccess) return err;
+            if (gate) gate->ev_gen[e.pre_record].store(round + 1, std::memory_order_release);
+        }
+    }
+    float *ws = c->ws_run[t];
+    if (Trace *tr = c->trace) {
+        for (size_t j = 0; j < e.chunks.size(); ++j) {
+            const int phases = enqueue(e.chunks[j], s, true).phases;
+            for (int ph = 1; ph <= phases; ++ph) {
+                const size_t k = 2 * ((size_t)round * tr->per_round + tr->row_of[t][i][j] + (size_t)(ph - 1));
+                const LaunchTimer lt = {tr->ev[k], tr->ev[k + 1]};
+                launch_timer = &lt;
+                enqueue(e.chunks[j], s, false, phases == 1 ? 0 : ph, ws);
+                launch_timer = nullptr;
+            }
+        }
+    } else {
+        for (const Launch &l : e.chunks) enqueue(l, s, false, 0, ws);
+    }
+    if (with_events && e.record >= 0) {
+        if ((err = hipEventRecord(c->sync_events[e.record], s)) != hipSuccess) return err;
+        if (gate) gate->ev_gen[e.record].store(round + 1, std::memory_order_release);
+    }
+    return hipSuccess;
 }
 
-static gacer_status ensure_events(Ctx *c, int rounds)
+gacer_status ensure_plan_events(Ctx *c)
 {
     const int NT = (int)c->tenants.size();
-    while ((int)c->t_start.size() < rounds) {
-        hipEvent_t a, b;
-        HIPCHK(c, hipEventCreate(&a));
-        c->t_start.push_back(a);
-        HIPCHK(c, hipEventCreate(&b));
-        c->t_end.push_back(b);
-    }
     while (c->sync_events.size() < c->n_sync_events) {
         hipEvent_t ev;
         HIPCHK(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
@@ -661,17 +739,27 @@ static gacer_status ensure_events(Ctx *c, int rounds)
     return GACER_OK;
 }
 
-// Enqueues one round: fork from tenant 0's stream, every operator in issue order, join back.
-static gacer_status issue_round(Ctx *c, int mode)
+gacer_status ensure_events(Ctx *c, int rounds)
+{
+    while ((int)c->t_start.size() < rounds) {
+        hipEvent_t a, b;
+        HIPCHK(c, hipEventCreate(&a));
+        c->t_start.push_back(a);
+        HIPCHK(c, hipEventCreate(&b));
+        c->t_end.push_back(b);
+    }
+    return ensure_plan_events(c);
+}
+
+// Enqueues one round from the calling thread: fork from tenant 0's stream, every operator in issue order, join back.
+gacer_status issue_round(Ctx *c, int mode, int round)
 {
     const int NT = (int)c->tenants.size();
     hipStream_t s0 = c->tenants[0].stream;
     if (mode == GACER_MODE_SEQUENTIAL) {
         for (int t = 0; t < NT; ++t)
-            for (const OpExec &e : c->plain_exec[t]) {
-                gacer_status st = issue_op(c, e, s0, false);
-                if (st != GACER_OK) return st;
-            }
+            for (int i = 0; i < (int)c->plain_exec[t].size(); ++i)
+                HIPCHK(c, issue_op(c, t, i, c->plain_exec[t][i], s0, false, round, nullptr));
         return GACER_OK;
     }
     hipEvent_t fork = c->join_events[NT];
@@ -681,10 +769,8 @@ static gacer_status issue_round(Ctx *c, int mode)
     const bool plan = (mode == GACER_MODE_PLAN);
     const auto &order = plan ? c->plan_order : c->par_order;
     const auto &ex = plan ? c->plan_exec : c->plain_exec;
-    for (const auto &to : order) {
-        gacer_status st = issue_op(c, ex[to.first][to.second], c->tenants[to.first].stream, plan);
-        if (st != GACER_OK) return st;
-    }
+    for (const auto &to : order)
+        HIPCHK(c, issue_op(c, to.first, to.second, ex[to.first][to.second], c->tenants[to.first].stream, plan, round, nullptr));
     for (int t = 1; t < NT; ++t)
         if (c->tenants[t].stream != s0) {
             HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
@@ -693,7 +779,157 @@ static gacer_status issue_round(Ctx *c, int mode)
     return GACER_OK;
 }
 
-}  // extern "C"
+// One host thread per tenant (Section 2.1: every tenant's DFG is wrapped into a processing thread that feeds its
+// own stream).  The calling thread plays tenant 0 and owns the fork / join of every round.
+struct ThreadedIssue {
+    Ctx *c;
+    int mode, rounds;
+    IssueGate gate;
+    std::mutex err_mu;
+    std::string err;
+
+    void fail_with(const char *what, hipError_t e)
+    {
+        std::lock_guard<std::mutex> g(err_mu);
+        if (!gate.failed.exchange(1)) err = std::string(what) + " failed: " + hipGetErrorString(e);
+    }
+    bool issue_tenant(int t, int r)
+    {
+        const bool plan = (mode == GACER_MODE_PLAN);
+        const auto &ex = plan ? c->plan_exec[t] : c->plain_exec[t];
+        for (int i = 0; i < (int)ex.size(); ++i) {
+            const hipError_t e = issue_op(c, t, i, ex[i], c->tenants[t].stream, plan, r, &gate);
+            if (e != hipSuccess) { fail_with("enqueueing an operator", e); return false; }
+        }
+        return true;
+    }
+    void worker(int t)
+    {
+        if (hipSetDevice(c->device) != hipSuccess) { fail_with("hipSetDevice", hipGetLastError()); return; }
+        const int NT = (int)c->tenants.size();
+        for (int r = 0; r < rounds; ++r) {
+            if (!gate.wait_gen(gate.fork_gen, r + 1)) return;
+            hipError_t e = hipStreamWaitEvent(c->tenants[t].stream, c->join_events[NT], 0);
+            if (e != hipSuccess) { fail_with("hipStreamWaitEvent(fork)", e); return; }
+            if (!issue_tenant(t, r)) return;
+            e = hipEventRecord(c->join_events[t], c->tenants[t].stream);
+            if (e != hipSuccess) { fail_with("hipEventRecord(join)", e); return; }
+            gate.join_gen[t].store(r + 1, std::memory_order_release);
+        }
+    }
+#define TI_CHK(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { fail_with(#call, e_); return false; } } while (0)
+    bool lead()
+    {
+        const int NT = (int)c->tenants.size();
+        hipStream_t s0 = c->tenants[0].stream;
+        for (int r = 0; r < rounds; ++r) {
+            TI_CHK(hipEventRecord(c->t_start[r], s0));
+            TI_CHK(hipEventRecord(c->join_events[NT], s0));
+            gate.fork_gen.store(r + 1, std::memory_order_release);
+            if (!issue_tenant(0, r)) return false;
+            for (int t = 1; t < NT; ++t) {
+                if (!gate.wait_gen(gate.join_gen[t], r + 1)) return false;
+                TI_CHK(hipStreamWaitEvent(s0, c->join_events[t], 0));
+            }
+            TI_CHK(hipEventRecord(c->t_end[r], s0));
+        }
+        return true;
+    }
+#undef TI_CHK
+};
+
+gacer_status run_threaded(Ctx *c, int mode, int rounds)
+{
+    const int NT = (int)c->tenants.size();
+    ThreadedIssue ti;
+    ti.c = c; ti.mode = mode; ti.rounds = rounds;
+    const size_t ne = std::max<size_t>(1, c->sync_events.size());
+    ti.gate.ev_gen.reset(new std::atomic<long>[ne]);
+    ti.gate.join_gen.reset(new std::atomic<long>[NT]);
+    for (size_t i = 0; i < ne; ++i) ti.gate.ev_gen[i].store(0);
+    for (int t = 0; t < NT; ++t) ti.gate.join_gen[t].store(0);
+    std::vector<std::thread> workers;
+    for (int t = 1; t < NT; ++t) workers.emplace_back([&ti, t] { ti.worker(t); });
+    const bool ok = ti.lead();
+    if (!ok) ti.gate.failed.store(1);
+    for (std::thread &w : workers) w.join();
+    if (ti.gate.failed.load()) return fail(c, GACER_EHIP, "%s", ti.err.empty() ? "threaded issue failed" : ti.err.c_str());
+    return GACER_OK;
+}
+
+bool distinct_streams(const Ctx *c)
+{
+    for (size_t a = 0; a < c->tenants.size(); ++a)
+        for (size_t b = a + 1; b < c->tenants.size(); ++b)
+            if (c->tenants[a].stream == c->tenants[b].stream) return false;
+    return true;
+}
+
+// Enqueues `rounds` rounds with per-round timing events and waits for them.  c->ws_run and c->trace are set by the caller.
+gacer_status run_rounds(Ctx *c, int mode, int rounds, bool allow_graph)
+{
+    hipStream_t s0 = c->tenants[0].stream;
+    const auto host_t0 = std::chrono::steady_clock::now();
+    const bool graph = allow_graph && c->graph_exec[mode];
+    const bool threaded = c->issue_threads && mode != GACER_MODE_SEQUENTIAL && !graph && c->tenants.size() > 1 && distinct_streams(c);
+    gacer_status st = GACER_OK;
+    if (threaded) {
+        st = run_threaded(c, mode, rounds);
+    } else {
+        for (int r = 0; r < rounds && st == GACER_OK; ++r) {
+            HIPCHK(c, hipEventRecord(c->t_start[r], s0));
+            if (graph) HIPCHK(c, hipGraphLaunch(c->graph_exec[mode], s0));
+            else st = issue_round(c, mode, r);
+            if (st == GACER_OK) HIPCHK(c, hipEventRecord(c->t_end[r], s0));
+        }
+    }
+    if (st != GACER_OK) { (void)hipDeviceSynchronize(); return st; }
+    c->last_issue_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - host_t0).count();
+    c->last_issue_launches = 0;
+    gacer_launch_count(static_cast<gacer_ctx *>(c), mode, &c->last_issue_launches);
+    c->last_issue_launches *= rounds;
+    HIPCHK(c, hipStreamSynchronize(s0));
+    HIPCHK(c, hipGetLastError());
+    return GACER_OK;
+}
+
+void use_tenant_workspaces(Ctx *c)
+{
+    c->ws_run.resize(c->tenants.size());
+    for (size_t t = 0; t < c->tenants.size(); ++t) c->ws_run[t] = c->tenants[t].ws;
+}
+
+// True when three or more tenants wait on each other's events in a ring (tenant a waits on b, b on c, ..., back to a),
+// judged on the tenant-level graph of the plan's edges.  Mutual pairs (a <-> b, the shape of a hub barrier) are not rings.
+// Simple paths are enumerated depth first; a search that grows beyond its step budget answers "ring" (the safe side).
+bool tenants_wait_in_a_ring(const Ctx *c)
+{
+    const int NT = (int)c->tenants.size();
+    std::vector<std::vector<int>> waits_on(NT);
+    for (const gacer_sync &e : c->syncs)
+        if (std::find(waits_on[e.dst_tenant].begin(), waits_on[e.dst_tenant].end(), e.src_tenant) == waits_on[e.dst_tenant].end())
+            waits_on[e.dst_tenant].push_back(e.src_tenant);
+    long budget = 200000;
+    std::vector<char> on_path(NT, 0);
+    std::vector<std::pair<int, size_t>> stack;
+    for (int root = 0; root < NT; ++root) {
+        stack.assign(1, {root, 0});
+        on_path.assign(NT, 0);
+        on_path[root] = 1;
+        while (!stack.empty()) {
+            if (--budget < 0) return true;
+            const int node = stack.back().first;
+            if (stack.back().second == waits_on[node].size()) { on_path[node] = 0; stack.pop_back(); continue; }
+            const int nxt = waits_on[node][stack.back().second++];
+            if (nxt == root && stack.size() >= 3) return true;
+            if (nxt > root && !on_path[nxt]) { on_path[nxt] = 1; stack.push_back({nxt, 0}); }   // rings are found from their lowest tenant
+        }
+    }
+    return false;
+}
+
+}  // namespace
+
 namespace gacer {
 void drop_graphs(Ctx *c)
 {
@@ -701,6 +937,7 @@ void drop_graphs(Ctx *c)
         if (c->graph_exec[m]) { (void)hipGraphExecDestroy(c->graph_exec[m]); c->graph_exec[m] = nullptr; }
 }
 }  // namespace gacer
+
 extern "C" {
 
 gacer_status gacer_capture(gacer_ctx *c, int mode)
@@ -708,29 +945,23 @@ gacer_status gacer_capture(gacer_ctx *c, int mode)
     if (!c) return GACER_EINVAL;
     if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_capture before gacer_load_tenants");
     if (mode < 0 || mode > 2) return fail(c, GACER_EINVAL, "bad mode");
-    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
     if (mode == GACER_MODE_PLAN) {
-        // HIP runtimes before 7.2 crash in hipStreamEndCapture on mutual multi-stream event waits
+        // HIP runtimes before 7.2 crash in hipStreamEndCapture when three or more captured streams wait on each other
+        // mutually.  Hub barriers only pair the hub with each member and capture fine.
         int rt = 0;
-        if (hipRuntimeGetVersion(&rt) != hipSuccess || rt < 70200000) {
-            int multi_wait_tenants = 0;
-            for (const auto &t : c->plan_exec) {
-                bool multi = false;
-                for (const OpExec &e : t) multi = multi || e.waits.size() >= 2;
-                multi_wait_tenants += multi ? 1 : 0;
-            }
-            if (multi_wait_tenants > 1)
-                return fail(c, GACER_EPLAN, "this HIP runtime (%d) cannot capture a plan in which operators of several tenants wait on "
-                                            "two or more events; use hub barriers or run uncaptured", rt);
-        }
+        if ((hipRuntimeGetVersion(&rt) != hipSuccess || rt < 70200000) && tenants_wait_in_a_ring(c))
+            return fail(c, GACER_EPLAN, "this HIP runtime (%d) cannot capture a plan in which three or more tenants wait on each "
+                                        "other in a ring; use hub barriers with one hub (gacer_plan_from_pointers) or run uncaptured", rt);
     }
+    if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
     gacer_status st = ensure_events(c, 1);
     if (st != GACER_OK) return st;
     if (c->graph_exec[mode]) { (void)hipGraphExecDestroy(c->graph_exec[mode]); c->graph_exec[mode] = nullptr; }
     hipStream_t s0 = c->tenants[0].stream;
     for (Tenant &t : c->tenants) HIPCHK(c, hipStreamSynchronize(t.stream));
+    use_tenant_workspaces(c);
     HIPCHK(c, hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
-    st = issue_round(c, mode);
+    st = issue_round(c, mode, 0);
     hipGraph_t graph = nullptr;
     const hipError_t e_end = hipStreamEndCapture(s0, &graph);
     if (st != GACER_OK || e_end != hipSuccess || !graph) {
@@ -755,113 +986,6 @@ gacer_status gacer_release_graphs(gacer_ctx *c)
     return GACER_OK;
 }
 
-// One host thread per tenant (Section 2.1: every tenant's DFG is wrapped into a processing thread that feeds
-// its own stream).  Threads enqueue independently; the only host-side coupling is that an event must have been
-// recorded (by its owner thread) before another thread may enqueue a wait on it, tracked with generation counters.
-namespace {
-struct ThreadedIssue {
-    Ctx *c;
-    int mode, rounds;
-    std::atomic<long> fork_gen{0};
-    std::unique_ptr<std::atomic<long>[]> ev_gen, join_gen;
-    std::atomic<int> failed{0};
-    std::mutex err_mu;
-    std::string err;
-
-    void fail_with(const char *what, hipError_t e)
-    {
-        std::lock_guard<std::mutex> g(err_mu);
-        if (!failed.exchange(1)) err = std::string(what) + " failed: " + hipGetErrorString(e);
-    }
-    bool wait_gen(const std::atomic<long> &g, long need) const
-    {
-        while (g.load(std::memory_order_acquire) < need) {
-            if (failed.load(std::memory_order_relaxed)) return false;
-            std::this_thread::yield();
-        }
-        return true;
-    }
-#define TI_CHK(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) { fail_with(#call, e_); return false; } } while (0)
-    // enqueues tenant t's operators of round r on its stream
-    bool issue_tenant(int t, int r)
-    {
-        const bool plan = (mode == GACER_MODE_PLAN);
-        const auto &ex = plan ? c->plan_exec[t] : c->plain_exec[t];
-        hipStream_t s = c->tenants[t].stream;
-        for (const OpExec &e : ex) {
-            if (plan) {
-                for (int w : e.waits) {
-                    if (!wait_gen(ev_gen[w], r + 1)) return false;
-                    TI_CHK(hipStreamWaitEvent(s, c->sync_events[w], 0));
-                }
-                if (e.pre_record >= 0) {
-                    TI_CHK(hipEventRecord(c->sync_events[e.pre_record], s));
-                    ev_gen[e.pre_record].store(r + 1, std::memory_order_release);
-                }
-            }
-            for (const Launch &l : e.chunks) enqueue(l, s, false);
-            if (plan && e.record >= 0) {
-                TI_CHK(hipEventRecord(c->sync_events[e.record], s));
-                ev_gen[e.record].store(r + 1, std::memory_order_release);
-            }
-        }
-        return true;
-    }
-    void worker(int t)
-    {
-        if (hipSetDevice(c->device) != hipSuccess) { fail_with("hipSetDevice", hipGetLastError()); return; }
-        const int NT = (int)c->tenants.size();
-        for (int r = 0; r < rounds; ++r) {
-            if (!wait_gen(fork_gen, r + 1)) return;
-            hipError_t e = hipStreamWaitEvent(c->tenants[t].stream, c->join_events[NT], 0);
-            if (e != hipSuccess) { fail_with("hipStreamWaitEvent(fork)", e); return; }
-            if (!issue_tenant(t, r)) return;
-            e = hipEventRecord(c->join_events[t], c->tenants[t].stream);
-            if (e != hipSuccess) { fail_with("hipEventRecord(join)", e); return; }
-            join_gen[t].store(r + 1, std::memory_order_release);
-        }
-    }
-    // the calling thread plays tenant 0 and owns the fork / join of every round
-    bool lead()
-    {
-        const int NT = (int)c->tenants.size();
-        hipStream_t s0 = c->tenants[0].stream;
-        for (int r = 0; r < rounds; ++r) {
-            TI_CHK(hipEventRecord(c->t_start[r], s0));
-            TI_CHK(hipEventRecord(c->join_events[NT], s0));
-            fork_gen.store(r + 1, std::memory_order_release);
-            if (!issue_tenant(0, r)) return false;
-            for (int t = 1; t < NT; ++t) {
-                if (!wait_gen(join_gen[t], r + 1)) return false;
-                TI_CHK(hipStreamWaitEvent(s0, c->join_events[t], 0));
-            }
-            TI_CHK(hipEventRecord(c->t_end[r], s0));
-        }
-        return true;
-    }
-#undef TI_CHK
-};
-}  // namespace
-
-static gacer_status run_threaded(Ctx *c, int mode, int rounds)
-{
-    const int NT = (int)c->tenants.size();
-    ThreadedIssue ti;
-    ti.c = c; ti.mode = mode; ti.rounds = rounds;
-    const size_t ne = std::max<size_t>(1, c->sync_events.size());
-    ti.ev_gen.reset(new std::atomic<long>[ne]);
-    ti.join_gen.reset(new std::atomic<long>[NT]);
-    for (size_t i = 0; i < ne; ++i) ti.ev_gen[i].store(0);
-    for (int t = 0; t < NT; ++t) ti.join_gen[t].store(0);
-    std::vector<std::thread> workers;
-    for (int t = 1; t < NT; ++t) workers.emplace_back([&ti, t] { ti.worker(t); });
-    const bool ok = ti.lead();
-    if (!ok) ti.failed.store(1);
-    for (std::thread &w : workers) w.join();
-    if (ti.failed.load()) return fail(c, GACER_EHIP, "%s", ti.err.empty() ? "threaded issue failed" : ti.err.c_str());
-    return GACER_OK;
-}
-
 gacer_status gacer_set_issue_threads(gacer_ctx *c, int enable)
 {
     if (!c) return GACER_EINVAL;
@@ -877,32 +1001,9 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
     if (c->ws_missing) return fail(c, GACER_EHIP, "split-K workspace could not be allocated when the tenants were loaded");
     gacer_status st = ensure_events(c, rounds);
     if (st != GACER_OK) return st;
-    hipStream_t s0 = c->tenants[0].stream;
-    const auto host_t0 = std::chrono::steady_clock::now();
-    bool threaded = c->issue_threads && mode != GACER_MODE_SEQUENTIAL && !c->graph_exec[mode] && c->tenants.size() > 1;
-    for (size_t a = 0; threaded && a < c->tenants.size(); ++a)          // threads need one stream per tenant
-        for (size_t b = a + 1; b < c->tenants.size(); ++b)
-            if (c->tenants[a].stream == c->tenants[b].stream) threaded = false;
-    if (threaded) {
-        st = run_threaded(c, mode, rounds);
-        if (st != GACER_OK) { (void)hipDeviceSynchronize(); return st; }
-    }
-    for (int r = 0; r < rounds && !threaded; ++r) {
-        HIPCHK(c, hipEventRecord(c->t_start[r], s0));
-        if (c->graph_exec[mode]) {
-            HIPCHK(c, hipGraphLaunch(c->graph_exec[mode], s0));
-        } else {
-            st = issue_round(c, mode);
-            if (st != GACER_OK) return st;
-        }
-        HIPCHK(c, hipEventRecord(c->t_end[r], s0));
-    }
-    c->last_issue_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - host_t0).count();
-    c->last_issue_launches = 0;
-    gacer_launch_count(c, mode, &c->last_issue_launches);
-    c->last_issue_launches *= rounds;
-    HIPCHK(c, hipStreamSynchronize(s0));
-    HIPCHK(c, hipGetLastError());
+    use_tenant_workspaces(c);
+    st = run_rounds(c, mode, rounds, true);
+    if (st != GACER_OK) return st;
     if (ms_per_round)
         for (int r = 0; r < rounds; ++r) HIPCHK(c, hipEventElapsedTime(&ms_per_round[r], c->t_start[r], c->t_end[r]));
     return GACER_OK;
@@ -950,96 +1051,60 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
         for (int t = 0; t < NT; ++t)
             for (int i = 0; i < (int)c->tenants[t].ops.size(); ++i) order.push_back({t, i});
     } else order = plan ? c->plan_order : c->par_order;
-    size_t total = 0;                          // kernels per round (a split-K chunk is two kernels)
+    Trace tr;
+    tr.row_of.resize(NT);
+    for (int t = 0; t < NT; ++t) tr.row_of[t].resize(c->tenants[t].ops.size());
+    size_t total = 0;                          // kernels per round (a split-K chunk is two kernels), rows in issue order
     for (const auto &to : order)
-        for (const Launch &l : ex[to.first][to.second].chunks) total += (size_t)enqueue(l, nullptr, true).phases;
+        for (const Launch &l : ex[to.first][to.second].chunks) {
+            tr.row_of[to.first][to.second].push_back(total);
+            total += (size_t)enqueue(l, nullptr, true).phases;
+        }
     *n_out = total;
     if (cap == 0 || !out) return GACER_OK;
     if (cap < total) return fail(c, GACER_EINVAL, "trace buffer too small (%zu rows needed)", total);
-    {
-        gacer_status st = ensure_events(c, 1);
-        if (st != GACER_OK) return st;
-    }
-    std::vector<hipEvent_t> ev(2 * total * rounds);
-    for (hipEvent_t &e : ev) HIPCHK(c, hipEventCreate(&e));
-    hipEvent_t fork;
-    HIPCHK(c, hipEventCreateWithFlags(&fork, hipEventDisableTiming));
-    hipStream_t s0 = c->tenants[0].stream;
-    // What an event pair reads with nothing between its two records (marker processing on the queue): measured
-    // here, behind pending work as in a round, and taken off every bracket below.
-    float empty_ms = 0.f;
-    {
-        const int reps = 16;
-        std::vector<float> v;
-        hipEvent_t a, b;
-        HIPCHK(c, hipEventCreate(&a));
-        HIPCHK(c, hipEventCreate(&b));
-        for (int i = 0; i < reps; ++i) {
-            (void)enqueue(ex[order[0].first][order[0].second].chunks[0], s0, false, 0);
-            HIPCHK(c, hipEventRecord(a, s0));
-            HIPCHK(c, hipEventRecord(b, s0));
-            HIPCHK(c, hipStreamSynchronize(s0));
-            float ms = 0.f;
-            HIPCHK(c, hipEventElapsedTime(&ms, a, b));
-            v.push_back(ms);
-        }
-        (void)hipEventDestroy(a);
-        (void)hipEventDestroy(b);
-        std::sort(v.begin(), v.end());
-        empty_ms = v[v.size() / 2];
-    }
-    size_t k = 0;
-    for (int r = 0; r < rounds; ++r) {
-        if (mode != GACER_MODE_SEQUENTIAL) {
-            HIPCHK(c, hipEventRecord(fork, s0));
-            for (int t = 1; t < NT; ++t)
-                if (c->tenants[t].stream != s0) HIPCHK(c, hipStreamWaitEvent(c->tenants[t].stream, fork, 0));
-        }
-        size_t row = 0;
-        for (const auto &to : order) {
-            const OpExec &e = ex[to.first][to.second];
-            hipStream_t s = mode == GACER_MODE_SEQUENTIAL ? s0 : c->tenants[to.first].stream;
-            if (plan) {
-                for (int w : e.waits) HIPCHK(c, hipStreamWaitEvent(s, c->sync_events[w], 0));
-                if (e.pre_record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.pre_record], s));
+    gacer_status st = ensure_events(c, rounds);
+    if (st != GACER_OK) return st;
+    tr.per_round = total;
+    tr.ev.resize(2 * total * (size_t)rounds);
+    for (hipEvent_t &e : tr.ev) HIPCHK(c, hipEventCreate(&e));
+    for (const auto &to : order) {
+        const OpExec &e = ex[to.first][to.second];
+        for (size_t j = 0; j < e.chunks.size(); ++j) {
+            const int phases = enqueue(e.chunks[j], nullptr, true).phases;
+            for (int ph = 1; ph <= phases; ++ph) {
+                gacer_launch_stat &row = out[tr.row_of[to.first][to.second][j] + (size_t)(ph - 1)];
+                const LaunchInfo li = enqueue(e.chunks[j], nullptr, true, phases == 1 ? 0 : ph);
+                row.tenant = to.first; row.op = to.second; row.chunk = (int)j;
+                row.ms = row.start_ms = row.end_ms = 0.f;
+                row.workgroups = li.workgroups;
+                row.flops = row.bytes = 0.0;
+                if (ph == 1) launch_work(e.chunks[j], &row.flops, &row.bytes);   // the operator's work is booked on its main kernel
+                std::snprintf(row.kernel, sizeof row.kernel, "%s", li.kernel);
             }
-            for (size_t j = 0; j < e.chunks.size(); ++j) {
-                const int phases = enqueue(e.chunks[j], s, true).phases;
-                for (int ph = 1; ph <= phases; ++ph) {
-                    HIPCHK(c, hipEventRecord(ev[k++], s));
-                    const LaunchInfo li = enqueue(e.chunks[j], s, false, phases == 1 ? 0 : ph);
-                    HIPCHK(c, hipEventRecord(ev[k++], s));
-                    if (r == 0) {
-                        gacer_launch_stat &st = out[row];
-                        st.tenant = to.first; st.op = to.second; st.chunk = (int)j; st.ms = 0.f; st.workgroups = li.workgroups;
-                        st.flops = st.bytes = 0.0;
-                        if (ph == 1) launch_work(e.chunks[j], &st.flops, &st.bytes);   // the operator's work is booked on its main kernel
-                        std::snprintf(st.kernel, sizeof st.kernel, "%s", li.kernel);
-                    }
-                    ++row;
-                }
-            }
-            if (plan && e.record >= 0) HIPCHK(c, hipEventRecord(c->sync_events[e.record], s));
         }
-        if (mode != GACER_MODE_SEQUENTIAL)
-            for (int t = 1; t < NT; ++t)
-                if (c->tenants[t].stream != s0) {
-                    HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
-                    HIPCHK(c, hipStreamWaitEvent(s0, c->join_events[t], 0));
-                }
     }
-    HIPCHK(c, hipStreamSynchronize(s0));
-    HIPCHK(c, hipGetLastError());
-    for (int r = 0; r < rounds; ++r)
-        for (size_t row = 0; row < total; ++row) {
-            float ms = 0.f;
-            const size_t b = 2 * ((size_t)r * total + row);
-            HIPCHK(c, hipEventElapsedTime(&ms, ev[b], ev[b + 1]));
-            out[row].ms += std::max(0.f, ms - empty_ms) / (float)rounds;
-        }
-    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
-    (void)hipEventDestroy(fork);
-    return GACER_OK;
+    use_tenant_workspaces(c);
+    c->trace = &tr;
+    st = run_rounds(c, mode, rounds, false);
+    c->trace = nullptr;
+    if (st == GACER_OK) {
+        for (int r = 0; r < rounds && st == GACER_OK; ++r)
+            for (size_t row = 0; row < total; ++row) {
+                const size_t b = 2 * ((size_t)r * total + row);
+                float ms = 0.f, t0 = 0.f, t1 = 0.f;
+                if (hipEventElapsedTime(&ms, tr.ev[b], tr.ev[b + 1]) != hipSuccess ||
+                    hipEventElapsedTime(&t0, c->t_start[r], tr.ev[b]) != hipSuccess ||
+                    hipEventElapsedTime(&t1, c->t_start[r], tr.ev[b + 1]) != hipSuccess) {
+                    st = fail(c, GACER_EHIP, "hipEventElapsedTime failed on a kernel's event pair: %s", hipGetErrorString(hipGetLastError()));
+                    break;
+                }
+                out[row].ms += ms / (float)rounds;
+                if (r == rounds - 1) { out[row].start_ms = t0; out[row].end_ms = t1; }
+            }
+    }
+    for (hipEvent_t e : tr.ev) (void)hipEventDestroy(e);
+    return st;
 }
 
 }  // extern "C"
@@ -1148,10 +1213,10 @@ gacer_status gacer_profile(gacer_ctx *c, gacer_prof *out, size_t cap, size_t *n_
             else ch.push_back(make_launch(T, v.op, 0, T.batch, 0, cout));
         }
         const LaunchInfo li = enqueue(ch[0], T.stream, true);
-        for (const Launch &l : ch) enqueue(l, T.stream, false);            // warm-up
+        for (const Launch &l : ch) enqueue(l, T.stream, false, 0, T.ws);   // warm-up
         HIPCHK(c, hipEventRecord(e0, T.stream));
         for (int r = 0; r < reps; ++r)
-            for (const Launch &l : ch) enqueue(l, T.stream, false);
+            for (const Launch &l : ch) enqueue(l, T.stream, false, 0, T.ws);
         HIPCHK(c, hipEventRecord(e1, T.stream));
         HIPCHK(c, hipEventSynchronize(e1));
         float ms = 0.f;
@@ -1176,16 +1241,16 @@ gacer_status gacer_profile(gacer_ctx *c, gacer_prof *out, size_t cap, size_t *n_
         float serial = 0.f, pingpong = 0.f;
         HIPCHK(c, hipStreamSynchronize(B.stream));
         HIPCHK(c, hipEventRecord(e0, A.stream));
-        for (int h = 0; h < hops; ++h) { enqueue(la, A.stream, false); enqueue(lb, A.stream, false); }
+        for (int h = 0; h < hops; ++h) { enqueue(la, A.stream, false, 0, A.ws); enqueue(lb, A.stream, false, 0, B.ws); }
         HIPCHK(c, hipEventRecord(e1, A.stream));
         HIPCHK(c, hipEventSynchronize(e1));
         HIPCHK(c, hipEventElapsedTime(&serial, e0, e1));
         HIPCHK(c, hipEventRecord(e0, A.stream));
         for (int h = 0; h < hops; ++h) {
-            enqueue(la, A.stream, false);
+            enqueue(la, A.stream, false, 0, A.ws);
             HIPCHK(c, hipEventRecord(pa, A.stream));
             HIPCHK(c, hipStreamWaitEvent(B.stream, pa, 0));
-            enqueue(lb, B.stream, false);
+            enqueue(lb, B.stream, false, 0, B.ws);
             HIPCHK(c, hipEventRecord(pb, B.stream));
             HIPCHK(c, hipStreamWaitEvent(A.stream, pb, 0));
         }
@@ -1202,6 +1267,130 @@ gacer_status gacer_profile(gacer_ctx *c, gacer_prof *out, size_t cap, size_t *n_
     p.tenant = -1; p.op = -1; p.axis = GACER_AXIS_NONE; p.factor = 1; p.ms = t_sw; p.workgroups = 0; p.cu_share = 1.f;
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
+    return GACER_OK;
+}
+
+
+// Rough cost of one tenant for stream placement: matrix-core time of its convolutions / GEMMs plus a fixed cost per
+// operator launch.  Only the ranking matters.
+static double tenant_weight(const gacer_tenant &t)
+{
+    double macs = 0;
+    for (int i = 0; i < t.n_ops; ++i) {
+        const gacer_op &op = t.ops[i];
+        if (op.out < 0 || op.out >= t.n_tensors) continue;
+        const gacer_tensor &y = t.tensors[op.out];
+        const double outs = (double)y.n * y.c * y.h * y.w;
+        switch (op.kind) {
+        case GACER_CONV2D: case GACER_DWCONV2D: macs += outs * (op.cin / std::max(1, op.groups)) * op.kh * op.kw; break;
+        case GACER_GEMM: case GACER_BGEMM_QK: case GACER_BGEMM_PV: macs += outs * op.cin; break;
+        default: break;
+        }
+    }
+    return 2.0 * macs / (t.dtype == GACER_BF16 ? 4.0e14 : 1.0e14) + 6e-6 * t.n_ops;
+}
+
+gacer_status gacer_place_streams(const gacer_tenant *tenants, int n, void *const *candidates, int n_cand, int *chosen, int *queue_of,
+                                 int *n_queues)
+{
+    if (!tenants || !candidates || !chosen || n < 1 || n > 64 || n_cand < 1 || n_cand > 64) return GACER_EINVAL;
+    std::vector<int> group(n_cand);
+    const gacer_status st = gacer_probe_stream_queues(candidates, n_cand, group.data());
+    if (st != GACER_OK) return st;
+    const int nq = *std::max_element(group.begin(), group.end()) + 1;
+    std::vector<std::vector<int>> by_queue(nq);
+    for (int i = 0; i < n_cand; ++i) by_queue[group[i]].push_back(i);
+    std::vector<size_t> next(nq, 0);
+    std::vector<double> load(nq, 0.0), w(n);
+    for (int t = 0; t < n; ++t) w[t] = tenant_weight(tenants[t]);
+    std::vector<int> order(n);
+    for (int t = 0; t < n; ++t) order[t] = t;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return w[a] > w[b]; });
+    for (int t : order) {                      // longest first, onto the least loaded queue
+        int q = 0;
+        for (int k = 1; k < nq; ++k)
+            if (load[k] < load[q]) q = k;
+        // a queue that has run out of candidate streams shares its first one (those tenants serialise anyway)
+        chosen[t] = next[q] < by_queue[q].size() ? by_queue[q][next[q]++] : by_queue[q][0];
+        if (queue_of) queue_of[t] = q;
+        load[q] += w[t];
+    }
+    if (n_queues) *n_queues = nq;
+    return GACER_OK;
+}
+
+gacer_status gacer_refine(gacer_ctx *c, const gacer_prof *prof, size_t n, int trial_rounds, float min_gain, gacer_plan **out, float *ms_out)
+{
+    if (!c || !prof || !out) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_refine before gacer_load_tenants");
+    if (trial_rounds < 1 || !(min_gain >= 0.f)) return fail(c, GACER_EINVAL, "trial_rounds < 1 or negative min_gain");
+    const int NT = (int)c->tenants.size();
+    std::vector<std::vector<double>> T(NT);
+    for (int t = 0; t < NT; ++t) T[t].assign(c->tenants[t].ops.size(), 0.0);
+    for (size_t k = 0; k < n; ++k)
+        if (prof[k].tenant >= 0 && prof[k].tenant < NT && prof[k].factor == 1 && prof[k].op >= 0 && prof[k].op < (int)T[prof[k].tenant].size())
+            T[prof[k].tenant][prof[k].op] = prof[k].ms;
+    // working copy of the installed plan; chunk lists live in `lists` (an inner vector's storage stays put when the outer one grows)
+    std::vector<gacer_split> best_sp = c->splits;
+    std::vector<std::vector<int>> lists;
+    for (gacer_split &sp : best_sp)
+        if (sp.sizes) { lists.emplace_back(sp.sizes, sp.sizes + sp.factor); sp.sizes = lists.back().data(); }
+    const std::vector<gacer_sync> syncs = c->syncs;
+    std::vector<float> buf((size_t)trial_rounds);
+    gacer_status st = GACER_OK;
+    auto measure = [&](const std::vector<gacer_split> &sp, float *ms) -> gacer_status {
+        gacer_status r = install_plan(c, sp, syncs);
+        if (r != GACER_OK) return r;
+        if ((r = gacer_run(c, GACER_MODE_PLAN, 3, nullptr)) != GACER_OK) return r;
+        if ((r = gacer_run(c, GACER_MODE_PLAN, trial_rounds, buf.data())) != GACER_OK) return r;
+        std::vector<float> v = buf;
+        std::sort(v.begin(), v.end());
+        *ms = v[v.size() / 2];
+        return GACER_OK;
+    };
+    float best = 0.f;
+    if ((st = measure(best_sp, &best)) != GACER_OK) return st;
+    std::vector<int> order(NT);
+    std::vector<double> tot(NT, 0.0);
+    for (int t = 0; t < NT; ++t) { order[t] = t; for (double v : T[t]) tot[t] += v; }
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return tot[a] > tot[b]; });
+    for (int t : order) {
+        const Tenant &Tn = c->tenants[t];
+        std::vector<double> sorted = T[t];
+        std::sort(sorted.begin(), sorted.end());
+        const double thr = sorted.empty() ? 0.0 : sorted[(size_t)(sorted.size() * 0.75)];
+        auto taken = [&](int op) {
+            for (const gacer_split &s : best_sp)
+                if (s.tenant == t && s.op == op) return true;
+            return false;
+        };
+        struct Option { gacer_axis axis; int factor; bool uneven; };
+        const Option options[4] = {{GACER_AXIS_BATCH, 2, false}, {GACER_AXIS_BATCH, 4, false}, {GACER_AXIS_COUT, 2, false}, {GACER_AXIS_BATCH, 2, true}};
+        for (const Option &o : options) {
+            if (o.uneven && Tn.batch < 4) continue;
+            std::vector<gacer_split> trial = best_sp;
+            size_t added = 0;
+            for (int i = 0; i < (int)Tn.ops.size(); ++i) {
+                if (T[t][i] < thr || taken(i) || !axis_legal(Tn.ops[i].kind, o.axis) || o.factor > axis_extent(Tn, i, o.axis)) continue;
+                gacer_split sp = {t, i, o.axis, o.factor, nullptr};
+                if (o.uneven) {                  // a chunk list: three quarters, then one quarter (Section 4.2: a chunk sized to a gap)
+                    lists.push_back({Tn.batch - Tn.batch / 4, Tn.batch / 4});
+                    sp.sizes = lists.back().data();
+                }
+                trial.push_back(sp);
+                ++added;
+            }
+            if (!added) continue;
+            float ms = 0.f;
+            if ((st = measure(trial, &ms)) != GACER_OK) return st;
+            if (ms < best * (1.f - min_gain)) { best = ms; best_sp.swap(trial); break; }
+        }
+    }
+    if ((st = install_plan(c, best_sp, syncs)) != GACER_OK) return st;
+    gacer_plan *pl = make_plan(best_sp, syncs);
+    if (!pl) return fail(c, GACER_ENOMEM, "out of memory building the plan");
+    *out = pl;
+    if (ms_out) *ms_out = best;
     return GACER_OK;
 }
 

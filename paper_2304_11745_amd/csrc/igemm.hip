@@ -727,9 +727,9 @@ static void launch_finish(const GemmArgs &a, hipStream_t s)
     const int64_t total = (int64_t)(a.m_hi - a.m_lo) * Nl;
     const bool v4 = Nl % 4 == 0 && a.n_lo % 4 == 0 && a.y_row % 4 == 0 && (((uintptr_t)a.ws) & 15) == 0 && (((uintptr_t)a.y) & 15) == 0;
     if (v4)
-        hipLaunchKernelGGL((splitk_finish<T, 4>), dim3((unsigned)((total / 4 + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
+        GACER_LAUNCH((splitk_finish<T, 4>), dim3((unsigned)((total / 4 + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
     else
-        hipLaunchKernelGGL((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
+        GACER_LAUNCH((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -763,13 +763,13 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
         return li;
     }
     if (a.b_trans)
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, a);
     else if (!vec_ok)
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, a);
     else if (taps)
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, a);
     else
-        hipLaunchKernelGGL((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
     if (ks > 1 && phase == 0) launch_finish<T>(a, s);
     return li;
 }
@@ -792,7 +792,7 @@ static int rows_lds(int tn, int K, int esz)
 template <int DT, int TN, int G>
 static LaunchInfo go_rows_g(const GemmArgs &a, hipStream_t s, const LaunchInfo &li, int groups)
 {
-    hipLaunchKernelGGL((rowgemm_kernel<DT, TN, G>), dim3((a.m_hi - a.m_lo + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, a);
+    GACER_LAUNCH((rowgemm_kernel<DT, TN, G>), dim3((a.m_hi - a.m_lo + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, a);
     return li;
 }
 

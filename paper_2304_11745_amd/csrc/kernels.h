@@ -62,6 +62,13 @@ struct StreamArgs {
     int64_t rows_per_item;     // row operators: rows (positions) per batch item
 };
 
+// Per-kernel timing (measurement aid): while `launch_timer` points at an event pair on the calling thread, every
+// launcher below hands the pair to the runtime together with its kernel, and the pair then reads the kernel's own
+// begin and end on the device clock (the interval a profiler reports for the dispatch), without changing what is
+// enqueued.  Null (the default) launches plainly.
+struct LaunchTimer { hipEvent_t start, stop; };
+extern thread_local const LaunchTimer *launch_timer;
+
 // phases: 1 = one kernel; 2 = a split-K operator (slice kernel, then the ordered finishing pass)
 struct LaunchInfo { int workgroups; int threads; int lds_bytes; int wg_per_cu; const char *kernel; int phases; };
 

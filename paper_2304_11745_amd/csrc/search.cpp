@@ -251,12 +251,9 @@ gacer_plan *to_plan(Ctx *c, const Splits &sp, const Pointers &P)
     for (int t = 0; t < NT; ++t)
         for (int i = 0; i < (int)sp[t].size(); ++i)
             if (sp[t][i].f > 1) list.push_back({t, i, (gacer_axis)sp[t][i].axis, sp[t][i].f, nullptr});
-    gacer_split *arr = list.empty() ? nullptr : new (std::nothrow) gacer_split[list.size()];
-    if (!list.empty() && !arr) { gacer_plan_free(edges); return nullptr; }
-    std::copy(list.begin(), list.end(), arr);
-    edges->n_split = (int)list.size();
-    edges->split = arr;
-    return edges;
+    gacer_plan *pl = make_plan(list, std::vector<gacer_sync>(edges->sync, edges->sync + edges->n_sync));
+    gacer_plan_free(edges);
+    return pl;
 }
 
 }  // namespace

@@ -12,6 +12,8 @@
 
 namespace gacer {
 
+thread_local const LaunchTimer *launch_timer = nullptr;
+
 static constexpr int TPB = 256;
 
 // ---- depthwise k x k convolution, weights [kh][kw][C] ------------------------------------------
@@ -469,21 +471,21 @@ static LaunchInfo info(int64_t wgs, const char *kernel)
     if (a.dtype == DT_BF16) {                                                                              \
         if (vec_ok<unsigned short, 8>(a)) {                                                                \
             const int64_t g = (outs / 8 + TPB - 1) / TPB;                                                  \
-            if (!dry && g) hipLaunchKernelGGL((KERNEL<unsigned short, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); \
+            if (!dry && g) GACER_LAUNCH((KERNEL<unsigned short, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); \
             return info(g, NAME);                                                                               \
         }                                                                                                  \
         const int64_t g = (outs + TPB - 1) / TPB;                                                          \
-        if (!dry && g) hipLaunchKernelGGL((KERNEL<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);     \
+        if (!dry && g) GACER_LAUNCH((KERNEL<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);     \
         return info(g, NAME);                                                                                   \
     }                                                                                                      \
     if (vec_ok<float, 4>(a)) {                                                                             \
         const int64_t g = (outs / 4 + TPB - 1) / TPB;                                                      \
-        if (!dry && g) hipLaunchKernelGGL((KERNEL<float, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
+        if (!dry && g) GACER_LAUNCH((KERNEL<float, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
         return info(g, NAME);                                                                                   \
     }                                                                                                      \
     {                                                                                                      \
         const int64_t g = (outs + TPB - 1) / TPB;                                                          \
-        if (!dry && g) hipLaunchKernelGGL((KERNEL<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
+        if (!dry && g) GACER_LAUNCH((KERNEL<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
         return info(g, NAME);                                                                                   \
     }
 
@@ -496,8 +498,8 @@ LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
             const int64_t tiles = tiles_for(a.stride == 1 ? DW_TW<4, 1>::value : DW_TW<4, 2>::value);
             const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 4) + TPB - 1) / TPB;
             if (!dry && g) {
-                if (a.stride == 1) hipLaunchKernelGGL((dwconv3_kernel<unsigned short, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-                else hipLaunchKernelGGL((dwconv3_kernel<unsigned short, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                if (a.stride == 1) GACER_LAUNCH((dwconv3_kernel<unsigned short, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                else GACER_LAUNCH((dwconv3_kernel<unsigned short, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
             }
             return info(g, "dwconv3x3");
         }
@@ -505,8 +507,8 @@ LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
             const int64_t tiles = tiles_for(a.stride == 1 ? DW_TW<4, 1>::value : DW_TW<4, 2>::value);
             const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 4) + TPB - 1) / TPB;
             if (!dry && g) {
-                if (a.stride == 1) hipLaunchKernelGGL((dwconv3_kernel<float, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-                else hipLaunchKernelGGL((dwconv3_kernel<float, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                if (a.stride == 1) GACER_LAUNCH((dwconv3_kernel<float, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                else GACER_LAUNCH((dwconv3_kernel<float, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
             }
             return info(g, "dwconv3x3");
         }
@@ -531,8 +533,8 @@ LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t g = (int64_t)(a.n_hi - a.n_lo) * ((a.c_hi - a.c_lo + 63) / 64);
     if (!dry && g) {
-        if (a.dtype == DT_BF16) hipLaunchKernelGGL((gavgpool_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-        else hipLaunchKernelGGL((gavgpool_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        if (a.dtype == DT_BF16) GACER_LAUNCH((gavgpool_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        else GACER_LAUNCH((gavgpool_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
     }
     return info(g, "gavgpool");
 }
@@ -542,10 +544,10 @@ static bool launch_layernorm_vec(const StreamArgs &a, hipStream_t s, int64_t g)
 {
     if (a.C % V || !aligned16(a.x) || !aligned16(a.y) || !aligned16(a.res) || !aligned16(a.scale) || !aligned16(a.shift)) return false;
     const int nv = (a.C / V + 63) / 64;
-    if (nv == 1) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-    else if (nv == 2) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-    else if (nv == 3) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 3>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-    else if (nv == 4) hipLaunchKernelGGL((layernorm_vec_kernel<T, V, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    if (nv == 1) GACER_LAUNCH((layernorm_vec_kernel<T, V, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else if (nv == 2) GACER_LAUNCH((layernorm_vec_kernel<T, V, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else if (nv == 3) GACER_LAUNCH((layernorm_vec_kernel<T, V, 3>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+    else if (nv == 4) GACER_LAUNCH((layernorm_vec_kernel<T, V, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);
     else return false;
     return true;
 }
@@ -557,9 +559,9 @@ LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry)
     if (!dry && g) {
         if (a.dtype == DT_BF16) {
             if (!launch_layernorm_vec<unsigned short, 8>(a, s, g))
-                hipLaunchKernelGGL((layernorm_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                GACER_LAUNCH((layernorm_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
         } else if (!launch_layernorm_vec<float, 4>(a, s, g)) {
-            hipLaunchKernelGGL((layernorm_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+            GACER_LAUNCH((layernorm_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
         }
     }
     return info(g, "layernorm");
@@ -575,13 +577,13 @@ static int64_t launch_softmax_vec(const StreamArgs &a, hipStream_t s, bool dry, 
     const int64_t g = (rows + 4 * (64 / G) - 1) / (4 * (64 / G));
     if (dry || !g) return g;
     switch (G) {
-    case 1: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
-    case 2: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
-    case 4: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
-    case 8: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
-    case 16: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 16>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
-    case 32: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 32>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
-    default: hipLaunchKernelGGL((softmax_vec_kernel<T, V, 64>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 1: GACER_LAUNCH((softmax_vec_kernel<T, V, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 2: GACER_LAUNCH((softmax_vec_kernel<T, V, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 4: GACER_LAUNCH((softmax_vec_kernel<T, V, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 8: GACER_LAUNCH((softmax_vec_kernel<T, V, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 16: GACER_LAUNCH((softmax_vec_kernel<T, V, 16>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    case 32: GACER_LAUNCH((softmax_vec_kernel<T, V, 32>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
+    default: GACER_LAUNCH((softmax_vec_kernel<T, V, 64>), dim3((unsigned)g), dim3(TPB), 0, s, a); break;
     }
     return g;
 }
@@ -595,8 +597,8 @@ LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry)
     }
     const int64_t g = (rows + 3) / 4;
     if (!dry && g) {
-        if (a.dtype == DT_BF16) hipLaunchKernelGGL((softmax_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-        else hipLaunchKernelGGL((softmax_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        if (a.dtype == DT_BF16) GACER_LAUNCH((softmax_kernel<unsigned short>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+        else GACER_LAUNCH((softmax_kernel<float>), dim3((unsigned)g), dim3(TPB), 0, s, a);
     }
     return info(g, "softmax");
 }
@@ -610,7 +612,7 @@ __global__ void spin_kernel(unsigned long long ticks)
 
 void launch_spin(hipStream_t s, unsigned long long ticks)
 {
-    hipLaunchKernelGGL(spin_kernel, dim3(1), dim3(64), 0, s, ticks);
+    GACER_LAUNCH(spin_kernel, dim3(1), dim3(64), 0, s, ticks);
 }
 
 }  // namespace gacer

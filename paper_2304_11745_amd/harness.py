@@ -36,7 +36,7 @@ class Session:
         B.check(self.ctx, B.gacer_create(C.byref(self.ctx)))
         self._keep = []
         self.streams = []
-        placed = self._place_streams(tenants) if (place_streams and not shared_stream and len(tenants) > 1) else None
+        place = place_streams and not shared_stream and len(tenants) > 1
         self.acts = []          # per tenant: list of device tensors (channels-last)
         descs = (B.gacer_tenant * len(tenants))()
         for ti, (t, (x, params)) in enumerate(zip(tenants, data)):
@@ -81,48 +81,33 @@ class Session:
                                     _ptr(dparam(op.w, wkind, op)), _ptr(dparam(op.bias)), _ptr(dparam(op.scale)),
                                     _ptr(dparam(op.shift)), op.cin, op.cout, op.kh, op.kw, op.stride, op.pad,
                                     op.groups, _ACT[op.act], alpha)
-            if shared_stream and self.streams:
-                s = self.streams[0]
-            elif placed is not None:
-                s = placed[ti]
-            else:
-                s = torch.cuda.Stream(device=self.dev)
+            s = self.streams[0] if (shared_stream and self.streams) else torch.cuda.Stream(device=self.dev)
             self.streams.append(s)
             descs[ti] = B.gacer_tenant(len(t.ops), ops, len(acts), tens, t.input, t.output,
                                        B.GACER_BF16 if t.dtype == "bf16" else B.GACER_F32, t.batch,
                                        C.c_void_p(s.cuda_stream))
             self._keep += [tens, ops, dev_params]
         torch.cuda.synchronize(self.dev)
+        if place:
+            self._place_streams(descs, len(tenants))
         self._descs = descs
         B.check(self.ctx, B.gacer_load_tenants(self.ctx, descs, len(tenants)))
 
     # -- stream placement --------------------------------------------------------------------------
-    def _place_streams(self, tenants):
-        """One stream per tenant, chosen so that tenants spread over the device's hardware queues: streams that share a
-        queue serialise (see gacer_probe_stream_queues).  Candidates are probed, then tenants are placed longest first
-        on the least loaded queue, by a rough time estimate (MFMA time plus a per-launch cost)."""
-        from synth import gemm_macs
+    def _place_streams(self, descs, n):
+        """Hands 16 candidate streams to gacer_place_streams and gives every tenant the stream it chose (tenants spread
+        over the device's hardware queues; see gacer_probe_stream_queues)."""
         cands = [torch.cuda.Stream(device=self.dev) for _ in range(16)]
         arr = (C.c_void_p * len(cands))(*[c.cuda_stream for c in cands])
-        grp = (C.c_int * len(cands))()
-        st = B.gacer_probe_stream_queues(arr, len(cands), grp)
+        chosen, queue_of, nq = (C.c_int * n)(), (C.c_int * n)(), C.c_int()
+        st = B.gacer_place_streams(descs, n, arr, len(cands), chosen, queue_of, C.byref(nq))
         if st != B.GACER_OK:
-            raise RuntimeError(f"gacer_probe_stream_queues failed with status {st}")
-        by_queue = {}
-        for c, g in zip(cands, grp):
-            by_queue.setdefault(g, []).append(c)
-        self.queue_groups = len(by_queue)
-        est = [2.0 * gemm_macs(t) / (4.0e14 if t.dtype == "bf16" else 1.0e14) + 6e-6 * len(t.ops) for t in tenants]
-        load = {g: 0.0 for g in by_queue}
-        first = {g: by_queue[g][0] for g in by_queue}
-        placed = [None] * len(tenants)
-        self.tenant_queue = [None] * len(tenants)
-        for ti in sorted(range(len(tenants)), key=lambda i: -est[i]):
-            g = min(load, key=lambda q: (load[q], q))
-            placed[ti] = by_queue[g].pop(0) if by_queue[g] else first[g]
-            self.tenant_queue[ti] = g
-            load[g] += est[ti]
-        return placed
+            raise RuntimeError(f"gacer_place_streams failed with status {st}")
+        self.queue_groups = nq.value
+        self.tenant_queue = list(queue_of)
+        self.streams = [cands[i] for i in chosen]
+        for ti in range(n):
+            descs[ti].stream = C.c_void_p(self.streams[ti].cuda_stream)
 
     # -- plan ------------------------------------------------------------------------------------
     def set_plan(self, splits=(), syncs=()):
@@ -197,13 +182,13 @@ class Session:
         return n.value
 
     def trace(self, mode=B.GACER_MODE_PLAN, rounds=3):
-        """Per-launch statistics of one round (see gacer_trace_run)."""
+        """Per-launch figures of one round (see gacer_trace_run)."""
         n = C.c_size_t()
         B.check(self.ctx, B.gacer_trace_run(self.ctx, mode, rounds, None, 0, C.byref(n)))
         rows = (B.gacer_launch_stat * n.value)()
         B.check(self.ctx, B.gacer_trace_run(self.ctx, mode, rounds, rows, n.value, C.byref(n)))
         return [dict(tenant=r.tenant, op=r.op, chunk=r.chunk, ms=r.ms, flops=r.flops, bytes=r.bytes,
-                     workgroups=r.workgroups, kernel=r.kernel.decode()) for r in rows]
+                     workgroups=r.workgroups, kernel=r.kernel.decode(), start_ms=r.start_ms, end_ms=r.end_ms) for r in rows]
 
     def tensor(self, ti, idx):
         """Tensor ``idx`` of tenant ``ti`` as float32 numpy in logical NCHW order."""
@@ -238,57 +223,31 @@ class Session:
         n_ptr = C.c_int()
         R = C.c_double()
         B.check(self.ctx, B.gacer_search(self.ctx, rows, len(rows), max_rounds, C.byref(out), ptrs, C.byref(n_ptr), C.byref(R)))
-        pl = out.contents
-        inv = {v: k for k, v in AXIS.items()}
-        splits = [(pl.split[i].tenant, pl.split[i].op, inv[pl.split[i].axis], pl.split[i].factor) for i in range(pl.n_split)]
-        syncs = [(pl.sync[i].src_tenant, pl.sync[i].src_op, pl.sync[i].dst_tenant, pl.sync[i].dst_op, pl.sync[i].when)
-                 for i in range(pl.n_sync)]
+        splits, syncs = self._plan_lists(out.contents)
         B.gacer_plan_free(out)
         P = [[ptrs[t * n_ptr.value + j] for j in range(n_ptr.value)] for t in range(len(self.tenants))]
         return splits, syncs, P, R.value
 
-    def refine_plan(self, rows, base_splits=(), base_syncs=(), rounds=12, min_gain=0.005, log=None):
-        """Measured greedy refinement of a plan (the spatial step of Section 4.2 with the GPU as the judge):
-        tenants in order of profiled time; for each, decompose its heaviest operators (top quartile of isolated
-        time) batch x2, batch x4, Cout x2 or batch [3/4, 1/4] and keep the option that lowers the measured makespan by more than
-        ``min_gain``.  Returns (splits, syncs, makespan_ms).  Every candidate is a valid plan, so outputs stay
-        bit-identical; only the schedule changes."""
-        import statistics
-        T = [[0.0] * len(t.ops) for t in self.tenants]
-        for r in rows:
-            if r.tenant >= 0 and r.factor == 1:
-                T[r.tenant][r.op] = r.ms
+    def refine_plan(self, rows, rounds=12, min_gain=0.005):
+        """gacer_refine on the installed plan; returns (splits, syncs, makespan_ms) of the refined, installed plan."""
+        out = C.POINTER(B.gacer_plan)()
+        ms = C.c_float()
+        B.check(self.ctx, B.gacer_refine(self.ctx, rows, len(rows), rounds, min_gain, C.byref(out), C.byref(ms)))
+        splits, syncs = self._plan_lists(out.contents)
+        B.gacer_plan_free(out)
+        return splits, syncs, ms.value
 
-        def measure(splits, syncs):
-            self.set_plan(splits, syncs)
-            self.run(B.GACER_MODE_PLAN, 3)
-            return statistics.median(self.run(B.GACER_MODE_PLAN, rounds))
-        best_sp, best_sy = list(base_splits), list(base_syncs)
-        best = measure(best_sp, best_sy)
-        order = sorted(range(len(self.tenants)), key=lambda i: -sum(T[i]))
-        for ti in order:
-            taken = {(t, o) for (t, o, _, _) in best_sp}
-            thr = sorted(T[ti])[int(len(T[ti]) * 0.75)] if T[ti] else 0.0
-            options = []
-            for axis, f in (("batch", 2), ("batch", 4), ("cout", 2)):
-                sp = [x for x in self.uniform_splits(axis, f, tenants=[ti]) if T[ti][x[1]] >= thr and (x[0], x[1]) not in taken]
-                if sp:
-                    options.append((f"{self.tenants[ti].name}[{ti}] {axis}x{f}", sp))
-            bt = self.tenants[ti].batch
-            if bt >= 4:                          # an uneven chunk list (Section 4.2: a chunk sized to the gap it should fill)
-                sp = [(x[0], x[1], "batch", [bt - bt // 4, bt // 4]) for x in self.uniform_splits("batch", 2, tenants=[ti])
-                      if T[ti][x[1]] >= thr and (x[0], x[1]) not in taken]
-                if sp:
-                    options.append((f"{self.tenants[ti].name}[{ti}] batch [{bt - bt // 4},{bt // 4}]", sp))
-            for name, sp in options:
-                ms = measure(best_sp + sp, best_sy)
-                if log:
-                    log(f"refine: {name}: {ms:.4f} ms (best {best:.4f})")
-                if ms < best * (1.0 - min_gain):
-                    best, best_sp = ms, best_sp + sp
-                    break
-        self.set_plan(best_sp, best_sy)
-        return best_sp, best_sy, best
+    @staticmethod
+    def _plan_lists(pl):
+        inv = {v: k for k, v in AXIS.items()}
+        splits = []
+        for i in range(pl.n_split):
+            sp = pl.split[i]
+            f = [sp.sizes[j] for j in range(sp.factor)] if sp.sizes else sp.factor
+            splits.append((sp.tenant, sp.op, inv[sp.axis], f))
+        syncs = [(pl.sync[i].src_tenant, pl.sync[i].src_op, pl.sync[i].dst_tenant, pl.sync[i].dst_op, pl.sync[i].when)
+                 for i in range(pl.n_sync)]
+        return splits, syncs
 
     def close(self):
         if self.ctx:

@@ -5,9 +5,31 @@ import numpy as np
 import pytest
 
 import synth
-from parity import TOL, rel_err
+from parity import TOL, TOL_ONE_OP, rel_err
 
 pytestmark = pytest.mark.gpu
+
+
+def _check_every_tensor(sess, i, t, x, p):
+    """Tenant i at full size against the oracle: (1) the output, and for fp32 every tensor, of the oracle's own forward
+    pass at the end-to-end tolerance; (2) every operator on its own, the oracle evaluating it on the inputs the GPU
+    operator read, at the one-operator tolerance -- a wrong tile variant cannot hide behind the depth of the network."""
+    from oracle import forward as F
+    ref_all = F.run_tenant(t, x, p, keep_all=True)
+    gpu_all = [sess.tensor(i, k) for k in range(len(t.tensors))]
+    e_out = rel_err(gpu_all[t.output], ref_all[t.output])
+    assert e_out <= TOL[t.dtype], f"{t.name}: output rel err {e_out} > {TOL[t.dtype]}"
+    drift, forced = (0.0, -1), (0.0, -1)
+    for k, op in enumerate(t.ops):
+        e = rel_err(gpu_all[op.out], ref_all[op.out])
+        drift = max(drift, (e, k))
+        if t.dtype == "f32":
+            assert e <= TOL["f32"], f"{t.name} op {k} ({op.kind}): rel err {e}"
+        e1 = rel_err(gpu_all[op.out], F.run_op(t, k, gpu_all, p))
+        forced = max(forced, (e1, k))
+        assert e1 <= TOL_ONE_OP[t.dtype], f"{t.name} op {k} ({op.kind}) on the GPU's own inputs: rel err {e1} > {TOL_ONE_OP[t.dtype]}"
+    print(f"{t.name}({t.batch}) full size: output {e_out:.3e}; worst tensor of the free-running pass {drift[0]:.3e} (op {drift[1]}); "
+          f"worst single operator {forced[0]:.3e} (op {forced[1]})", flush=True)
 
 
 def test_config2_full_size_vs_oracle_and_split_sweep():
@@ -23,10 +45,7 @@ def test_config2_full_size_vs_oracle_and_split_sweep():
     sess.run(B.GACER_MODE_SEQUENTIAL, 1)
     base = [sess.output_bytes(i) for i in range(2)]
     for i, (t, (x, p)) in enumerate(zip(tenants, data)):
-        ref = F.run_tenant(t, x, p)
-        e = rel_err(sess.output(i), ref)
-        print(f"{t.name} full size rel_err={e:.3e}", flush=True)
-        assert e <= TOL["f32"]
+        _check_every_tensor(sess, i, t, x, p)
     for axis in ("batch", "cout"):
         for f in (1, 2, 4):
             sess.set_plan(sess.uniform_splits(axis, f) if f > 1 else [], [])
@@ -73,10 +92,7 @@ def test_bf16_configs_full_size(config):
         key = (t.name, t.batch)
         if key in done and config != 4:
             continue
-        ref = F.run_tenant(t, x, p)
-        e = rel_err(out, ref)
-        print(f"config {config} {t.name}({t.batch}) rel_err={e:.3e}", flush=True)
-        assert e <= TOL["bf16"], f"{t.name}: {e}"
+        _check_every_tensor(sess, i, t, x, p)
         done[key] = True
     n_ops = [len(t.ops) for t in tenants]
     splits = sess.uniform_splits("cout", 2) if config == 4 else sess.uniform_splits("batch", 2, tenants=[1]) + sess.uniform_splits("cout", 4, tenants=[0])
@@ -90,4 +106,12 @@ def test_bf16_configs_full_size(config):
     sess.run(B.GACER_MODE_STREAM_PARALLEL, 1)
     for i in range(len(tenants)):
         assert sess.output_bytes(i) == base[i]
+    if config == 3:            # the plan the configuration asks for: from the CPU search over the profiled table
+        splits, syncs, P, R = sess.search(sess.profile(), 20)
+        sess.set_plan(splits, syncs)
+        sess.poison_outputs()
+        sess.run(B.GACER_MODE_PLAN, 1)
+        for i in range(len(tenants)):
+            assert sess.output_bytes(i) == base[i], f"tenant {i} not bit-identical under the searched plan"
+        print(f"config 3 searched plan: {len(splits)} decomposed operators, pointers {P}, modelled residue {R:.4f}", flush=True)
     sess.close()

@@ -100,10 +100,11 @@ def test_small_families(gpu, config):
     _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
 
 
-def test_small_families_f32_all_kinds(gpu):
-    """Every operator kind in fp32, including the transformer tenant and standalone affine/add/act ops."""
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_small_families_all_kinds(gpu, dtype):
+    """Every operator kind, including the transformer tenant and standalone affine/add/act operators, in both dtypes."""
     from synth import graphs as G
-    b = G._B("eltwise_mix", "f32", 3)
+    b = G._B("eltwise_mix", dtype, 3)
     x = b.tensor(3, 20, 9, 7)
     y = b.conv(x, 24, 3, 1, 1, "none")
     y = b.affine(y, "relu")
@@ -115,7 +116,7 @@ def test_small_families_f32_all_kinds(gpu):
     y = b.gavgpool(y)
     y = b.gemm(y, 13, flatten=True)
     t = b.done(x, y)
-    tenants = [t, G.small_bert("f32", 3), G.small_mbv2("f32", 2)]
+    tenants = [t, G.small_bert(dtype, 3), G.small_mbv2(dtype, 2)]
     data = [G.materialise(tt, 77, i << 20) for i, tt in enumerate(tenants)]
     _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
 

@@ -1,0 +1,172 @@
+"""GPU checks of the regulation machinery itself, through the C ABI: temporal ordering of clusters (Section 4.3, Eq. 6)
+observed on the device clock, the lookup table of Section 4.1 (gacer_profile), and a searched plan (Section 4.4,
+Algorithm 1) installed and run end to end."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+import synth
+from parity import TOL, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2304_11745_amd import harness
+    return harness
+
+
+def _cluster_of(n_ops, P):
+    """cluster index of every operator of a tenant with pointer list P (value p cuts after the p-th operator)."""
+    out, k = [], 0
+    for i in range(n_ops):
+        while k < len(P) and i >= P[k]:
+            k += 1
+        out.append(k)
+    return out
+
+
+def _cluster_windows(rows, clusters):
+    """per cluster: (earliest kernel begin, latest kernel end) over all tenants, from a trace of one round."""
+    win = {}
+    for r in rows:
+        k = clusters[r["tenant"]][r["op"]]
+        lo, hi = win.get(k, (float("inf"), float("-inf")))
+        win[k] = (min(lo, r["start_ms"]), max(hi, r["end_ms"]))
+    return win
+
+
+@pytest.mark.parametrize("config", [3, 4])
+@pytest.mark.parametrize("threads", [False, True], ids=["one-thread", "thread-per-tenant"])
+def test_clusters_run_one_after_another(gpu, config, threads):
+    """Eq. 6: with pointers installed, every kernel of cluster k+1 (of any tenant) begins only after every kernel of
+    cluster k (of every tenant) has ended.  Kernel begin / end are read on the device clock.  The same windows taken
+    without edges overlap, which shows that the measurement would see a missing barrier."""
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(config, "small")
+    sess = gpu.Session(tenants, data)
+    n_ops = [len(t.ops) for t in tenants]
+    P = [[n // 3, (2 * n) // 3] for n in n_ops]
+    P[-1] = [0, n_ops[-1] // 2]                      # one tenant with an empty first segment (the [None] entry of Eq. 6)
+    clusters = [_cluster_of(n, p) for n, p in zip(n_ops, P)]
+    sess.set_issue_threads(threads)
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    base = [sess.output_bytes(i) for i in range(len(tenants))]
+    for splits in ([], sess.uniform_splits("cout", 2)):
+        sess.set_plan(splits, sess.edges_from_pointers(P))
+        sess.poison_outputs()
+        rows = sess.trace(B.GACER_MODE_PLAN, 2)
+        assert all(r["end_ms"] > r["start_ms"] >= 0.0 for r in rows)
+        win = _cluster_windows(rows, clusters)
+        assert sorted(win) == [0, 1, 2]
+        for k in (0, 1):
+            assert win[k + 1][0] >= win[k][1], f"cluster {k + 1} began at {win[k + 1][0]:.4f} ms, cluster {k} ended at {win[k][1]:.4f} ms"
+        # inside a cluster the streams run freely: a tenant's chunks stay in stream order
+        last_end = {}
+        for r in rows:
+            assert r["start_ms"] >= last_end.get(r["tenant"], 0.0) - 1e-6
+            last_end[r["tenant"]] = r["end_ms"]
+        for i in range(len(tenants)):
+            assert sess.output_bytes(i) == base[i]
+    # control: the same cluster windows without edges do overlap
+    sess.clear_plan()
+    rows = sess.trace(B.GACER_MODE_STREAM_PARALLEL, 2)
+    win = _cluster_windows(rows, clusters)
+    assert any(win[k + 1][0] < win[k][1] for k in (0, 1)), "free-running streams never overlapped two clusters"
+    sess.set_issue_threads(False)
+    sess.close()
+
+
+def test_trace_rows_cover_every_kernel_once(gpu):
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(2, "small")
+    sess = gpu.Session(tenants, data)
+    sess.set_plan(sess.uniform_splits("batch", 2), [])
+    for mode in (B.GACER_MODE_PLAN, B.GACER_MODE_SEQUENTIAL, B.GACER_MODE_STREAM_PARALLEL):
+        rows = sess.trace(mode, 3)
+        launches = sess.launch_count(mode)
+        assert len(rows) >= launches                                   # a K-sliced operator contributes two kernels
+        assert len({(r["tenant"], r["op"], r["chunk"]) for r in rows}) == launches
+        assert all(0.0 < r["ms"] < 5.0 and r["workgroups"] > 0 for r in rows)
+        assert all(abs((r["end_ms"] - r["start_ms"]) - r["ms"]) < 0.5 for r in rows)
+        if mode == B.GACER_MODE_SEQUENTIAL:                            # one stream: kernels never overlap
+            ordered = sorted(rows, key=lambda r: r["start_ms"])
+            assert all(b["start_ms"] >= a["end_ms"] - 1e-6 for a, b in zip(ordered, ordered[1:]))
+    sess.close()
+
+
+def _legal_variants(tenants):
+    cout_ok = ("conv", "dwconv", "gemm", "maxpool", "gavgpool", "affine")
+    out = []
+    for ti, t in enumerate(tenants):
+        for oi, op in enumerate(t.ops):
+            out.append((ti, oi, 0, 1))
+            for axis, ext in ((1, t.batch), (2, t.tensors[op.out][1] if op.kind in cout_ok else 0)):
+                for f in (2, 4, 8):
+                    if f <= ext:
+                        out.append((ti, oi, axis, f))
+    return out
+
+
+def test_profile_table(gpu):
+    """Lookup table of Section 4.1: one row per operator and legal (axis, factor), then the T_SW row; W follows from the
+    launch geometry; profiling leaves every tensor as a plain run leaves it."""
+    import torch
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(3, "small")
+    sess = gpu.Session(tenants, data)
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    before = [[a.clone() for a in acts] for acts in sess.acts]
+    rows = sess.profile()
+    got = [(r.tenant, r.op, r.axis, r.factor) for r in rows]
+    assert got[:-1] == _legal_variants(tenants)
+    last = rows[len(rows) - 1]
+    assert (last.tenant, last.op, last.factor) == (-1, -1, 1) and 0.0 <= last.ms < 0.1       # T_SW: below 100 us per pointer
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    for r in list(rows)[:-1]:
+        assert 0.0 < r.ms < 10.0 and r.workgroups >= 1
+        # W = min(1, workgroups / (compute units x resident workgroups per unit)), 1..8 resident workgroups per unit
+        cands = [min(1.0, max(r.workgroups / (cus * w), 1.0 / (cus * 8))) for w in range(1, 9)]
+        assert any(abs(r.cu_share - c) <= 1e-6 for c in cands), (r.workgroups, r.cu_share)
+    torch.cuda.synchronize()
+    for acts0, acts1 in zip(before, sess.acts):
+        for a0, a1 in zip(acts0, acts1):
+            assert torch.equal(a0.view(torch.uint8), a1.view(torch.uint8))
+    sess.close()
+
+
+@pytest.mark.parametrize("config", [2, 3, 4, 5])
+def test_searched_plan_end_to_end(gpu, config):
+    """profile -> gacer_search -> gacer_set_plan -> run: bit-identical to the sequential unsplit run and within tolerance
+    of the oracle; then the measured refinement (gacer_refine) on top, same checks."""
+    from oracle import forward as F
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(config, "small")
+    sess = gpu.Session(tenants, data)
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    base = [sess.output_bytes(i) for i in range(len(tenants))]
+    rows = sess.profile()
+    splits, syncs, P, R = sess.search(rows, 20)
+    assert len(P) == len(tenants) and len({len(p) for p in P}) == 1 and R >= 0.0
+    assert sorted(syncs) == sorted(sess.edges_from_pointers(P)) if P[0] else syncs == []
+
+    def check(tag):
+        sess.poison_outputs()
+        sess.run(B.GACER_MODE_PLAN, 2)
+        for i, (t, (x, p)) in enumerate(zip(tenants, data)):
+            assert sess.output_bytes(i) == base[i], f"{tag}: tenant {i} differs from the unsplit run"
+            e = rel_err(sess.output(i), F.run_tenant(t, x, p))
+            assert e <= TOL[t.dtype], f"{tag}: {t.name} rel err {e}"
+    sess.set_plan(splits, syncs)
+    check("searched")
+    sp2, sy2, ms = sess.refine_plan(rows, rounds=3, min_gain=0.0)
+    assert ms > 0.0 and sorted(sy2) == sorted(syncs) and len(sp2) >= len(splits)
+    check("refined")
+    sess.set_plan(sp2, sy2)                       # the returned plan is itself installable
+    check("refined, reinstalled")
+    sess.close()

@@ -355,3 +355,25 @@ def test_model_residue_and_search_match_the_oracle(ctx):
         # the returned plan is installable
         assert B.gacer_set_plan(ctx, out) == B.GACER_OK
         B.gacer_plan_free(out)
+
+
+def test_capture_refuses_a_ring_of_three_tenants(ctx):
+    """On a HIP runtime older than 7.2, capturing a plan whose edges close a ring of three or more tenants must be refused
+    before anything is enqueued; hub-shaped barriers (mutual pairs with one hub) pass that check (and then fail later here
+    for lack of a GPU, with a different status)."""
+    tenants = [synth.toy_mlp("f32", 4), synth.toy_mlp("f32", 4), synth.toy_mlp("f32", 4)]
+    st, keep = load(ctx, tenants)
+    assert st == B.GACER_OK
+    ring, k1 = _plan([], [(0, 0, 1, 1, 0), (1, 0, 2, 1, 0), (2, 0, 0, 1, 0)])       # 1 waits on 0, 2 on 1, 0 on 2: single waits only
+    assert B.gacer_set_plan(ctx, C.byref(ring)) == B.GACER_OK
+    st = B.gacer_capture(ctx, B.GACER_MODE_PLAN)
+    import torch
+    old_runtime = torch.version.hip is not None and tuple(int(v) for v in torch.version.hip.split(".")[:2]) < (7, 2)
+    if old_runtime:
+        assert st == B.GACER_EPLAN and b"ring" in B.gacer_last_error(ctx)
+    flat = (C.c_int * 3)(1, 1, 1)
+    out = C.POINTER(B.gacer_plan)()
+    assert B.gacer_plan_from_pointers(ctx, flat, 1, C.byref(out)) == B.GACER_OK
+    assert B.gacer_set_plan(ctx, out) == B.GACER_OK
+    B.gacer_plan_free(out)
+    assert B.gacer_capture(ctx, B.GACER_MODE_PLAN) != B.GACER_EPLAN                 # a star around tenant 0 is no ring

@@ -97,6 +97,56 @@ def test_gavgpool_constant_and_hand():
     assert np.array_equal(F.gavgpool(x).ravel(), np.array([1.5, 5.5], np.float32))
 
 
+def test_affine_act_hand_distinct_scale_shift_residual():
+    """y = act(x*scale[c] + shift[c] + res): scale, shift and the residual get different values per channel so that
+    swapping scale and shift, indexing them by position instead of channel, or dropping the residual changes a result."""
+    x = np.array([[[[1.0, -2.0]], [[3.0, 0.5]]]], np.float32)            # (1, 2, 1, 2): channel 0 = [1,-2], channel 1 = [3,0.5]
+    scale = np.array([2.0, -4.0], np.float32)
+    shift = np.array([0.5, 8.0], np.float32)
+    res = np.array([[[[10.0, 1.0]], [[-1.0, 4.0]]]], np.float32)
+    # by hand: c0: 1*2+0.5 = 2.5, -2*2+0.5 = -3.5 ; c1: 3*-4+8 = -4, 0.5*-4+8 = 6
+    assert np.array_equal(F.affine_act(x, scale, shift, None, "none").ravel(), [2.5, -3.5, -4.0, 6.0])
+    # + residual: 12.5, -2.5, -5, 10
+    assert np.array_equal(F.affine_act(x, scale, shift, res, "none").ravel(), [12.5, -2.5, -5.0, 10.0])
+    assert np.array_equal(F.affine_act(x, scale, shift, res, "relu").ravel(), [12.5, 0.0, 0.0, 10.0])
+    assert np.array_equal(F.affine_act(x, scale, shift, res, "relu6").ravel(), [6.0, 0.0, 0.0, 6.0])
+    g = F.affine_act(x, scale, shift, None, "gelu").ravel()               # gelu(2.5), gelu(-3.5), gelu(-4), gelu(6)
+    from math import erf, sqrt
+    for got, v in zip(g, [2.5, -3.5, -4.0, 6.0]):
+        assert abs(got - 0.5 * v * (1.0 + erf(v / sqrt(2.0)))) < 1e-6
+    # the activation is applied after the residual, not before: relu(-3.5) + 1 would be 1, relu(-3.5 + 1) is 0
+    assert F.affine_act(x, scale, shift, res, "relu")[0, 0, 0, 1] == 0.0
+    # sub-ranges write only the named images / channels
+    y = np.full_like(x, 77.0)
+    F.affine_act(x, scale, shift, res, "none", None, (1, 2), y)
+    assert np.array_equal(y.ravel(), [77.0, 77.0, -5.0, 10.0])
+
+
+def test_add_hand():
+    a = np.array([[[[1.0, -5.0]], [[7.0, 2.5]]]], np.float32)
+    b = np.array([[[[0.25, 2.0]], [[-0.5, 4.0]]]], np.float32)
+    assert np.array_equal(F.add(a, b, "none").ravel(), [1.25, -3.0, 6.5, 6.5])
+    assert np.array_equal(F.add(a, b, "relu").ravel(), [1.25, 0.0, 6.5, 6.5])
+    assert np.array_equal(F.add(a, b, "relu6").ravel(), [1.25, 0.0, 6.0, 6.0])
+    two = np.concatenate([a, 2 * a])                                       # batch of 2: only image 1 is written
+    y = np.full_like(two, -9.0)
+    F.add(two, np.concatenate([b, b]), "none", (1, 2), y)
+    assert np.array_equal(y[0].ravel(), [-9.0] * 4) and np.array_equal(y[1].ravel(), [2.25, -8.0, 13.5, 9.0])
+
+
+@pytest.mark.parametrize("act", ["none", "relu", "relu6", "gelu"])
+def test_affine_add_act_vs_torch(act):
+    x, res, x2 = rnd((3, 5, 4, 6), 50, -4, 4), rnd((3, 5, 4, 6), 51, -4, 4), rnd((3, 5, 4, 6), 52, -4, 4)
+    scale, shift = rnd((5,), 53, -2, 2), rnd((5,), 54, -3, 3)
+    actf = {"none": lambda v: v, "relu": torch.relu, "relu6": lambda v: torch.clamp(v, 0, 6), "gelu": tF.gelu}[act]
+    tx, tr, t2 = [torch.from_numpy(v).double() for v in (x, res, x2)]
+    ts, th = torch.from_numpy(scale).double().view(1, 5, 1, 1), torch.from_numpy(shift).double().view(1, 5, 1, 1)
+    assert np.abs(F.affine_act(x, scale, shift, res, act) - actf(tx * ts + th + tr).numpy()).max() < 2e-6
+    assert np.abs(F.affine_act(x, scale, shift, None, act) - actf(tx * ts + th).numpy()).max() < 2e-6
+    assert np.abs(F.add(x, x2, act) - actf(tx + t2).numpy()).max() < 2e-6
+    assert np.abs(F.act(x, act) - actf(tx).numpy()).max() < 2e-6
+
+
 def test_gelu_relu_values():
     x = np.array([[[[-1.0, 0.0, 1.0, 7.0]]]], np.float32)
     assert np.array_equal(F.act(x, "relu").ravel(), [0, 0, 1, 7])
@@ -193,6 +243,12 @@ def _torch_forward(t, x, params):
             else:
                 y = tF.linear(a.permute(0, 2, 3, 1), P[op.w], P[op.bias]).permute(0, 3, 1, 2)
             y = actf[op.act](y + r)
+        elif op.kind == "affine":
+            y = actf[op.act](a * P[op.scale].view(1, -1, 1, 1) + P[op.shift].view(1, -1, 1, 1) + r)
+        elif op.kind == "add":
+            y = actf[op.act](a + T[op.in1])
+        elif op.kind == "act":
+            y = actf[op.act](a)
         elif op.kind == "maxpool":
             y = tF.max_pool2d(a, op.kh, op.stride, op.pad)
         elif op.kind == "gavgpool":
@@ -219,8 +275,25 @@ def _torch_forward(t, x, params):
     return T[t.output].numpy()
 
 
+def eltwise_mix(dtype="f32", batch=3):
+    """A graph with standalone affine (with and without residual), add and act operators."""
+    from synth import graphs as G
+    b = G._B("eltwise_mix", dtype, batch)
+    x = b.tensor(batch, 20, 9, 7)
+    y = b.conv(x, 24, 3, 1, 1, "none")
+    y = b.affine(y, "relu")
+    z = b.conv(y, 24, 1, 1, 0, "none")
+    z = b.affine(z, "none", res=y)
+    y = b.add(z, y, "relu6")
+    y = b.act(y, "gelu")
+    y = b.maxpool(y, 3, 2, 1)
+    y = b.gavgpool(y)
+    y = b.gemm(y, 13, flatten=True)
+    return b.done(x, y)
+
+
 @pytest.mark.parametrize("maker", [synth.toy_cnn, synth.toy_mlp, synth.small_cnn, synth.small_resnet,
-                                   synth.small_mbv2, synth.small_bert])
+                                   synth.small_mbv2, synth.small_bert, eltwise_mix])
 def test_graph_walk_vs_torch_fp64(maker):
     t = maker("f32")
     x, p = synth.materialise(t, 5)
@@ -230,7 +303,7 @@ def test_graph_walk_vs_torch_fp64(maker):
     assert np.abs(y - ref).max() <= 2e-5 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("maker", [synth.small_cnn, synth.small_resnet, synth.small_mbv2, synth.small_bert])
+@pytest.mark.parametrize("maker", [synth.small_cnn, synth.small_resnet, synth.small_mbv2, synth.small_bert, eltwise_mix])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_oracle_split_invariance(maker, dtype):
     """Decomposition (Eq. 5) must not change the oracle's own result, bit for bit."""
@@ -269,3 +342,14 @@ def test_chunk_ranges():
     assert F.chunk_ranges(10, 4) == [(0, 3), (3, 6), (6, 8), (8, 10)]
     assert F.chunk_ranges(8, 2) == [(0, 4), (4, 8)]
     assert sum(b - a for a, b in F.chunk_ranges(1000, 8)) == 1000
+
+
+@pytest.mark.parametrize("maker", [synth.small_resnet, synth.small_bert, synth.small_mbv2, eltwise_mix])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_run_op_reproduces_the_graph_walk(maker, dtype):
+    """run_op on the walk's own tensors returns the walk's tensors, bit for bit."""
+    t = maker(dtype)
+    x, p = synth.materialise(t, 3)
+    T = F.run_tenant(t, x, p, keep_all=True)
+    for i, op in enumerate(t.ops):
+        assert np.array_equal(F.run_op(t, i, T, p), T[op.out])
