@@ -199,6 +199,21 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *ctx, const int *P, int n_ptr, g
 gacer_status gacer_run(gacer_ctx *ctx, int mode, int rounds, float *ms_per_round);
 
 /*
+ * gacer_run for callers that cannot allocate device memory: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same rounds, same kernels, same results as gacer_run(ctx, mode, rounds, NULL),
+ * but the split-K partial tiles go to a fixed 32 MiB workspace inside the library's code object (one copy per GPU, held
+ * until the process ends) instead of the buffers gacer_load_tenants allocated, and the call itself allocates nothing:
+ * no hipMalloc / hipFree, no event or stream creation (it uses the events gacer_load_tenants and gacer_set_plan
+ * created), one issuing thread, no graph replay, no per-round timing.  Every tenant gets a 256-byte aligned part of
+ * the workspace; GACER_ENOMEM when the loaded tenants need more than 32 MiB together (the message states the need),
+ * GACER_ESTATE when the context was created without a GPU.  Nothing in the workspace has to start at zero (every
+ * partial tile is written before it is read), so the contents a previous call left behind do not matter; but all
+ * calls on one GPU share the one workspace, and calls that overlap on a GPU (two contexts, two threads) race.
+ * Returns after all rounds have finished.
+ */
+gacer_status gacer_run_static(gacer_ctx *ctx, int mode, int rounds);
+
+/*
  * Measurement aid: like gacer_run (same issue loop, one thread or one per tenant as set), but every kernel
  * is launched together with a start / stop event pair that the runtime stamps with the kernel's own begin
  * and end on the device clock -- the interval a profiler's kernel trace reports for the dispatch -- so that

@@ -25,7 +25,7 @@ EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_pla
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
            "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats", "gacer_capture",
            "gacer_release_graphs", "gacer_set_issue_threads", "gacer_probe_stream_queues", "gacer_place_streams",
-           "gacer_refine"]
+           "gacer_refine", "gacer_run_static"]
 
 
 class gacer_tensor(C.Structure):
@@ -83,6 +83,7 @@ def _load():
     lib.gacer_set_plan.argtypes = [ctx, C.POINTER(gacer_plan)]
     lib.gacer_plan_from_pointers.argtypes = [ctx, C.POINTER(C.c_int), C.c_int, C.POINTER(C.POINTER(gacer_plan))]
     lib.gacer_run.argtypes = [ctx, C.c_int, C.c_int, C.POINTER(C.c_float)]
+    lib.gacer_run_static.argtypes = [ctx, C.c_int, C.c_int]
     lib.gacer_profile.argtypes = [ctx, C.POINTER(gacer_prof), C.c_size_t, C.POINTER(C.c_size_t)]
     lib.gacer_search.argtypes = [ctx, C.POINTER(gacer_prof), C.c_size_t, C.c_int, C.POINTER(C.POINTER(gacer_plan)),
                                  C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_double)]
@@ -114,6 +115,7 @@ gacer_load_tenants = lib.gacer_load_tenants
 gacer_set_plan = lib.gacer_set_plan
 gacer_plan_from_pointers = lib.gacer_plan_from_pointers
 gacer_run = lib.gacer_run
+gacer_run_static = lib.gacer_run_static
 gacer_profile = lib.gacer_profile
 gacer_search = lib.gacer_search
 gacer_model_residue = lib.gacer_model_residue

@@ -5,6 +5,7 @@
 // "record on the producer stream, wait on the consumer streams".  The host never blocks inside a
 // round, so the GPU does not idle while the CPU synchronises (the overhead analysed around Eq. 8
 // shrinks to the device-side wait).
+#include <hip/hip_runtime.h>
 #include <algorithm>
 #include <atomic>
 #include <chrono>
@@ -27,6 +28,35 @@ using namespace gacer;
         hipError_t e_ = (call);                                                                             \
         if (e_ != hipSuccess) return fail(ctx, GACER_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));  \
     } while (0)
+
+// Workspace of gacer_run_static: device memory that belongs to the loaded code object, so that an entry point which
+// may not allocate still has somewhere to put split-K partial tiles.  Every GPU the library runs on holds its own copy
+// until the process ends.  In host code the array's name is only a stand-in; its device address is taken once per
+// device with hipGetSymbolAddress (gacer_create) and kept here.
+#define GACER_STATIC_SCRATCH_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[GACER_STATIC_SCRATCH_BYTES];
+static constexpr int MAX_DEVICES = 64;
+static unsigned char *g_scratch_ptr[MAX_DEVICES];
+static hipError_t g_scratch_err[MAX_DEVICES];
+static std::mutex g_scratch_mu;
+
+// Device address of `scratch` on the current device `dev` (looked up on first use, with that device current).  The
+// function has external linkage on purpose: the compiler keeps a file-local device array, and gives it a name the
+// runtime can look up, only when it sees host code with external linkage refer to it.
+namespace gacer { hipError_t scratch_address(int dev, unsigned char **out); }
+hipError_t gacer::scratch_address(int dev, unsigned char **out)
+{
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[dev] && g_scratch_err[dev] == hipSuccess) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) { (void)hipGetLastError(); g_scratch_err[dev] = e; }
+        else g_scratch_ptr[dev] = (unsigned char *)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return g_scratch_err[dev];
+}
 
 static gacer_status fail(Ctx *c, gacer_status st, const char *fmt, ...)
 {
@@ -522,6 +552,8 @@ gacer_status gacer_create(gacer_ctx **out)
     if (hipGetDevice(&dev) == hipSuccess) {
         c->device = dev;
         c->has_device = true;
+        unsigned char *unused = nullptr;
+        (void)scratch_address(dev, &unused);     // set-up of gacer_run_static's workspace; a failure is reported by that call
         int cu = 0;
         if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cu > 0) c->n_cu = cu;
     } else {
@@ -589,6 +621,7 @@ gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n
     c->ws_missing = false;
     plan_workspaces(c, fresh);
     c->tenants.swap(fresh);
+    c->ws_run.assign(c->tenants.size(), nullptr);
     c->loaded = true;
     expand_plain(c);
     c->err.clear();
@@ -1006,6 +1039,39 @@ gacer_status gacer_run(gacer_ctx *c, int mode, int rounds, float *ms_per_round)
     if (st != GACER_OK) return st;
     if (ms_per_round)
         for (int r = 0; r < rounds; ++r) HIPCHK(c, hipEventElapsedTime(&ms_per_round[r], c->t_start[r], c->t_end[r]));
+    return GACER_OK;
+}
+
+gacer_status gacer_run_static(gacer_ctx *c, int mode, int rounds)
+{
+    if (!c) return GACER_EINVAL;
+    if (!c->loaded) return fail(c, GACER_ESTATE, "gacer_run_static before gacer_load_tenants");
+    if (mode < 0 || mode > 2 || rounds < 1) return fail(c, GACER_EINVAL, "bad mode or rounds");
+    const int NT = (int)c->tenants.size();
+    // every tenant gets its own 256-byte aligned part of the static workspace (tenants run concurrently)
+    size_t need = 0;
+    for (const Tenant &t : c->tenants) need += (t.ws_floats * sizeof(float) + 255) / 256 * 256;
+    if (need > (size_t)GACER_STATIC_SCRATCH_BYTES)
+        return fail(c, GACER_ENOMEM, "the loaded tenants need %zu bytes of split-K workspace, the static workspace holds %zu; "
+                                     "use gacer_run", need, (size_t)GACER_STATIC_SCRATCH_BYTES);
+    if (!c->has_device) return fail(c, GACER_ESTATE, "the context was created without a GPU");
+    if ((int)c->join_events.size() < NT + 1 || c->sync_events.size() < c->n_sync_events || (int)c->ws_run.size() != NT)
+        return fail(c, GACER_ESTATE, "the plan's events do not exist (they are created by gacer_load_tenants / gacer_set_plan)");
+    unsigned char *base = nullptr;
+    const hipError_t e_sym = scratch_address(c->device, &base);
+    if (e_sym != hipSuccess || !base) return fail(c, GACER_EHIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e_sym));
+    size_t off = 0;
+    for (int t = 0; t < NT; ++t) {
+        c->ws_run[t] = c->tenants[t].ws_floats ? (float *)(base + off) : nullptr;
+        off += (c->tenants[t].ws_floats * sizeof(float) + 255) / 256 * 256;
+    }
+    // one issuing thread, no captured graph (a capture has the allocated workspaces baked in), no timing events
+    gacer_status st = GACER_OK;
+    for (int r = 0; r < rounds && st == GACER_OK; ++r) st = issue_round(c, mode, r);
+    const hipError_t e_sync = hipStreamSynchronize(c->tenants[0].stream);
+    if (st != GACER_OK) return st;
+    if (e_sync != hipSuccess) return fail(c, GACER_EHIP, "hipStreamSynchronize failed: %s", hipGetErrorString(e_sync));
+    HIPCHK(c, hipGetLastError());
     return GACER_OK;
 }
 

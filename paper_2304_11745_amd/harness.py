@@ -159,6 +159,10 @@ class Session:
         B.check(self.ctx, B.gacer_run(self.ctx, mode, rounds, ms))
         return list(ms)
 
+    def run_static(self, mode=B.GACER_MODE_PLAN, rounds=1):
+        """gacer_run_static: the same rounds with the split-K workspace inside the library (no allocation in the call)."""
+        B.check(self.ctx, B.gacer_run_static(self.ctx, mode, rounds))
+
     def capture(self, mode=B.GACER_MODE_PLAN):
         """Capture one round of ``mode`` into a HIP graph; later run(mode) calls replay it."""
         B.check(self.ctx, B.gacer_capture(self.ctx, mode))

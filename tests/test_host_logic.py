@@ -377,3 +377,23 @@ def test_capture_refuses_a_ring_of_three_tenants(ctx):
     assert B.gacer_set_plan(ctx, out) == B.GACER_OK
     B.gacer_plan_free(out)
     assert B.gacer_capture(ctx, B.GACER_MODE_PLAN) != B.GACER_EPLAN                 # a star around tenant 0 is no ring
+
+
+def test_run_static_rejects_more_workspace_than_it_holds(ctx):
+    """The allocation-free entry point has a fixed 32 MiB workspace: tenants that need more are refused with the need in
+    the message, before anything touches the GPU; tenants that fit get past that check (and stop here for lack of a GPU)."""
+    from synth import graphs as G
+
+    def sliced(batch):
+        b = G._B("sliced", "f32", batch)
+        x = b.tensor(batch, 512, 7, 7)
+        return b.done(x, b.conv(x, 512, 3, 1, 1, "relu"))            # 7x7 rows, K = 4608: cut into many slices
+    st, keep = load(ctx, [sliced(8)] * 12)
+    assert st == B.GACER_OK
+    assert B.gacer_run_static(ctx, B.GACER_MODE_STREAM_PARALLEL, 1) == B.GACER_ENOMEM
+    msg = B.gacer_last_error(ctx).decode()
+    assert "static workspace holds 33554432" in msg and "need" in msg
+    st, keep = load(ctx, [sliced(8)])
+    assert st == B.GACER_OK
+    assert B.gacer_run_static(ctx, B.GACER_MODE_STREAM_PARALLEL, 1) in (B.GACER_ESTATE, B.GACER_EHIP)
+    assert B.gacer_run_static(ctx, 7, 1) == B.GACER_EINVAL and B.gacer_run_static(None, 0, 1) == B.GACER_EINVAL
