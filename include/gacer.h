@@ -130,9 +130,12 @@ typedef struct { int n_split; const gacer_split *split; int n_sync; const gacer_
 
 /* One row of the lookup table of Section 4.1: operator (tenant, op) decomposed `factor` ways on
  * `axis` takes `ms` per chunk in isolation, launches `workgroups` workgroups per chunk and
- * occupies `cu_share` (0..1] of the compute units (the analogue of SM occupancy W).  The row
- * with tenant == -1 carries the synchronisation wait T_SW (Eq. 8) in `ms`. */
-typedef struct { int tenant, op; gacer_axis axis; int factor; float ms; int workgroups; float cu_share; } gacer_prof;
+ * occupies `cu_share` (0..1] of the compute units (the analogue of SM occupancy W).  `bw_share`
+ * [0..1] is the chunk's share of the second resource pool, memory bandwidth (Section 4.4, claim (2)):
+ * the bytes it has to move (inputs, parameters and output once) per unit of its time, over the
+ * device's 8 TB/s; 0 in every row switches the second pool off in gacer_search / gacer_model_residue.
+ * The row with tenant == -1 carries the synchronisation wait T_SW (Eq. 8) in `ms`. */
+typedef struct { int tenant, op; gacer_axis axis; int factor; float ms; int workgroups; float cu_share; float bw_share; } gacer_prof;
 
 /* One kernel launch of a round, as measured by gacer_trace_run: average duration, algorithmic
  * work of the launched sub-range (flops = 2*MACs for conv/GEMM/attention launches, 0 otherwise;
@@ -235,15 +238,19 @@ gacer_status gacer_trace_run(gacer_ctx *ctx, int mode, int rounds, gacer_launch_
 gacer_status gacer_profile(gacer_ctx *ctx, gacer_prof *out, size_t cap, size_t *n);
 
 /*
- * Granularity-aware search (Section 4.4, Algorithm 1, alternated with the spatial step of
+ * Granularity-aware search (Section 4.4, Algorithm 1, alternated with the spatial regulation of
  * Section 4.2) on the CPU, over the lookup table `prof`: returns the plan (splits + pointer
- * edges) with the smallest modelled residue R (Eq. 8).  `pointers_out`, if not NULL, receives
- * n_tenants * (*n_ptr_out) pointer values (capacity 8 per tenant).  No GPU work is done.
+ * edges) with the smallest modelled residue R (Eq. 8).  The spatial regulation decomposes an
+ * operator into a chunk sized to the residue it is to fill plus the remainder, so the plan's splits
+ * carry chunk lists (`sizes`, e.g. {5, 3}); costs of chunk sizes between the table's rows are
+ * interpolated linearly in the size.  `pointers_out`, if not NULL, receives n_tenants * (*n_ptr_out)
+ * pointer values (capacity 8 per tenant).  No GPU work is done.
  */
 gacer_status gacer_search(gacer_ctx *ctx, const gacer_prof *prof, size_t n, int max_rounds,
                           gacer_plan **out, int *pointers_out, int *n_ptr_out, double *residue_out);
 
-/* Modelled residue R (Eq. 8) of an explicit (splits, Matrix_P) on the table; CPU only. */
+/* Modelled residue R (Eq. 8) and completion time of an explicit (splits, Matrix_P) on the table; even
+ * decompositions need their row in the table, chunk lists are interpolated.  CPU only. */
 gacer_status gacer_model_residue(gacer_ctx *ctx, const gacer_prof *prof, size_t n, const gacer_split *split,
                                  int n_split, const int *P, int n_ptr, double *residue_out, double *makespan_out);
 

@@ -61,7 +61,7 @@ class gacer_plan(C.Structure):
 
 class gacer_prof(C.Structure):
     _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("axis", C.c_int), ("factor", C.c_int), ("ms", C.c_float),
-                ("workgroups", C.c_int), ("cu_share", C.c_float)]
+                ("workgroups", C.c_int), ("cu_share", C.c_float), ("bw_share", C.c_float)]
 
 
 class gacer_launch_stat(C.Structure):

@@ -1293,6 +1293,9 @@ gacer_status gacer_profile(gacer_ctx *c, gacer_prof *out, size_t cap, size_t *n_
         p.workgroups = li.workgroups;
         const float share = (float)li.workgroups / (float)(c->n_cu * std::max(1, li.wg_per_cu));
         p.cu_share = std::min(1.f, std::max(share, 1.f / (float)(c->n_cu * 8)));
+        double flops = 0, bytes = 0;
+        launch_work(ch[0], &flops, &bytes);                   // chunks of one decomposition differ by at most one element
+        p.bw_share = p.ms > 0.f ? (float)std::min(1.0, bytes / (p.ms * 1e-3) / 8.0e12) : 0.f;
     }
     // T_SW: extra latency of one cross-stream event hop (record on one stream, wait on another),
     // measured as ping-pong between two tenant streams against the same launches on one stream.
@@ -1330,7 +1333,7 @@ gacer_status gacer_profile(gacer_ctx *c, gacer_prof *out, size_t cap, size_t *n_
         if (st != GACER_OK) return st;
     }
     gacer_prof &p = out[k++];
-    p.tenant = -1; p.op = -1; p.axis = GACER_AXIS_NONE; p.factor = 1; p.ms = t_sw; p.workgroups = 0; p.cu_share = 1.f;
+    p.tenant = -1; p.op = -1; p.axis = GACER_AXIS_NONE; p.factor = 1; p.ms = t_sw; p.workgroups = 0; p.cu_share = 1.f; p.bw_share = 0.f;
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     return GACER_OK;

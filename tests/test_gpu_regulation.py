@@ -129,7 +129,7 @@ def test_profile_table(gpu):
     assert (last.tenant, last.op, last.factor) == (-1, -1, 1) and 0.0 <= last.ms < 0.1       # T_SW: below 100 us per pointer
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     for r in list(rows)[:-1]:
-        assert 0.0 < r.ms < 10.0 and r.workgroups >= 1
+        assert 0.0 < r.ms < 10.0 and r.workgroups >= 1 and 0.0 < r.bw_share <= 1.0
         # W = min(1, workgroups / (compute units x resident workgroups per unit)), 1..8 resident workgroups per unit
         cands = [min(1.0, max(r.workgroups / (cus * w), 1.0 / (cus * 8))) for w in range(1, 9)]
         assert any(abs(r.cu_share - c) <= 1e-6 for c in cands), (r.workgroups, r.cu_share)

@@ -296,52 +296,73 @@ def _chain_tenants(n_ops):
     return out
 
 
-def _table_rows(rng, n_ops, wmax=1.0):
+def _table_rows(rng, n_ops, wmax=1.0, second_pool=False):
+    """random lookup table (float32 values, as the C struct holds them); chain tenants: batch 8, 16 output channels"""
     rows, table, splittable = [], {}, {}
     for n, k in enumerate(n_ops):
         for i in range(k):
             T, W = float(np.float32(rng.uniform(0.1, 2.0))), float(np.float32(rng.uniform(0.05, wmax)))
-            rows.append((n, i, 0, 1, T, W))
+            Wb = float(np.float32(rng.uniform(0.05, 0.9))) if second_pool else 0.0
+            rows.append((n, i, 0, 1, T, W, Wb))
             axes = (1, 2) if rng.random() < 0.7 else ((1,) if rng.random() < 0.5 else ())
             if axes:
                 splittable[(n, i)] = axes
             for a in axes:
                 for f in (2, 4, 8):
-                    rows.append((n, i, a, f, float(np.float32(T / f * rng.uniform(1.0, 1.3))), float(np.float32(max(0.02, W / f)))))
-    for (n, i, a, f, T, W) in rows:
-        table[(n, i, a, f)] = S.Entry(T, W)
+                    rows.append((n, i, a, f, float(np.float32(T / f * rng.uniform(1.0, 1.3))), float(np.float32(max(0.02, W / f))),
+                                 float(np.float32(Wb * rng.uniform(0.7, 1.0)))))
+    for (n, i, a, f, T, W, Wb) in rows:
+        table[(n, i, a, f)] = S.Entry(T, W, Wb)
     return rows, table, splittable
+
+
+def _chain_extent(n, i, axis):
+    return 8 if axis == 1 else 16
 
 
 def _prof(rows, t_sw):
     arr = (B.gacer_prof * (len(rows) + 1))()
-    for k, (n, i, a, f, T, W) in enumerate(rows):
-        arr[k] = B.gacer_prof(n, i, a, f, T, 0, W)
-    arr[len(rows)] = B.gacer_prof(-1, -1, 0, 1, t_sw, 0, 1.0)
+    for k, (n, i, a, f, T, W, Wb) in enumerate(rows):
+        arr[k] = B.gacer_prof(n, i, a, f, T, 0, W, Wb)
+    arr[len(rows)] = B.gacer_prof(-1, -1, 0, 1, t_sw, 0, 1.0, 0.0)
     return arr
 
 
-def test_model_residue_and_search_match_the_oracle(ctx):
-    rng = np.random.default_rng(11)
+@pytest.mark.parametrize("second_pool", [False, True], ids=["one-pool", "two-pools"])
+def test_model_residue_and_search_match_the_oracle(ctx, second_pool):
+    rng = np.random.default_rng(12 if second_pool else 11)
     for trial in range(8):
         n_ops = [int(rng.integers(2, 7)) for _ in range(int(rng.integers(2, 4)))]
         st, keep = load(ctx, _chain_tenants(n_ops))
         assert st == B.GACER_OK, B.gacer_last_error(ctx)
-        rows, table, splittable = _table_rows(rng, n_ops)
+        rows, table, splittable = _table_rows(rng, n_ops, second_pool=second_pool)
         t_sw = float(np.float32(0.03))
         prof = _prof(rows, t_sw)
-        # (1) residue model on an explicit plan
+        # (1) residue model on an explicit plan: even decompositions and chunk lists
         npnt = int(rng.integers(0, 3))
         P = [sorted(int(rng.integers(0, k + 1)) for _ in range(npnt)) for k in n_ops]
-        split = {key: (axes[0], 2) for key, axes in splittable.items() if rng.random() < 0.5}
-        sp = (B.gacer_split * max(1, len(split)))(*[B.gacer_split(n, i, a, f) for (n, i), (a, f) in split.items()])
+        split, keep_sizes, sp_rows = {}, [], []
+        for key, axes in splittable.items():
+            r = rng.random()
+            if r < 0.35:
+                split[key] = (axes[0], 2)
+                sp_rows.append(B.gacer_split(key[0], key[1], axes[0], 2, None))
+            elif r < 0.7:
+                E = _chain_extent(key[0], key[1], axes[-1])
+                b = int(rng.integers(1, E))
+                split[key] = (axes[-1], [b, E - b])
+                arr = (C.c_int * 2)(b, E - b)
+                keep_sizes.append(arr)
+                sp_rows.append(B.gacer_split(key[0], key[1], axes[-1], 2, arr))
+        sp = (B.gacer_split * max(1, len(sp_rows)))(*sp_rows)
         flat = (C.c_int * max(1, len(n_ops) * npnt))(*[p for row in P for p in row])
         R, mk = C.c_double(), C.c_double()
-        assert B.gacer_model_residue(ctx, prof, len(prof), sp, len(split), flat, npnt, C.byref(R), C.byref(mk)) == B.GACER_OK
-        iv, _, total = S.simulate(n_ops, table, split, P, t_sw)
-        assert abs(R.value - S.residue(iv, npnt, t_sw)) < 1e-9 and abs(mk.value - total) < 1e-9
+        assert B.gacer_model_residue(ctx, prof, len(prof), sp, len(sp_rows), flat, npnt, C.byref(R), C.byref(mk)) == B.GACER_OK, \
+            B.gacer_last_error(ctx)
+        iv, _, total = S.simulate(n_ops, table, split, P, t_sw, _chain_extent)
+        assert abs(R.value - S.residue(iv, npnt, t_sw, second_pool)) < 1e-9 and abs(mk.value - total) < 1e-9
         # (2) the search itself: same decisions as the step-by-step oracle
-        o_split, o_P, o_R, _ = S.search(n_ops, table, t_sw, splittable, rounds=20, max_pointers=8)
+        o_split, o_P, o_R, _ = S.search(n_ops, table, t_sw, splittable, _chain_extent, rounds=20, max_pointers=8)
         out = C.POINTER(B.gacer_plan)()
         ptrs = (C.c_int * (8 * len(n_ops)))()
         n_ptr, Rs = C.c_int(), C.c_double()
@@ -349,11 +370,13 @@ def test_model_residue_and_search_match_the_oracle(ctx):
         assert abs(Rs.value - o_R) < 1e-9
         got_P = [[ptrs[t * n_ptr.value + j] for j in range(n_ptr.value)] for t in range(len(n_ops))]
         assert got_P == [list(p) for p in o_P]
-        got_split = {(out.contents.split[k].tenant, out.contents.split[k].op): (out.contents.split[k].axis, out.contents.split[k].factor)
-                     for k in range(out.contents.n_split)}
-        assert got_split == {k: v for k, v in o_split.items() if v[1] > 1}
+        got_split = {}
+        for k in range(out.contents.n_split):
+            s_ = out.contents.split[k]
+            got_split[(s_.tenant, s_.op)] = (s_.axis, [s_.sizes[j] for j in range(s_.factor)])
+        assert got_split == {k: (a, list(f)) for k, (a, f) in o_split.items()}
         # the returned plan is installable
-        assert B.gacer_set_plan(ctx, out) == B.GACER_OK
+        assert B.gacer_set_plan(ctx, out) == B.GACER_OK, B.gacer_last_error(ctx)
         B.gacer_plan_free(out)
 
 
