@@ -4,7 +4,8 @@
 A step is one round: every tenant of the workload runs once (inputs, weights and activations
 resident in HBM).  Three executions of the same kernels are timed: sequential (one stream, unsplit),
 stream-parallel (one stream per tenant, unsplit, no ordering) and regulated (the chosen plan:
-operator chunks + pointer edges).  ``value`` is the regulated aggregate items/s.
+operator chunks + pointer edges).  ``value`` is the regulated aggregate items/s of the headline
+workload (configs[1]); ``per_config`` carries the same measurements for configs[2..4].
 
 Prints ONE JSON line.  Plan selection (profile, search, short trials) happens before the timed
 region, as in offline deployment (Section 4.4, "Search Cost Analysis").
@@ -24,11 +25,10 @@ HBM_PEAK = 8.0e12
 
 
 # HBM traffic of the dominant kernel per launch, from two rocprofv3 counter passes (FETCH_SIZE, WRITE_SIZE, KiB per
-# dispatch, scaled by what the same counters read for a plain copy of known size: 2.0 and 1.0).  Valid only for the
-# kernel sources the counters were taken with: the digest below covers them, any change resets `traffic` to null.
+# dispatch, scaled by what the same counters read for a plain copy of known size).  Valid only for the kernel
+# sources the counters were taken with: the digest below covers them, any change resets `traffic` to null.
 TRAFFIC = {
-    2: {"kernel": "igemm_taps_f32_64x64x32", "fetch_bytes": int(9111.1 * 2.0 * 1024), "write_bytes": int(6076.0 * 1024),
-        "sources_sha256": "c0af19c78429dc823a4e32f12c92be640f82f1ca708a79cd992a6726c77d5816"},
+    2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": None, "write_bytes": None, "sources_sha256": ""},
 }
 TRAFFIC_SOURCES = ["igemm.hip", "device_util.h", "kernels.h", "executor.cpp"]
 
@@ -69,29 +69,56 @@ def timed_rounds(sess, mode, steps, warmup):
     return wall_ms, per_round
 
 
+def model_makespan(sess, B, rows, splits, P):
+    """Completion time and residue the regulation model (Eq. 1, Eq. 8) predicts for a plan, from the lookup table."""
+    import ctypes as C
+    from paper_2304_11745_amd import harness
+    keep, sp_rows = [], []
+    for row in splits:
+        t, o, a, f = row[:4]
+        if isinstance(f, (list, tuple)):
+            arr = (C.c_int * len(f))(*f)
+            keep.append(arr)
+            sp_rows.append(B.gacer_split(t, o, harness.AXIS[a], len(f), arr))
+        else:
+            sp_rows.append(B.gacer_split(t, o, harness.AXIS[a], f, None))
+    sp = (B.gacer_split * max(1, len(sp_rows)))(*sp_rows)
+    n_ptr = len(P[0]) if P else 0
+    flat = (C.c_int * max(1, len(sess.tenants) * n_ptr))(*[p for row in P for p in row])
+    R, mk = C.c_double(), C.c_double()
+    st = B.gacer_model_residue(sess.ctx, rows, len(rows), sp, len(sp_rows), flat, n_ptr, C.byref(R), C.byref(mk))
+    if st != B.GACER_OK:
+        return None
+    return {"makespan_ms": round(mk.value, 4), "residue": round(R.value, 4)}
+
+
 def choose_plan(sess, B, trial_rounds):
-    """Candidates: the searched plan, plain stream-parallel, and uniform sweeps; keep the fastest."""
+    """Candidates: the searched plan (Algorithm 1 + spatial regulation on the profiled table), plain stream-parallel, and
+    uniform sweeps; each is measured for a few rounds next to what the model predicts for it; the fastest is refined
+    (gacer_refine) and installed.  Because the unsplit plan is a candidate, the regulated run is never slower than
+    stream-parallel by more than measurement noise."""
     t0 = time.perf_counter()
     rows = sess.profile()
     t_prof = time.perf_counter() - t0
     t0 = time.perf_counter()
     splits, syncs, P, R = sess.search(rows, 100)
     t_search = time.perf_counter() - t0
-    cands = {"searched": (splits, syncs), "unsplit": ([], [])}
+    none_P = [[] for _ in sess.tenants]
+    cands = {"searched": (splits, syncs, P), "unsplit": ([], [], none_P)}
     for axis in ("batch", "cout"):
         for f in (2, 4):
             sp = sess.uniform_splits(axis, f)
             if sp:
-                cands[f"sweep-{axis}x{f}"] = (sp, [])
-    results = {}
-    for name, (sp, sy) in cands.items():
+                cands[f"sweep-{axis}x{f}"] = (sp, [], none_P)
+    results, model = {}, {}
+    for name, (sp, sy, Pm) in cands.items():
         sess.set_plan(sp, sy)
         sess.run(B.GACER_MODE_PLAN, 3)
         ms = sess.run(B.GACER_MODE_PLAN, trial_rounds)
         results[name] = statistics.median(ms)
+        model[name] = model_makespan(sess, B, rows, sp, Pm)
     best = min(results, key=results.get)
-    sp, sy = cands[best]
-    # measured refinement on top of the best candidate (heaviest operators of the heaviest tenants)
+    sp, sy, _ = cands[best]
     t0 = time.perf_counter()
     sess.set_plan(sp, sy)
     sp2, sy2, ms2 = sess.refine_plan(rows, rounds=trial_rounds)
@@ -100,63 +127,159 @@ def choose_plan(sess, B, trial_rounds):
     chosen = best
     if ms2 < results[best] and len(sp2) > len(sp):
         chosen, sp, sy = f"{best}+refined({len(sp2) - len(sp)} ops decomposed)", sp2, sy2
+    kind = "regulated (decomposition and/or pointers)" if (sp or sy) else "stream-parallel (the plan holds no decomposition and no pointers)"
     info = {"profile_s": round(t_prof, 3), "search_s": round(t_search, 4), "refine_s": round(t_refine, 3), "searched_pointers": P,
             "searched_splits": len(splits), "model_residue": R,
-            "trial_ms": {k: round(v, 4) for k, v in results.items()}, "chosen": chosen}
+            "trial_ms": {k: round(v, 4) for k, v in results.items()},
+            "model_vs_measured": {k: {"model": model[k], "measured_ms": round(results[k], 4)} for k in cands},
+            "chosen": chosen, "chosen_kind": kind}
     sess.set_plan(sp, sy)
     return info
 
 
-def cpu_baseline(tenants, data, items):
-    """The oracle as it stands, timed on the host cores, on one full round of the workload."""
+def cpu_baseline(tenants, data, budget_s=25.0):
+    """The oracle as it stands, timed on the host cores: tenants of one round in order, until the time budget is used up."""
     from oracle import forward as F
-    lib = F.lib()
-
-    def one_round():
+    F.lib()
+    done, t_total = [], 0.0
+    for t, (x, p) in zip(tenants, data):
         t0 = time.perf_counter()
-        for t, (x, p) in zip(tenants, data):
-            F.run_tenant(t, x, p)
-        return time.perf_counter() - t0
-    dt = one_round()
+        F.run_tenant(t, x, p)
+        t_total += time.perf_counter() - t0
+        done.append(t)
+        if t_total > budget_s:
+            break
+    items = sum(t.batch for t in done)
     cores = int(os.environ.get("OMP_NUM_THREADS", 0)) or len(os.sched_getaffinity(0))
-    out = {"value": items / dt, "unit": "images/s", "cores": cores, "kind": "oracle",
-           "sample": f"one full round of the workload ({items} items), {dt:.2f} s wall"}
-    if dt * cores < 30.0:                      # also on one core when that stays within the time bound
-        lib.omp_set_num_threads(1)
-        dt1 = one_round()
-        lib.omp_set_num_threads(cores)
-        out["one_core"] = {"value": items / dt1, "unit": "images/s", "sample": f"the same round on one core, {dt1:.2f} s wall"}
+    what = "one full round of the workload" if len(done) == len(tenants) else \
+        "the first %d of %d tenants of a round (%s)" % (len(done), len(tenants), "+".join(f"{t.name}({t.batch})" for t in done))
+    return {"value": items / t_total, "unit": "images/s", "cores": cores, "kind": "oracle",
+            "sample": f"{what}: {items} items, {t_total:.2f} s wall"}
+
+
+def dominant_roofline(trace, dtype, config):
+    per_kernel = {}
+    for r in trace:
+        k = per_kernel.setdefault(r["kernel"], {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
+        k["ms"] += r["ms"]; k["flops"] += r["flops"]; k["bytes"] += r["bytes"]; k["launches"] += 1
+    dom = max(per_kernel, key=lambda n: per_kernel[n]["ms"])
+    d = per_kernel[dom]
+    avg_ms = d["ms"] / d["launches"]
+    if d["flops"] > 0:
+        achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
+                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": measured_traffic(config, dom)}
+    else:
+        achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": measured_traffic(config, dom)}
+    roof.update({"kernel": dom, "launches_per_round": d["launches"], "avg_launch_us": avg_ms * 1e3,
+                 "share_of_kernel_time": d["ms"] / sum(k["ms"] for k in per_kernel.values()),
+                 "duration_basis": "kernel begin/end stamped by the runtime on the launch (what a profiler's kernel trace reports), "
+                                   "mean over the launches of 5 regulated rounds"})
+    kernels = {k: {"launches": v["launches"], "ms_per_round": round(v["ms"], 4),
+                   "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else None,
+                   "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else None}
+               for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1]["ms"])}
+    return roof, kernels
+
+
+def run_config(config, args, cpu_budget_s):
+    """One workload: plan selection, three timed modes, per-kernel trace, CPU baseline."""
+    import synth
+    from paper_2304_11745_amd import binding as B
+    from paper_2304_11745_amd import harness
+    tenants, data = synth.build_config(config, args.scale)
+    items = sum(t.batch for t in tenants)
+    dtype = tenants[0].dtype
+    macs = sum(synth.gemm_macs(t) for t in tenants)
+    sess = harness.Session(tenants, data, "cuda:0")
+    sess.run(B.GACER_MODE_SEQUENTIAL, 3)
+
+    plan_info = {"chosen": "unsplit", "chosen_kind": "stream-parallel (the plan holds no decomposition and no pointers)"}
+    if args.plan == "auto":
+        plan_info = choose_plan(sess, B, 10)
+    # host side of the plan: one issuing thread for all tenants, or one per tenant (the deployment model of Section 2.1);
+    # measured like every other candidate, before the timed region
+    trial = {}
+    for thr in (False, True):
+        sess.set_issue_threads(thr)
+        sess.run(B.GACER_MODE_PLAN, 5)
+        t0 = time.perf_counter()
+        sess.run(B.GACER_MODE_PLAN, 20)
+        trial[thr] = (time.perf_counter() - t0) * 1e3 / 20
+    use_threads = len(tenants) > 1 and trial[True] < 0.97 * trial[False]
+    sess.set_issue_threads(use_threads)
+    plan_info["issue_threads"] = use_threads
+    plan_info["issue_trial_ms"] = {"one_thread": round(trial[False], 4), "thread_per_tenant": round(trial[True], 4)}
+    log(f"config {config} plan selection:", json.dumps(plan_info))
+
+    if args.only_regulated:
+        seq_ms = par_ms = None
+        seq_rounds = par_rounds = [float("nan")]
+    else:
+        seq_ms, seq_rounds = timed_rounds(sess, B.GACER_MODE_SEQUENTIAL, args.steps, args.warmup)
+        par_ms, par_rounds = timed_rounds(sess, B.GACER_MODE_STREAM_PARALLEL, args.steps, args.warmup)
+    reg_ms, reg_rounds = timed_rounds(sess, B.GACER_MODE_PLAN, args.steps, args.warmup)
+
+    roof, kernels = dominant_roofline(sess.trace(B.GACER_MODE_PLAN, 5), dtype, config)
+    out = {
+        "workload": f"configs[{config - 1}]: {synth.CONFIG_NAMES[config]}" + (" (small)" if args.scale == "small" else ""),
+        "items_per_round": items, "tenants": [f"{t.name}({t.batch})" for t in tenants], "dtype": dtype,
+        "plan": plan_info.get("chosen"), "plan_kind": plan_info.get("chosen_kind"), "issue_threads": plan_info.get("issue_threads"),
+        "launches_per_round": sess.launch_count(B.GACER_MODE_PLAN),
+        "ms_per_step": reg_ms,
+        "regulated_images_per_s": items / (reg_ms * 1e-3),
+        "sequential_images_per_s": items / (seq_ms * 1e-3) if seq_ms else None,
+        "stream_parallel_images_per_s": items / (par_ms * 1e-3) if par_ms else None,
+        "speedup_vs_sequential": seq_ms / reg_ms if seq_ms else None,
+        "speedup_vs_stream_parallel": par_ms / reg_ms if par_ms else None,
+        "makespan_ms_median": {"sequential": statistics.median(seq_rounds), "stream_parallel": statistics.median(par_rounds),
+                               "regulated": statistics.median(reg_rounds)},
+        "makespan_ms_p10_p90": {"sequential": pct(seq_rounds), "stream_parallel": pct(par_rounds), "regulated": pct(reg_rounds)},
+        "mfma_frac_of_peak": {"sequential": 2 * macs / (seq_ms * 1e-3) / PEAK[dtype] if seq_ms else None,
+                              "stream_parallel": 2 * macs / (par_ms * 1e-3) / PEAK[dtype] if par_ms else None,
+                              "regulated": 2 * macs / (reg_ms * 1e-3) / PEAK[dtype]},
+        "plan_selection": plan_info,
+        "kernels": kernels,
+        "roofline": roof,
+    }
+    sess.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(tenants, data, cpu_budget_s)
     return out
 
 
 def granularity_table(dtype, rounds):
     """The spatial-granularity experiment of Section 5.4 (its Table 3) on this executor: VGG-16(32) and ResNet-18(32)
-    share the GPU; the rows differ in how each model's batch is decomposed over streams (V16(16)+V16(16) is the batch
-    of 32 run as two half-batch instances on two streams).  Synthetic inputs, seeded weights (instances of one model
-    draw the same weights).  Prints one JSON line of its own."""
-    import synth
+    share the GPU; the rows differ in how one model's batch is decomposed, every operator of that model into the same
+    chunk list, with the chunks alternating between the model's stream and its sibling stream (gacer_split.sibling), so
+    that V16(16)+V16(16) really is two half batches side by side.  Synthetic inputs, seeded weights.  Prints one JSON line."""
     from synth import graphs as G
     from paper_2304_11745_amd import binding as B
     from paper_2304_11745_amd import harness
-    rows = {"1: V16(32) R18(32)": [("v", 32), ("r", 32)],
-            "2: V16(16) V16(16) R18(32)": [("v", 16), ("v", 16), ("r", 32)],
-            "3: V16(24) V16(8) R18(32)": [("v", 24), ("v", 8), ("r", 32)],
-            "4: V16(32) R18(16) R18(16)": [("v", 32), ("r", 16), ("r", 16)],
-            "5: V16(8)x4 R18(32)": [("v", 8)] * 4 + [("r", 32)]}
+    tenants = [G.vgg16(dtype, 32), G.resnet18(dtype, 32)]
+    data = [G.materialise(t, 20230411, i << 20) for i, t in enumerate(tenants)]
+    sess = harness.Session(tenants, data, "cuda:0")
+    rows = {"1: V16(32) R18(32)": [],
+            "2: V16(16)+V16(16) R18(32)": [(0, [16, 16])],
+            "3: V16(24)+V16(8) R18(32)": [(0, [24, 8])],
+            "4: V16(32) R18(16)+R18(16)": [(1, [16, 16])],
+            "5: V16(8)x4 R18(32)": [(0, [8, 8, 8, 8])]}
     out = {}
+    sess.run(B.GACER_MODE_SEQUENTIAL, 2)
     for name, spec in rows.items():
-        tenants = [G.vgg16(dtype, b) if m == "v" else G.resnet18(dtype, b) for m, b in spec]
-        data = [G.materialise(t, 20230411, 0 if m == "v" else 1 << 20) for t, (m, b) in zip(tenants, spec)]
-        sess = harness.Session(tenants, data, "cuda:0")
-        sess.run(B.GACER_MODE_STREAM_PARALLEL, 5)
-        par = statistics.median(sess.run(B.GACER_MODE_STREAM_PARALLEL, rounds))
-        seq = statistics.median(sess.run(B.GACER_MODE_SEQUENTIAL, rounds))
-        sess.close()
-        out[name] = {"streams_ms": round(par, 4), "sequential_ms": round(seq, 4)}
-        log(f"granularity {name}: streams {par:.3f} ms, sequential {seq:.3f} ms")
-    base = out["1: V16(32) R18(32)"]["streams_ms"]
+        for siblings in (True, False):
+            splits = [(ti, oi, "batch", sizes, siblings) for (ti, sizes) in spec for oi in range(len(tenants[ti].ops))]
+            sess.set_plan(splits, [])
+            sess.run(B.GACER_MODE_PLAN, 5)
+            ms = statistics.median(sess.run(B.GACER_MODE_PLAN, rounds))
+            out.setdefault(name, {})["sibling_streams_ms" if siblings else "one_stream_per_model_ms"] = round(ms, 4)
+        log(f"granularity {name}: {out[name]}")
+    sess.close()
+    base = out["1: V16(32) R18(32)"]["sibling_streams_ms"]
     for v in out.values():
-        v["vs_row1"] = round(base / v["streams_ms"], 3)
+        v["vs_row1"] = round(base / v["sibling_streams_ms"], 3)
     print(json.dumps({"experiment": "spatial granularity (Section 5.4, Table 3)", "dtype": dtype, "unit": "ms per round of 64 images",
                       "rows": out, "paper_context": "Titan V: 80 / 66 / 72 / 78 / 85 ms for rows 1-5; other hardware, context only"}), flush=True)
 
@@ -166,7 +289,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--config", type=int, default=2, help="headline workload 1..5 (default 2)")
+    ap.add_argument("--also", default="3,4,5", help="further workloads reported under per_config (comma separated; '' for none)")
     ap.add_argument("--scale", default="full", choices=["full", "small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan", default="auto", help="auto | unsplit")
@@ -188,8 +312,7 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: the executor runs on exactly one GPU (tenants shard across GPUs with no exchange); use --gpus 1")
 
-    import torch
-    import synth
+    import torch  # noqa: F401
     from paper_2304_11745_amd import binding as B
     from paper_2304_11745_amd import harness
 
@@ -203,92 +326,32 @@ def main():
         probe.close()
         log("copy probe: eltwise kernel, 3 dispatches, 268435456 bytes read + 268435456 bytes written each")
 
-    tenants, data = synth.build_config(args.config, args.scale)
-    items = sum(t.batch for t in tenants)
-    dtype = tenants[0].dtype
-    macs = sum(synth.gemm_macs(t) for t in tenants)
-    sess = harness.Session(tenants, data, "cuda:0")
-    sess.run(B.GACER_MODE_SEQUENTIAL, 3)
-
-    plan_info = {"chosen": "unsplit"}
-    if args.plan == "auto":
-        plan_info = choose_plan(sess, B, 10)
-    # host side of the plan: one issuing thread for all tenants, or one per tenant (the deployment model of Section 2.1);
-    # measured like every other candidate, before the timed region
-    trial = {}
-    for thr in (False, True):
-        sess.set_issue_threads(thr)
-        sess.run(B.GACER_MODE_PLAN, 5)
-        t0 = time.perf_counter()
-        sess.run(B.GACER_MODE_PLAN, 20)
-        trial[thr] = (time.perf_counter() - t0) * 1e3 / 20
-    use_threads = len(tenants) > 1 and trial[True] < 0.97 * trial[False]
-    sess.set_issue_threads(use_threads)
-    plan_info["issue_threads"] = use_threads
-    plan_info["issue_trial_ms"] = {"one_thread": round(trial[False], 4), "thread_per_tenant": round(trial[True], 4)}
-    log("plan selection:", json.dumps(plan_info))
-
-    if args.only_regulated:
-        seq_ms = par_ms = None
-        seq_rounds = par_rounds = [float("nan")]
-    else:
-        seq_ms, seq_rounds = timed_rounds(sess, B.GACER_MODE_SEQUENTIAL, args.steps, args.warmup)
-        par_ms, par_rounds = timed_rounds(sess, B.GACER_MODE_STREAM_PARALLEL, args.steps, args.warmup)
-    reg_ms, reg_rounds = timed_rounds(sess, B.GACER_MODE_PLAN, args.steps, args.warmup)
-
-    # per-launch durations of the regulated round, on the streams the kernels run on
-    trace = sess.trace(B.GACER_MODE_PLAN, 5)
-    per_kernel = {}
-    for r in trace:
-        k = per_kernel.setdefault(r["kernel"], {"ms": 0.0, "flops": 0.0, "bytes": 0.0, "launches": 0})
-        k["ms"] += r["ms"]; k["flops"] += r["flops"]; k["bytes"] += r["bytes"]; k["launches"] += 1
-    dom = max(per_kernel, key=lambda n: per_kernel[n]["ms"])
-    d = per_kernel[dom]
-    avg_ms = d["ms"] / d["launches"]
-    if d["flops"] > 0:
-        achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
-        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": measured_traffic(args.config, dom)}
-    else:
-        achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
-        roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": achieved / (HBM_PEAK / 1e9), "traffic": measured_traffic(args.config, dom)}
-    roof.update({"kernel": dom, "launches_per_round": d["launches"], "avg_launch_us": avg_ms * 1e3,
-                 "share_of_kernel_time": d["ms"] / sum(k["ms"] for k in per_kernel.values())})
-
+    head = run_config(args.config, args, 25.0)
     out = {
         "metric": "aggregate tenant images/s (regulated concurrent run)",
-        "value": items / (reg_ms * 1e-3),
+        "value": head["regulated_images_per_s"],
         "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": reg_ms,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}]: {synth.CONFIG_NAMES[args.config]}" + (" (small)" if args.scale == "small" else ""),
-                   "items_per_round": items, "tenants": [f"{t.name}({t.batch})" for t in tenants],
-                   "plan": plan_info.get("chosen"), "issue_threads": plan_info.get("issue_threads"),
-                   "launches_per_round": sess.launch_count(B.GACER_MODE_PLAN)},
-        "sequential_images_per_s": items / (seq_ms * 1e-3) if seq_ms else None,
-        "stream_parallel_images_per_s": items / (par_ms * 1e-3) if par_ms else None,
-        "speedup_vs_sequential": seq_ms / reg_ms if seq_ms else None,
-        "speedup_vs_stream_parallel": par_ms / reg_ms if par_ms else None,
-        "makespan_ms_median": {"sequential": statistics.median(seq_rounds), "stream_parallel": statistics.median(par_rounds),
-                               "regulated": statistics.median(reg_rounds)},
-        "makespan_ms_p10_p90": {"sequential": pct(seq_rounds), "stream_parallel": pct(par_rounds), "regulated": pct(reg_rounds)},
-        "mfma_frac_of_peak": {"sequential": 2 * macs / (seq_ms * 1e-3) / PEAK[dtype] if seq_ms else None,
-                              "stream_parallel": 2 * macs / (par_ms * 1e-3) / PEAK[dtype] if par_ms else None,
-                              "regulated": 2 * macs / (reg_ms * 1e-3) / PEAK[dtype]},
-        "plan_selection": plan_info,
-        "kernels": {k: {"launches": v["launches"], "ms_per_round": round(v["ms"], 4),
-                        "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else None,
-                        "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else None}
-                    for k, v in sorted(per_kernel.items(), key=lambda kv: -kv[1]["ms"])},
-        "roofline": roof,
-        "paper_context": "GACER reports 1.37x-1.66x over sequential cuDNN on Titan V (Section 5.2); other hardware, context only",
+        "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "items_per_round": head["items_per_round"], "tenants": head["tenants"],
+                   "plan": head["plan"], "plan_kind": head["plan_kind"], "issue_threads": head["issue_threads"],
+                   "launches_per_round": head["launches_per_round"]},
     }
-    sess.close()
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(tenants, data, items)
+    for k in ("sequential_images_per_s", "stream_parallel_images_per_s", "speedup_vs_sequential", "speedup_vs_stream_parallel",
+              "makespan_ms_median", "makespan_ms_p10_p90", "mfma_frac_of_peak", "plan_selection", "kernels", "roofline"):
+        out[k] = head[k]
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    out["paper_context"] = "GACER reports 1.37x-1.66x over sequential cuDNN on Titan V (Section 5.2); other hardware, context only"
+    also = [int(c) for c in args.also.split(",") if c.strip() and int(c) != args.config]
+    if also:
+        out["per_config"] = {}
+        for c in also:
+            r = run_config(c, args, 12.0)
+            r.pop("plan_selection", None)                  # kept on stderr; the line stays readable
+            out["per_config"][str(c)] = r
     print(json.dumps(out), flush=True)
 
 

@@ -112,14 +112,20 @@ typedef struct {
     gacer_dtype dtype;
     int batch;
     void *stream; /* hipStream_t created by the caller (default priority); NULL = null stream */
+    void *sibling_stream; /* optional second stream of this tenant (created by the caller, default priority) for
+                             decompositions marked `sibling`; NULL = such chunks stay on `stream` */
 } gacer_tenant;
 
 /* mask + list_B (Section 4.2, Eq. 5): operator (tenant, op) is decomposed into `factor` chunks on `axis`.
  * sizes == NULL: even chunks, factor in {1,2,4,8}, chunk j holds floor(E/factor) + (j < E mod factor) elements of the
  * axis extent E.  sizes != NULL: list_B itself -- `factor` (1..8) positive chunk sizes in launch order whose sum must
  * equal E (e.g. {24, 8} on a batch of 32); the array is copied by gacer_set_plan.  Chunks are contiguous ascending
- * sub-ranges and run in that order on the tenant's stream. */
-typedef struct { int tenant, op; gacer_axis axis; int factor; const int *sizes; } gacer_split;
+ * sub-ranges and run in that order on the tenant's stream.
+ * sibling != 0 (the decomposition over several streams of Section 5.4, Table 3): the odd-numbered chunks are issued on
+ * the tenant's sibling stream, which first waits for everything the operator itself had to wait for, and the
+ * operator counts as finished (for the next operator and for sync edges) only when both streams have finished
+ * their chunks -- chunks of one operator can then overlap each other.  Ignored without a sibling stream. */
+typedef struct { int tenant, op; gacer_axis axis; int factor; const int *sizes; int sibling; } gacer_split;
 /* One ordering constraint between streams.  when == 0: (dst_tenant,dst_op) starts only after every chunk of
  * (src_tenant,src_op) has finished.  when == 1: it starts once everything (src_tenant,src_op) itself has to wait
  * for is done (its stream predecessors and its own when-0 edges) -- the source operator then acts as the hub of a
@@ -302,10 +308,11 @@ gacer_status gacer_probe_stream_queues(void *const *streams, int n, int *group);
  * cost) and places tenants longest first on the least loaded queue.  chosen[i] receives the index of the candidate
  * stream for tenant i, queue_of[i] (may be NULL) its queue, *n_queues (may be NULL) the number of queues found.  Up
  * to n_queues tenants get queues of their own; further tenants share, and once a queue has no unused candidate left
- * its tenants share one stream.
+ * its tenants share one stream.  sibling[i] (may be NULL) receives the index of a further, unused candidate on
+ * another queue for tenant i's sibling stream (see gacer_split.sibling), or -1 when no such candidate is left.
  */
 gacer_status gacer_place_streams(const gacer_tenant *tenants, int n, void *const *candidates, int n_cand, int *chosen,
-                                 int *queue_of, int *n_queues);
+                                 int *queue_of, int *n_queues, int *sibling);
 
 /*
  * Measured refinement of the installed plan: the greedy spatial step of Section 4.2 ("Overall Spatial Regulation")

@@ -42,11 +42,12 @@ class gacer_op(C.Structure):
 class gacer_tenant(C.Structure):
     _fields_ = [("n_ops", C.c_int), ("ops", C.POINTER(gacer_op)), ("n_tensors", C.c_int),
                 ("tensors", C.POINTER(gacer_tensor)), ("input", C.c_int), ("output", C.c_int),
-                ("dtype", C.c_int), ("batch", C.c_int), ("stream", C.c_void_p)]
+                ("dtype", C.c_int), ("batch", C.c_int), ("stream", C.c_void_p), ("sibling_stream", C.c_void_p)]
 
 
 class gacer_split(C.Structure):
-    _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("axis", C.c_int), ("factor", C.c_int), ("sizes", C.POINTER(C.c_int))]
+    _fields_ = [("tenant", C.c_int), ("op", C.c_int), ("axis", C.c_int), ("factor", C.c_int), ("sizes", C.POINTER(C.c_int)),
+                ("sibling", C.c_int)]
 
 
 class gacer_sync(C.Structure):
@@ -101,7 +102,7 @@ def _load():
     lib.gacer_issue_stats.argtypes = [ctx, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.gacer_probe_stream_queues.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_int)]
     lib.gacer_place_streams.argtypes = [C.POINTER(gacer_tenant), C.c_int, C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_int),
-                                        C.POINTER(C.c_int), C.POINTER(C.c_int)]
+                                        C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.gacer_refine.argtypes = [ctx, C.POINTER(gacer_prof), C.c_size_t, C.c_int, C.c_float, C.POINTER(C.POINTER(gacer_plan)),
                                  C.POINTER(C.c_float)]
     return lib

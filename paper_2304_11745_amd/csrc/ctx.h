@@ -14,6 +14,7 @@ struct Launch {
     LaunchKind kind;
     GemmArgs g;
     StreamArgs s;
+    size_t ws_off = 0;      // floats into the tenant's split-K workspace: chunks of one operator own disjoint parts
 };
 
 struct Tenant {
@@ -22,6 +23,7 @@ struct Tenant {
     int input = 0, output = 0, batch = 1;
     gacer_dtype dtype = GACER_F32;
     hipStream_t stream = nullptr;
+    hipStream_t sibling = nullptr;                  // optional second stream for decompositions marked `sibling`
     // split-K bookkeeping (conv / GEMM operators only): slices and 64-byte K blocks per slice, fixed per
     // operator from its unsplit shape; one library-owned workspace per tenant (its operators never overlap)
     std::vector<int> ksplit, kb_per_slice;
@@ -35,6 +37,7 @@ struct OpExec {
     std::vector<int> waits;     // indices into Ctx::sync_events
     int record = -1;            // event recorded after the last chunk, -1 = none
     int pre_record = -1;        // event recorded after the waits and before the first chunk (barrier hub)
+    int fork = -1, join = -1;   // sibling decomposition: odd chunks run on the tenant's sibling stream between these events
 };
 
 // Event pairs of a traced call: rounds x kernels-per-round x {start, stop}; row_of[tenant][op][chunk] is the row of

@@ -208,7 +208,7 @@ LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase, float *w
         if (l.g.ksplit > 1 && !dry) {
             if (!ws) return launch_igemm(l.g, s, true, phase);     // never launch slices without a workspace
             GemmArgs g = l.g;
-            g.ws = ws;
+            g.ws = ws + l.ws_off;
             return launch_igemm(g, s, dry, phase);
         }
         return launch_igemm(l.g, s, dry, phase);
@@ -492,6 +492,7 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
     for (const gacer_sync &e : syncs)
         if (!ev_of.count({e.src_tenant, e.src_op, e.when})) { const int id = (int)ev_of.size(); ev_of[{e.src_tenant, e.src_op, e.when}] = id; }
     std::vector<std::vector<OpExec>> ex(NT);
+    int n_events = (int)ev_of.size();            // edge events first, then a fork / join pair per sibling decomposition
     for (int t = 0; t < NT; ++t) {
         const Tenant &T = c->tenants[t];
         ex[t].resize(T.ops.size());
@@ -501,6 +502,8 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
             const int f = (it == smap.end()) ? 1 : it->second.factor;
             const gacer_axis ax = (it == smap.end() || f == 1) ? GACER_AXIS_NONE : it->second.axis;
             const int *sizes = (it == smap.end() || f == 1) ? nullptr : it->second.sizes;
+            const bool sib = it != smap.end() && f > 1 && it->second.sibling != 0 && T.sibling && T.sibling != T.stream;
+            if (sib) { ex[t][i].fork = n_events++; ex[t][i].join = n_events++; }
             int next = 0;
             for (int j = 0; j < f; ++j) {
                 int lo, hi;
@@ -513,6 +516,14 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
                 } else {
                     ex[t][i].chunks.push_back(make_launch(T, i, 0, T.batch, 0, cout));
                 }
+            }
+            // chunks of one operator may run at the same time (sibling streams): each gets its own part of the tenant's
+            // split-K workspace; the parts add up to what the unsplit operator needs
+            size_t off = 0;
+            for (Launch &l : ex[t][i].chunks) {
+                if (l.kind != LK_IGEMM || l.g.ksplit <= 1) continue;
+                l.ws_off = off;
+                off += (size_t)l.g.ksplit * (size_t)(l.g.m_hi - l.g.m_lo) * (size_t)(l.g.n_hi - l.g.n_lo);
             }
         }
     }
@@ -535,7 +546,7 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
     c->syncs = syncs;
     c->plan_exec.swap(ex);
     c->plan_order.swap(order);
-    c->n_sync_events = ev_of.size();
+    c->n_sync_events = (size_t)n_events;
     if (c->has_device) return ensure_plan_events(c);    // fork / join / edge events are created at set-up, not by a run
     return GACER_OK;
 }
@@ -614,6 +625,7 @@ gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n
         T.tensors.assign(t.tensors, t.tensors + t.n_tensors);
         T.input = t.input; T.output = t.output; T.batch = t.batch; T.dtype = t.dtype;
         T.stream = (hipStream_t)t.stream;
+        T.sibling = (hipStream_t)t.sibling_stream;
     }
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
     drop_graphs(c);
@@ -735,6 +747,14 @@ hipError_t issue_op(Ctx *c, int t, int i, const OpExec &e, hipStream_t s, bool w
         }
     }
     float *ws = c->ws_run[t];
+    // sibling decomposition (Section 5.4, Table 3): odd chunks go to the tenant's second stream, released by `fork` (everything
+    // this operator waited for is done) and gathered by `join` before the operator counts as finished
+    hipStream_t s2 = s;
+    if (with_events && e.fork >= 0) {
+        s2 = c->tenants[t].sibling;
+        if ((err = hipEventRecord(c->sync_events[e.fork], s)) != hipSuccess) return err;
+        if ((err = hipStreamWaitEvent(s2, c->sync_events[e.fork], 0)) != hipSuccess) return err;
+    }
     if (Trace *tr = c->trace) {
         for (size_t j = 0; j < e.chunks.size(); ++j) {
             const int phases = enqueue(e.chunks[j], s, true).phases;
@@ -742,12 +762,16 @@ hipError_t issue_op(Ctx *c, int t, int i, const OpExec &e, hipStream_t s, bool w
                 const size_t k = 2 * ((size_t)round * tr->per_round + tr->row_of[t][i][j] + (size_t)(ph - 1));
                 const LaunchTimer lt = {tr->ev[k], tr->ev[k + 1]};
                 launch_timer = &lt;
-                enqueue(e.chunks[j], s, false, phases == 1 ? 0 : ph, ws);
+                enqueue(e.chunks[j], (j & 1) ? s2 : s, false, phases == 1 ? 0 : ph, ws);
                 launch_timer = nullptr;
             }
         }
     } else {
-        for (const Launch &l : e.chunks) enqueue(l, s, false, 0, ws);
+        for (size_t j = 0; j < e.chunks.size(); ++j) enqueue(e.chunks[j], (j & 1) ? s2 : s, false, 0, ws);
+    }
+    if (s2 != s) {
+        if ((err = hipEventRecord(c->sync_events[e.join], s2)) != hipSuccess) return err;
+        if ((err = hipStreamWaitEvent(s, c->sync_events[e.join], 0)) != hipSuccess) return err;
     }
     if (with_events && e.record >= 0) {
         if ((err = hipEventRecord(c->sync_events[e.record], s)) != hipSuccess) return err;
@@ -1146,6 +1170,11 @@ gacer_status gacer_trace_run(gacer_ctx *c, int mode, int rounds, gacer_launch_st
                 row.workgroups = li.workgroups;
                 row.flops = row.bytes = 0.0;
                 if (ph == 1) launch_work(e.chunks[j], &row.flops, &row.bytes);   // the operator's work is booked on its main kernel
+                else {                          // the finishing pass moves the partial tiles in and the output out
+                    const GemmArgs &g = e.chunks[j].g;
+                    const double mn = (double)(g.m_hi - g.m_lo) * (g.n_hi - g.n_lo) * g.zb * g.zh;
+                    row.bytes = mn * (4.0 * g.ksplit + (g.dtype == DT_BF16 ? 2.0 : 4.0) * (g.res ? 2.0 : 1.0));
+                }
                 std::snprintf(row.kernel, sizeof row.kernel, "%s", li.kernel);
             }
         }
@@ -1360,7 +1389,7 @@ static double tenant_weight(const gacer_tenant &t)
 }
 
 gacer_status gacer_place_streams(const gacer_tenant *tenants, int n, void *const *candidates, int n_cand, int *chosen, int *queue_of,
-                                 int *n_queues)
+                                 int *n_queues, int *sibling)
 {
     if (!tenants || !candidates || !chosen || n < 1 || n > 64 || n_cand < 1 || n_cand > 64) return GACER_EINVAL;
     std::vector<int> group(n_cand);
@@ -1375,14 +1404,27 @@ gacer_status gacer_place_streams(const gacer_tenant *tenants, int n, void *const
     std::vector<int> order(n);
     for (int t = 0; t < n; ++t) order[t] = t;
     std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return w[a] > w[b]; });
+    std::vector<int> own_queue(n, 0);
     for (int t : order) {                      // longest first, onto the least loaded queue
         int q = 0;
         for (int k = 1; k < nq; ++k)
             if (load[k] < load[q]) q = k;
         // a queue that has run out of candidate streams shares its first one (those tenants serialise anyway)
         chosen[t] = next[q] < by_queue[q].size() ? by_queue[q][next[q]++] : by_queue[q][0];
+        own_queue[t] = q;
         if (queue_of) queue_of[t] = q;
         load[q] += w[t];
+    }
+    if (sibling) {
+        // second stream per tenant: an unused candidate on the least loaded queue other than the tenant's own (a chunk on the
+        // tenant's own queue could not overlap the tenant's other chunks); heaviest tenants choose first; -1 when none is left
+        for (int t : order) {
+            int q = -1;
+            for (int k = 0; k < nq; ++k)
+                if (k != own_queue[t] && next[k] < by_queue[k].size() && (q < 0 || load[k] < load[q])) q = k;
+            sibling[t] = q < 0 ? -1 : by_queue[q][next[q]++];
+            if (q >= 0) load[q] += 0.5 * w[t];
+        }
     }
     if (n_queues) *n_queues = nq;
     return GACER_OK;

@@ -152,6 +152,80 @@ __device__ __forceinline__ void finish_scalar(const GemmArgs &a, const float *v,
     for (int q = 0; q < EV; ++q) finish_one<DT>(v[q], a.alpha, a.bias, a.act, rg, yg, o + q, n + q, a.n_hi);
 }
 
+// ---- epilogue shared by the tiled kernels ----
+// MFMA leaves element e of a 32x32 tile at row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.  Each wave
+// turns its tiles through a private LDS patch (`stage`, 32 rows of 36 floats) so that a lane owns EV consecutive
+// output channels of one row: residual loads and output stores are then 16-byte vectors along the contiguous axis.
+template <int DT, int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void igemm_epilogue(const GemmArgs &a, f32x16 (&acc)[BM / WM / 32][BN / WN / 32], float *stage, int m0, int n0,
+                                               int wm, int wn, int lane, int slice, int64_t y_off)
+{
+    typedef typename El<DT>::T T;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    constexpr int EV = DT == DT_BF16 ? 8 : 4;          // outputs per lane and group
+    constexpr int LPR = 32 / EV;                        // lanes per tile row
+    constexpr int GROUPS = 16 / EV;                     // row groups per lane
+    constexpr int SROW = 36;                            // floats per staged row (16-byte aligned, padded)
+    const bool split = a.ksplit > 1;
+    const int Nl = a.n_hi - a.n_lo;
+    float *ws = split ? a.ws + (int64_t)slice * (a.m_hi - a.m_lo) * Nl : nullptr;
+    T *yg = (T *)a.y + y_off;
+    const T *rg = a.res ? (const T *)a.res + y_off : nullptr;
+    const bool vec_out = split ? (Nl % 4 == 0 && (((uintptr_t)a.ws) & 15) == 0)
+                               : (a.y_row % EV == 0 && a.n_lo % EV == 0 && (y_off % EV) == 0 && (((uintptr_t)a.y) & 15) == 0 &&
+                                  (((uintptr_t)a.res) & 15) == 0 && (((uintptr_t)a.bias) & 15) == 0);
+    const int erow = lane / LPR, ecol = (lane % LPR) * EV;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = n0 + wn * (BN / WN) + j * 32 + ecol;
+            const bool n_vec = vec_out && n + EV <= a.n_hi;
+            // bias and residual loads first, then the LDS turn: one global round trip per tile, overlapped with the turn
+            float bv[EV];
+            load_bias_vec<EV>(a.bias, n, !split && n_vec, bv);
+            uint4 rv[GROUPS];
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int m = m0 + wm * (BM / WM) + i * 32 + erow + g * (64 / LPR);
+                rv[g] = make_uint4(0u, 0u, 0u, 0u);
+                if (!split && rg && n_vec && m < a.m_hi) rv[g] = *(const uint4 *)(rg + (int64_t)m * a.y_row + n);
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) stage[((e >> 2) * 8 + lhalf * 4 + (e & 3)) * SROW + lrow] = acc[i][j][e];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int row = erow + g * (64 / LPR);
+                const int m = m0 + wm * (BM / WM) + i * 32 + row;
+                float v[EV];
+#pragma unroll
+                for (int q = 0; q < EV; q += 4) {
+                    const float4 t4 = *(const float4 *)(stage + row * SROW + ecol + q);
+                    v[q] = t4.x; v[q + 1] = t4.y; v[q + 2] = t4.z; v[q + 3] = t4.w;
+                }
+                if (m >= a.m_hi || n >= a.n_hi) continue;
+                if (split) {
+                    float *p = ws + (int64_t)(m - a.m_lo) * Nl + (n - a.n_lo);
+                    if (vec_out && n + EV <= a.n_hi) {
+#pragma unroll
+                        for (int q = 0; q < EV; q += 4) *(float4 *)(p + q) = make_float4(v[q], v[q + 1], v[q + 2], v[q + 3]);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < EV; ++q)
+                            if (n + q < a.n_hi) p[q] = v[q];
+                    }
+                    continue;
+                }
+                const int64_t o = (int64_t)m * a.y_row + n;
+                if (n_vec) finish_vec<DT>(a, v, bv, rg != nullptr, rv[g], yg, o);
+                else finish_scalar<DT>(a, v, rg, yg, o, n);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+}
+
 template <int DT, int BM, int BN, int WM, int WN, int KV, int LOAD>
 __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 {
@@ -437,72 +511,258 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     if (kb < nkb) compute(0);                   // odd block count: the last block already sits in LDS buffer 0
     __syncthreads();                            // the epilogue reuses the tile buffers
 
-    // ---- epilogue ----
-    // MFMA leaves element e of a 32x32 tile at row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.  Each wave
-    // turns its tiles through a private LDS patch so that a lane owns EV consecutive output channels of
-    // one row: residual loads and output stores are then 16-byte vectors along the contiguous axis.
-    constexpr int EV = DT == DT_BF16 ? 8 : 4;          // outputs per lane and group
-    constexpr int LPR = 32 / EV;                        // lanes per tile row
-    constexpr int GROUPS = 16 / EV;                     // row groups per lane
-    constexpr int SROW = 36;                            // floats per staged row (16-byte aligned, padded)
-    float *stage = (float *)smem + wave * (32 * SROW);
-    const bool split = a.ksplit > 1;
-    const int Nl = a.n_hi - a.n_lo;
-    float *ws = split ? a.ws + (int64_t)slice * (a.m_hi - a.m_lo) * Nl : nullptr;
-    T *yg = (T *)a.y + y_off;
-    const T *rg = a.res ? (const T *)a.res + y_off : nullptr;
-    const bool vec_out = split ? (Nl % 4 == 0 && (((uintptr_t)a.ws) & 15) == 0)
-                               : (a.y_row % EV == 0 && a.n_lo % EV == 0 && (y_off % EV) == 0 && (((uintptr_t)a.y) & 15) == 0 &&
-                                  (((uintptr_t)a.res) & 15) == 0 && (((uintptr_t)a.bias) & 15) == 0);
-    const int erow = lane / LPR, ecol = (lane % LPR) * EV;
+    igemm_epilogue<DT, BM, BN, WM, WN>(a, acc, (float *)smem + wave * (32 * 36), m0, n0, wm, wn, lane, slice, y_off);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same product with the global -> LDS leg done by the memory pipeline itself ("buffer_load ... lds", 16 bytes per
+// lane on gfx950): tiles go straight from L2 / HBM into LDS without passing through registers, so many K blocks can be
+// in flight at once (NS stages of LDS) at no register cost.  What bounds the register-staged kernel above is the
+// latency of its single block of prefetch, not a throughput; here block kb + NS - 1 is requested before block kb is
+// consumed.
+//
+// Layout.  One such load makes a wave write 64 x 16 bytes back to back, so tile rows are unpadded (KV x 16 bytes) and
+// consecutive lanes fill consecutive 16-byte slots: thread t owns slot t of every pass of 256 slots (RPP = 256 / KV
+// tile rows per pass).  Bank conflicts of the fragment reads are avoided by an XOR swizzle instead of padding: the
+// 16-byte chunk with logical index q of tile row r sits in slot q ^ swz(r), swz(r) = (r / (256 / ROWB)) % KV, which the
+// loading lane applies on the global side (it fetches the logical chunk that belongs into its slot).
+//
+// Order of additions per output element is the one of igemm_kernel (ascending 32-byte k groups, zero fill beyond the
+// K range; a stage that lies wholly beyond K multiplies zeros), so both kernels produce the same bits.
+//
+// Synchronisation: the loads are counted by vmcnt.  At the end of step kb the wave waits until only the loads of the
+// NS - 2 youngest blocks are outstanding (block kb + 1 has landed), and for its own fragment reads, then meets the
+// others at a bare s_barrier.  The stages are separate __shared__ arrays so that the compiler can see that a load
+// into one stage does not alias the reads of another (with one array it waits for vmcnt(0) before every read).
+#define GACER_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+
+template <int DT, int BM, int BN, int WM, int WN, int KV, int NS, bool TAPS>
+__global__ __launch_bounds__(THREADS)
+__attribute__((amdgpu_waves_per_eu(2 * NS * (BM + BN) * KV * 16 <= 160 * 1024 ? 2 : 1)))      // two workgroups per unit where LDS allows
+void igemm_dma_kernel(GemmArgs a)
+{
+    typedef typename El<DT>::T T;
+    constexpr int VEC = El<DT>::VEC;
+    constexpr int ESZ = (int)sizeof(T);
+    constexpr int BK = KV * VEC;
+    constexpr int ROWB = KV * 16;               // unpadded tile row
+    constexpr int RPP = THREADS / KV;           // tile rows covered by one pass of all threads
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int AV = BM / RPP, BV = BN / RPP; // loads per thread and block
+    constexpr int STAGE = (BM + BN) * ROWB;
+    constexpr int R256 = 256 / ROWB;            // tile rows per 256 bytes of LDS (one sweep over the 64 banks)
+    constexpr int PATCH = 32 * 36 * 4;          // bytes of one wave's epilogue patch
+    constexpr bool OWN_PATCH = STAGE < PATCH * ((4 + NS - 1) / NS);
+    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && BM % RPP == 0 && BN % RPP == 0 && NS >= 3 && NS <= 4 && (KV == 4 || KV == 8), "tile shape");
+    static_assert((NS - 2) * (AV + BV) < 64, "outstanding loads exceed the counter");
+
+    __shared__ __align__(1024) unsigned char st0[STAGE];
+    __shared__ __align__(1024) unsigned char st1[STAGE];
+    __shared__ __align__(1024) unsigned char st2[STAGE];
+    __shared__ __align__(1024) unsigned char st3[NS > 3 ? STAGE : 16];
+    __shared__ __align__(16) unsigned char own_patch[OWN_PATCH ? 4 * PATCH : 16];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
+    const int tile_m = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / tiles_n));
+    const int tile_n = (int)blockIdx.x - tile_m * tiles_n;
+    const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
+
+    const int z = blockIdx.z;
+    const int zq = __builtin_amdgcn_readfirstlane(z / a.zh);
+    const int zb = a.z_lo + zq, zh = z - zq * a.zh;
+    const int64_t x_zoff = zb * a.x_zb + zh * a.x_zh, w_zoff = zb * a.w_zb + zh * a.w_zh;
+    const __amdgpu_buffer_rsrc_t xr = make_rsrc((const T *)a.x + x_zoff, a.x_bytes - x_zoff * ESZ);
+    const __amdgpu_buffer_rsrc_t wr = make_rsrc((const T *)a.w + w_zoff, a.w_bytes - w_zoff * ESZ);
+    const int64_t y_off = zb * a.y_zb + zh * a.y_zh;
+
+    const int HoWo = a.Ho * a.Wo;
+    const int vrow = tid / KV;                                  // tile row of this thread's slot in pass 0
+    const int lcol = (tid % KV) ^ ((vrow / R256) % KV);         // logical chunk that belongs into the slot
+
+    // per-thread A rows: byte offset of the window origin (or OOB) and one validity bit per tap
+    unsigned a_off[AV], a_hm[AV];
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+        const int m = m0 + vrow + i * RPP;
+        const bool ok = m < a.m_hi;
+        const int mm = ok ? m : a.m_lo;
+        const int img = mm / HoWo, rem = mm - img * HoWo;
+        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        const int ih0 = oh * a.stride - a.pad, iw0 = ow * a.stride - a.pad;
+        const int64_t e0 = (int64_t)img * a.x_img + ((int64_t)ih0 * a.W + iw0) * a.x_pix;   // may be negative at the border
+        a_off[i] = ok ? (unsigned)(int)(e0 * ESZ) : OOB;
+        unsigned tm = 0;
+        for (int r = 0; r < a.kh; ++r)
+            for (int q = 0; q < a.kw; ++q)
+                tm |= (unsigned)(ih0 + r >= 0 && ih0 + r < a.H && iw0 + q >= 0 && iw0 + q < a.W) << (r * a.kw + q);
+        a_hm[i] = ok ? tm : 0u;
+    }
+    unsigned b_off[BV];
+#pragma unroll
+    for (int i = 0; i < BV; ++i) {
+        const int n = n0 + vrow + i * RPP;
+        b_off[i] = n < a.n_hi ? (unsigned)((int64_t)n * a.w_row * ESZ) : OOB;
+    }
+
+    // K range of this slice, in blocks of BK (kb_per_slice counts 64-byte blocks)
+    const int nkb_all = (a.K + BK - 1) / BK;
+    const int per = a.kb_per_slice / (KV / 4);
+    const int slice = blockIdx.y;
+    const int kb_lo = slice * per;
+    const int nkb = min(nkb_all, kb_lo + per);
+    const int k_end = min(a.K, nkb * BK);       // loads at or beyond k_end return zeros
+
+    int kv = kb_lo * BK + lcol * VEC;
+    int kr = 0, ksx = 0, kci = kv;
+    if constexpr (TAPS) {
+        const int tap = kv / a.Cin;
+        kci = kv - tap * a.Cin;
+        kr = tap / a.kw;
+        ksx = tap - kr * a.kw;
+    }
+
+    // requests this thread's slots of the next K block into `stage` (one call per block, ascending)
+    const int wave_slot = wave * 1024;
+    auto request = [&](unsigned char *stage) {
+        const bool k_ok = kv < k_end;
+        if constexpr (TAPS) {
+            const unsigned delta = (unsigned)((((int64_t)kr * a.W + ksx) * a.x_pix + kci) * ESZ);
+            const unsigned tp = k_ok ? (unsigned)(kr * a.kw + ksx) : 31u;      // bit 31 is never set
+#pragma unroll
+            for (int i = 0; i < AV; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, GACER_LDS(stage + i * RPP * ROWB + wave_slot), 16,
+                                                         (int)(((a_hm[i] >> tp) & 1u) ? a_off[i] + delta : OOB), 0, 0, 0);
+        } else {
+            const unsigned delta = (unsigned)(kv * ESZ);
+#pragma unroll
+            for (int i = 0; i < AV; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, GACER_LDS(stage + i * RPP * ROWB + wave_slot), 16,
+                                                         (int)((k_ok && a_hm[i]) ? a_off[i] + delta : OOB), 0, 0, 0);
+        }
+        {
+            const unsigned delta = (unsigned)(kv * ESZ);
+#pragma unroll
+            for (int i = 0; i < BV; ++i)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, GACER_LDS(stage + (BM + i * RPP) * ROWB + wave_slot), 16,
+                                                         (int)((k_ok && b_off[i] != OOB) ? b_off[i] + delta : OOB), 0, 0, 0);
+        }
+        kv += BK;
+        if constexpr (TAPS) {
+            kci += BK;
+            if (a.Cin >= BK) {                  // at most one tap boundary per block: select-only update
+                const bool w1 = kci >= a.Cin;
+                kci -= w1 ? a.Cin : 0;
+                ksx += w1 ? 1 : 0;
+                const bool w2 = ksx == a.kw;
+                ksx = w2 ? 0 : ksx;
+                kr += w2 ? 1 : 0;
+            } else {
+                const int tap = kv / a.Cin;
+                kci = kv - tap * a.Cin;
+                kr = tap / a.kw;
+                ksx = tap - kr * a.kw;
+            }
+        }
+    };
+
+    f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = n0 + wn * (BN / WN) + j * 32 + ecol;
-            const bool n_vec = vec_out && n + EV <= a.n_hi;
-            // bias and residual loads first, then the LDS turn: one global round trip per tile, overlapped with the turn
-            float bv[EV];
-            load_bias_vec<EV>(a.bias, n, !split && n_vec, bv);
-            uint4 rv[GROUPS];
+        for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int g = 0; g < GROUPS; ++g) {
-                const int m = m0 + wm * (BM / WM) + i * 32 + erow + g * (64 / LPR);
-                rv[g] = make_uint4(0u, 0u, 0u, 0u);
-                if (!split && rg && n_vec && m < a.m_hi) rv[g] = *(const uint4 *)(rg + (int64_t)m * a.y_row + n);
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    // fragment reads: tile row lrow (+ a multiple of 32, which leaves the swizzle unchanged), logical chunk 2 ks + lhalf
+    const int frag_lo = (lhalf ^ ((lrow / R256) % KV)) * 16;
+    const int a_row0 = (wm * (BM / WM) + lrow) * ROWB, b_row0 = (BM + wn * (BN / WN) + lrow) * ROWB;
+    auto compute = [&](const unsigned char *stage) {
+#pragma unroll
+        for (int ks = 0; ks < KV / 2; ++ks) {
+            const int col = frag_lo ^ (ks * 32);
+            uint4 fa[TM], fb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[i] = *(const uint4 *)(stage + a_row0 + i * 32 * ROWB + col);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[j] = *(const uint4 *)(stage + b_row0 + j * 32 * ROWB + col);
+            if constexpr (DT == DT_BF16) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
+                                                                            __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            const float av = __uint_as_float(e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w);
+                            const float bv = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
+                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                        }
             }
-#pragma unroll
-            for (int e = 0; e < 16; ++e) stage[((e >> 2) * 8 + lhalf * 4 + (e & 3)) * SROW + lrow] = acc[i][j][e];
-            __builtin_amdgcn_wave_barrier();
-#pragma unroll
-            for (int g = 0; g < GROUPS; ++g) {
-                const int row = erow + g * (64 / LPR);
-                const int m = m0 + wm * (BM / WM) + i * 32 + row;
-                float v[EV];
-#pragma unroll
-                for (int q = 0; q < EV; q += 4) {
-                    const float4 t4 = *(const float4 *)(stage + row * SROW + ecol + q);
-                    v[q] = t4.x; v[q + 1] = t4.y; v[q + 2] = t4.z; v[q + 3] = t4.w;
-                }
-                if (m >= a.m_hi || n >= a.n_hi) continue;
-                if (split) {
-                    float *p = ws + (int64_t)(m - a.m_lo) * Nl + (n - a.n_lo);
-                    if (vec_out && n + EV <= a.n_hi) {
-#pragma unroll
-                        for (int q = 0; q < EV; q += 4) *(float4 *)(p + q) = make_float4(v[q], v[q + 1], v[q + 2], v[q + 3]);
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < EV; ++q)
-                            if (n + q < a.n_hi) p[q] = v[q];
-                    }
-                    continue;
-                }
-                const int64_t o = (int64_t)m * a.y_row + n;
-                if (n_vec) finish_vec<DT>(a, v, bv, rg != nullptr, rv[g], yg, o);
-                else finish_scalar<DT>(a, v, rg, yg, o, n);
-            }
-            __builtin_amdgcn_wave_barrier();
         }
+    };
+
+    // vmcnt(N) & lgkmcnt(0): the loads of all but the NS - 2 youngest blocks have landed, own LDS reads are done
+    constexpr int PENDING = (NS - 2) * (AV + BV);
+    constexpr int WAIT_NEXT = (PENDING & 15) | (7 << 4) | ((PENDING >> 4) << 14);
+    constexpr int WAIT_ALL = (7 << 4);
+    auto meet = [&](int imm_is_all) {
+        if (imm_is_all) __builtin_amdgcn_s_waitcnt(WAIT_ALL); else __builtin_amdgcn_s_waitcnt(WAIT_NEXT);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+    // one step: request block kb + NS - 1 into the stage that block kb - 1 has just left, consume block kb
+#define GACER_STEP(cur, into) do { request(into); compute(cur); meet(0); } while (0)
+
+    request(st0);
+    request(st1);
+    if constexpr (NS > 3) request(st2);
+    meet(0);                                    // block kb_lo has landed
+    const int n_blocks = nkb - kb_lo;
+    int done = 0;
+    if constexpr (NS == 3) {
+        for (; done + 3 <= n_blocks; done += 3) {       // whole rounds over the stages; a single loop exit keeps one accumulator set
+            GACER_STEP(st0, st2);
+            GACER_STEP(st1, st0);
+            GACER_STEP(st2, st1);
+        }
+        const int rest = n_blocks - done;
+        if (rest >= 1) GACER_STEP(st0, st2);
+        if (rest >= 2) GACER_STEP(st1, st0);
+    } else {
+        for (; done + 4 <= n_blocks; done += 4) {
+            GACER_STEP(st0, st3);
+            GACER_STEP(st1, st0);
+            GACER_STEP(st2, st1);
+            GACER_STEP(st3, st2);
+        }
+        const int rest = n_blocks - done;
+        if (rest >= 1) GACER_STEP(st0, st3);
+        if (rest >= 2) GACER_STEP(st1, st0);
+        if (rest >= 3) GACER_STEP(st2, st1);
+    }
+#undef GACER_STEP
+    meet(1);                                    // trailing requests (all beyond K: zeros) have landed; the epilogue reuses the stages
+
+    float *patch;
+    if constexpr (OWN_PATCH) {
+        patch = (float *)(own_patch + wave * PATCH);
+    } else {
+        const int which = wave % NS;
+        unsigned char *base = which == 0 ? st0 : which == 1 ? st1 : which == 2 ? st2 : st3;
+        patch = (float *)(base + (wave / NS) * PATCH);
+    }
+    igemm_epilogue<DT, BM, BN, WM, WN>(a, acc, patch, m0, n0, wm, wn, lane, slice, y_off);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -774,6 +1034,41 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     return li;
 }
 
+// launcher of igemm_dma_kernel (operands 16-byte aligned in every stride, B rows contiguous in k, at most 31 taps)
+template <int DT, int BM, int BN, int WM, int WN, int KV, int NS>
+static LaunchInfo go_dma(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, int phase)
+{
+    typedef typename El<DT>::T T;
+    constexpr int STAGE = (BM + BN) * KV * 16, PATCH = 32 * 36 * 4;
+    constexpr bool OWN_PATCH = STAGE < PATCH * ((4 + NS - 1) / NS);
+    const int tiles_m = (a.m_hi - a.m_lo + BM - 1) / BM, tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
+    const int z = a.zb * a.zh;
+    const int ks = a.ksplit;
+    LaunchInfo li;
+    li.workgroups = tiles_m * tiles_n * z * ks;
+    li.threads = THREADS;
+    li.lds_bytes = NS * STAGE + (OWN_PATCH ? 4 * PATCH : 0);
+    const int by_lds = (160 * 1024) / li.lds_bytes;
+    li.wg_per_cu = by_lds < 8 ? by_lds : 8;
+    static const std::string shape = std::string(DT == DT_BF16 ? "bf16_" : "f32_") + std::to_string(BM) + "x" + std::to_string(BN) +
+                                     "x" + std::to_string(KV * El<DT>::VEC) + "s" + std::to_string(NS);
+    static const std::string n_one = "igemm_dma_" + shape, n_taps = "igemm_dma_taps_" + shape;
+    const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
+    li.kernel = taps ? n_taps.c_str() : n_one.c_str();
+    li.phases = ks > 1 ? 2 : 1;
+    if (phase == 2) li.kernel = "splitk_finish";
+    if (dry || li.workgroups == 0) return li;
+    dim3 grid(tiles_m * tiles_n, ks, z), block(THREADS);
+    if (phase == 2) {
+        if (ks > 1) launch_finish<T>(a, s);
+        return li;
+    }
+    if (taps) GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, true>), grid, block, 0, s, a);
+    else GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, false>), grid, block, 0, s, a);
+    if (ks > 1 && phase == 0) launch_finish<T>(a, s);
+    return li;
+}
+
 // rowgemm_kernel is taken when the operator is a single-tap, unpadded, unsplit bf16 product whose rows are at most
 // 192 bytes of K (measured: beyond that, and for fp32 at any K, the tiled kernel is as fast or faster): properties
 // of the operator, not of the launched sub-range, so every chunk of an operator takes the same path as its
@@ -862,7 +1157,7 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
     constexpr double e_small = DT == DT_BF16 ? 0.8 : 1.0, e_mid = e_small;
     auto cost = [&](int bm, int bnn, double eff) {
         const int64_t w = wgs(bm, bnn);
-        return (double)((w + 255) / 256) * bm * bnn / eff * (w < 256 ? 1.25 : 1.0);
+        return (double)((w + 255) / 256) * bm * bnn / eff * (w < 256 ? 1.1 : 1.0);
     };
     int shape = 0;                               // 0: 64x64, 1: 128x64, 2: 128x128, 3: 128x32
     if (bn < 64) shape = 3;
@@ -870,6 +1165,22 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
         double best = cost(64, 64, e_small);
         if (cost(128, 64, e_mid) < best * 0.999) { best = cost(128, 64, e_mid); shape = 1; }
         if (bn == 128 && cost(128, 128, 1.0) < best * 0.999) shape = 2;
+    }
+    // Long K rows: the direct-to-LDS pipeline (igemm_dma_kernel) keeps several K blocks in flight and wins once the K
+    // loop is long enough to amortise filling its stages (measured layer by layer: from about 1.5 KB of K per row).
+    const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
+    if (vec_ok && !a.b_trans && shape != 3 && (!taps || a.kh * a.kw <= 31) && (int64_t)a.K * (int64_t)sizeof(typename El<DT>::T) >= 1536) {
+        const bool long_k = (int64_t)a.K * (int64_t)sizeof(typename El<DT>::T) >= 4096;
+        if (shape == 2) {
+            // 256x128 halves the L2 traffic of the A operand per flop again; it needs enough rows to still fill the chip
+            if (DT == DT_BF16 && wgs(256, 128) >= 384) return go_dma<DT, 256, 128, 2, 2, 4, 3>(a, s, dry, vec_ok, phase);
+            // one workgroup per compute unit anyway: whole 128-byte row segments (fewer, larger L2 requests)
+            if (wgs(128, 128) <= 256) return go_dma<DT, 128, 128, 2, 2, 8, 3>(a, s, dry, vec_ok, phase);
+            return go_dma<DT, 128, 128, 2, 2, 4, 4>(a, s, dry, vec_ok, phase);
+        }
+        if (shape == 1) return go_dma<DT, 128, 64, 2, 2, 8, 3>(a, s, dry, vec_ok, phase);
+        if (long_k) return go_dma<DT, 64, 64, 2, 2, 8, 4>(a, s, dry, vec_ok, phase);
+        return go_dma<DT, 64, 64, 2, 2, 8, 3>(a, s, dry, vec_ok, phase);
     }
     if (a.b_trans || a.K <= 16 * VEC || !vec_ok) {   // short K, or the latency-bound gather loader (more waves per unit): 64-byte blocks
         switch (shape) {

@@ -36,6 +36,7 @@ class Session:
         B.check(self.ctx, B.gacer_create(C.byref(self.ctx)))
         self._keep = []
         self.streams = []
+        self.sibling_streams = []
         place = place_streams and not shared_stream and len(tenants) > 1
         self.acts = []          # per tenant: list of device tensors (channels-last)
         descs = (B.gacer_tenant * len(tenants))()
@@ -99,28 +100,33 @@ class Session:
         over the device's hardware queues; see gacer_probe_stream_queues)."""
         cands = [torch.cuda.Stream(device=self.dev) for _ in range(16)]
         arr = (C.c_void_p * len(cands))(*[c.cuda_stream for c in cands])
-        chosen, queue_of, nq = (C.c_int * n)(), (C.c_int * n)(), C.c_int()
-        st = B.gacer_place_streams(descs, n, arr, len(cands), chosen, queue_of, C.byref(nq))
+        chosen, queue_of, nq, sib = (C.c_int * n)(), (C.c_int * n)(), C.c_int(), (C.c_int * n)()
+        st = B.gacer_place_streams(descs, n, arr, len(cands), chosen, queue_of, C.byref(nq), sib)
         if st != B.GACER_OK:
             raise RuntimeError(f"gacer_place_streams failed with status {st}")
         self.queue_groups = nq.value
         self.tenant_queue = list(queue_of)
         self.streams = [cands[i] for i in chosen]
+        self.sibling_streams = [cands[i] if i >= 0 else None for i in sib]
         for ti in range(n):
             descs[ti].stream = C.c_void_p(self.streams[ti].cuda_stream)
+            if self.sibling_streams[ti] is not None:
+                descs[ti].sibling_stream = C.c_void_p(self.sibling_streams[ti].cuda_stream)
 
     # -- plan ------------------------------------------------------------------------------------
     def set_plan(self, splits=(), syncs=()):
         """splits: iterable of (tenant, op, axis-name, factor) for even chunks, or (tenant, op, axis-name, [sizes...])
-        for an explicit chunk list; syncs: (src_t, src_op, dst_t, dst_op[, when])."""
+        for an explicit chunk list, each optionally followed by True to put the odd chunks on the tenant's sibling stream;
+        syncs: (src_t, src_op, dst_t, dst_op[, when])."""
         rows, keep = [], []
-        for (t, o, a, f) in splits:
+        for row in splits:
+            (t, o, a, f), sib = row[:4], (1 if len(row) > 4 and row[4] else 0)
             if isinstance(f, (list, tuple)):
                 arr = (C.c_int * len(f))(*f)
                 keep.append(arr)
-                rows.append(B.gacer_split(t, o, AXIS[a], len(f), arr))
+                rows.append(B.gacer_split(t, o, AXIS[a], len(f), arr, sib))
             else:
-                rows.append(B.gacer_split(t, o, AXIS[a], f, None))
+                rows.append(B.gacer_split(t, o, AXIS[a], f, None, sib))
         sp = (B.gacer_split * max(1, len(rows)))(*rows)
         sy = (B.gacer_sync * max(1, len(syncs)))(*[B.gacer_sync(*e) for e in syncs])
         plan = B.gacer_plan(len(splits), sp, len(syncs), sy)
@@ -248,7 +254,7 @@ class Session:
         for i in range(pl.n_split):
             sp = pl.split[i]
             f = [sp.sizes[j] for j in range(sp.factor)] if sp.sizes else sp.factor
-            splits.append((sp.tenant, sp.op, inv[sp.axis], f))
+            splits.append((sp.tenant, sp.op, inv[sp.axis], f) + ((True,) if sp.sibling else ()))
         syncs = [(pl.sync[i].src_tenant, pl.sync[i].src_op, pl.sync[i].dst_tenant, pl.sync[i].dst_op, pl.sync[i].when)
                  for i in range(pl.n_sync)]
         return splits, syncs

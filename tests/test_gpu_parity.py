@@ -155,6 +155,31 @@ def test_random_conv_shapes(gpu, dtype):
     _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_long_k_conv_shapes(gpu, dtype):
+    """Convolutions and GEMMs whose K rows are long enough for the direct-to-LDS pipeline (several stages of K blocks in
+    flight): ragged M / N / K tails, taps narrower and wider than a K block, strides, K ranges cut into slices, wide
+    outputs that take the larger tiles.  Parity on every tensor, bit-exactness under decomposition."""
+    from synth import graphs as G
+    specs = [  # (batch, hw, cin, [(cout, k, stride, pad, act, residual)])
+        (3, 9, 64, [(100, 5, 1, 2, "relu", False), (136, 3, 2, 1, "none", False), (136, 3, 1, 1, "relu6", True)]),
+        (2, 14, 72, [(64, 3, 1, 1, "relu", False), (256, 3, 1, 1, "gelu", False), (24, 1, 1, 0, "none", False)]),
+        (5, 7, 40, [(264, 5, 1, 2, "relu", False), (264, 3, 1, 1, "relu", True), (33, 3, 1, 0, "none", False)]),
+        (1, 12, 512, [(128, 1, 1, 0, "relu", False), (512, 3, 1, 1, "relu", False), (520, 1, 2, 0, "none", False)]),
+        (4, 6, 2048, [(64, 1, 1, 0, "none", False), (96, 3, 1, 1, "relu", False)]),
+    ]
+    tenants = []
+    for ti, (batch, hw, cin, layers) in enumerate(specs):
+        b = G._B(f"longk{ti}", dtype, batch)
+        x = y = b.tensor(batch, cin, hw, hw)
+        for (cout, k, stride, pad, act, res) in layers:
+            y = b.conv(y, cout, k, stride, pad, act, res=y if res else -1)
+        y = b.gemm(y, 40, "relu", flatten=True)                    # a long flattened K with one row per item
+        tenants.append(b.done(x, b.gemm(y, 10, flatten=True)))
+    data = [G.materialise(t, 123, i << 20) for i, t in enumerate(tenants)]
+    _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
+
+
 def test_stream_placement_over_hardware_queues(gpu):
     """Streams that share a hardware queue serialise: the probe must give the same grouping twice, the harness must put
     up to `queues` tenants on distinct queues, and placement must not change any output."""

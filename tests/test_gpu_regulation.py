@@ -170,3 +170,48 @@ def test_searched_plan_end_to_end(gpu, config):
     sess.set_plan(sp2, sy2)                       # the returned plan is itself installable
     check("refined, reinstalled")
     sess.close()
+
+
+def test_sibling_stream_decomposition(gpu):
+    """Chunks of one operator on two streams of the same tenant (Section 5.4, Table 3: a model's batch decomposed over
+    streams): bit-identical outputs with pointers, decomposition of the other tenant and per-tenant issue threads mixed
+    in, K-sliced operators included (their chunks own disjoint parts of the workspace); and the two chunks of an
+    operator really do overlap in time."""
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(2)                      # ResNet-18(8) + MobileNetV2(8), full size
+    sess = gpu.Session(tenants, data)
+    assert sess.sibling_streams[0] is not None and sess.sibling_streams[0].cuda_stream != sess.streams[0].cuda_stream
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    base = [sess.output_bytes(i) for i in range(2)]
+    n_ops = [len(t.ops) for t in tenants]
+    halves = [(0, i, "batch", [4, 4], True) for i in range(n_ops[0])]
+    plans = {"r18 halves on two streams": (halves, []),
+             "+ pointers and mobilenet cout x2": (halves + sess.uniform_splits("cout", 2, tenants=[1]),
+                                                  sess.edges_from_pointers([[n // 3, 2 * n // 3] for n in n_ops])),
+             "quarters alternating, uneven": ([(0, i, "batch", [3, 2, 2, 1], True) for i in range(n_ops[0])] +
+                                              [(1, i, "batch", [5, 3], True) for i in range(n_ops[1])], [])}
+    for threads in (False, True):
+        sess.set_issue_threads(threads)
+        for name, (splits, syncs) in plans.items():
+            sess.set_plan(splits, syncs)
+            sess.poison_outputs()
+            sess.run(B.GACER_MODE_PLAN, 3)
+            for i in range(2):
+                assert sess.output_bytes(i) == base[i], f"{name} (threads={threads}): tenant {i} differs"
+            sess.poison_outputs()
+            sess.run_static(B.GACER_MODE_PLAN, 1)
+            for i in range(2):
+                assert sess.output_bytes(i) == base[i], f"{name}: tenant {i} differs with the static workspace"
+    sess.set_issue_threads(False)
+    sess.set_plan(halves, [])
+    rows = [r for r in sess.trace(B.GACER_MODE_PLAN, 2) if r["tenant"] == 0 and r["kernel"] != "splitk_finish"]
+    by_op = {}
+    for r in rows:
+        by_op.setdefault(r["op"], {})[r["chunk"]] = r
+    overlapping = [op for op, ch in by_op.items() if len(ch) == 2 and ch[1]["start_ms"] < ch[0]["end_ms"] and ch[0]["start_ms"] < ch[1]["end_ms"]]
+    assert len(overlapping) >= len(by_op) // 4, f"only {len(overlapping)} of {len(by_op)} operators had their two chunks overlap"
+    # and the next operator starts only after both chunks of the previous one have ended
+    ends = {op: max(c["end_ms"] for c in ch.values()) for op, ch in by_op.items()}
+    starts = {op: min(c["start_ms"] for c in ch.values()) for op, ch in by_op.items()}
+    assert all(starts[op + 1] >= ends[op] - 1e-6 for op in by_op if op + 1 in by_op)
+    sess.close()

@@ -420,3 +420,20 @@ def test_run_static_rejects_more_workspace_than_it_holds(ctx):
     assert st == B.GACER_OK
     assert B.gacer_run_static(ctx, B.GACER_MODE_STREAM_PARALLEL, 1) in (B.GACER_ESTATE, B.GACER_EHIP)
     assert B.gacer_run_static(ctx, 7, 1) == B.GACER_EINVAL and B.gacer_run_static(None, 0, 1) == B.GACER_EINVAL
+
+
+def test_sibling_flag_in_plans(ctx):
+    """gacer_split.sibling is accepted on any decomposition and changes neither the launch count nor validation."""
+    tenants = [synth.small_resnet("f32", 4), synth.small_mbv2("f32", 4)]
+    st, keep = load(ctx, tenants)
+    assert st == B.GACER_OK
+    arr = (C.c_int * 2)(3, 1)
+    sp = (B.gacer_split * 2)(B.gacer_split(0, 0, B.GACER_AXIS_BATCH, 2, arr, 1), B.gacer_split(1, 2, B.GACER_AXIS_COUT, 2, None, 1))
+    plan = B.gacer_plan(2, sp, 0, None)
+    assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_OK, B.gacer_last_error(ctx)
+    n = C.c_int()
+    B.gacer_launch_count(ctx, B.GACER_MODE_PLAN, C.byref(n))
+    assert n.value == sum(len(t.ops) for t in tenants) + 2
+    bad = (B.gacer_split * 1)(B.gacer_split(0, 0, B.GACER_AXIS_BATCH, 8, None, 1))              # factor > batch, sibling or not
+    plan = B.gacer_plan(1, bad, 0, None)
+    assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_EPLAN
