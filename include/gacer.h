@@ -260,6 +260,17 @@ gacer_status gacer_search(gacer_ctx *ctx, const gacer_prof *prof, size_t n, int 
 gacer_status gacer_model_residue(gacer_ctx *ctx, const gacer_prof *prof, size_t n, const gacer_split *split,
                                  int n_split, const int *P, int n_ptr, double *residue_out, double *makespan_out);
 
+/*
+ * Offline deployment (Section 4.4, "Search Cost Analysis for Offline/Online Deployment"): a searched plan written
+ * out as text, to be stored per deployment scenario and installed later without searching again.
+ * gacer_plan_to_text writes a NUL-terminated text of *len bytes (terminator included) into buf; buf == NULL or
+ * cap == 0 only sizes; GACER_EINVAL when cap is too small.  gacer_plan_from_text parses such a text into a
+ * library-allocated plan (free with gacer_plan_free); GACER_EPLAN on anything it does not recognise.  The text is
+ * not validated against tenants here: gacer_set_plan does that when the plan is installed.
+ */
+gacer_status gacer_plan_to_text(const gacer_plan *plan, char *buf, size_t cap, size_t *len);
+gacer_status gacer_plan_from_text(const char *text, gacer_plan **out);
+
 void gacer_plan_free(gacer_plan *plan);
 /* Text of the last error on this context ("" if none); valid until the next call. */
 const char *gacer_last_error(const gacer_ctx *ctx);

@@ -25,7 +25,8 @@ EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_pla
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
            "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats", "gacer_capture",
            "gacer_release_graphs", "gacer_set_issue_threads", "gacer_probe_stream_queues", "gacer_place_streams",
-           "gacer_refine", "gacer_run_static"]
+           "gacer_refine", "gacer_run_static", "gacer_plan_to_text",
+           "gacer_plan_from_text"]
 
 
 class gacer_tensor(C.Structure):
@@ -90,6 +91,8 @@ def _load():
                                  C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_double)]
     lib.gacer_model_residue.argtypes = [ctx, C.POINTER(gacer_prof), C.c_size_t, C.POINTER(gacer_split), C.c_int,
                                         C.POINTER(C.c_int), C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.gacer_plan_to_text.argtypes = [C.POINTER(gacer_plan), C.c_char_p, C.c_size_t, C.POINTER(C.c_size_t)]
+    lib.gacer_plan_from_text.argtypes = [C.c_char_p, C.POINTER(C.POINTER(gacer_plan))]
     lib.gacer_plan_free.argtypes = [C.POINTER(gacer_plan)]
     lib.gacer_plan_free.restype = None
     lib.gacer_last_error.argtypes = [ctx]
@@ -121,6 +124,8 @@ gacer_profile = lib.gacer_profile
 gacer_search = lib.gacer_search
 gacer_model_residue = lib.gacer_model_residue
 gacer_plan_free = lib.gacer_plan_free
+gacer_plan_to_text = lib.gacer_plan_to_text
+gacer_plan_from_text = lib.gacer_plan_from_text
 gacer_last_error = lib.gacer_last_error
 gacer_launch_count = lib.gacer_launch_count
 gacer_trace_run = lib.gacer_trace_run

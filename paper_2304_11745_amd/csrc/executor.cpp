@@ -698,6 +698,82 @@ gacer_status gacer_plan_from_pointers(gacer_ctx *c, const int *P, int n_ptr, gac
     return GACER_OK;
 }
 
+// Plan <-> text.  One line per entry:  "split <tenant> <op> <axis> <factor> <sibling> [size ...]"  /  "sync <src_tenant>
+// <src_op> <dst_tenant> <dst_op> <when>", after a header line "gacer-plan 1".
+gacer_status gacer_plan_to_text(const gacer_plan *plan, char *buf, size_t cap, size_t *len)
+{
+    if (!plan || !len || plan->n_split < 0 || plan->n_sync < 0 || (plan->n_split > 0 && !plan->split) || (plan->n_sync > 0 && !plan->sync))
+        return GACER_EINVAL;
+    std::string text = "gacer-plan 1\n";
+    char line[160];
+    for (int k = 0; k < plan->n_split; ++k) {
+        const gacer_split &s = plan->split[k];
+        std::snprintf(line, sizeof line, "split %d %d %d %d %d", s.tenant, s.op, (int)s.axis, s.factor, s.sibling ? 1 : 0);
+        text += line;
+        if (s.sizes) {
+            if (s.factor < 1 || s.factor > 8) return GACER_EINVAL;
+            for (int j = 0; j < s.factor; ++j) { std::snprintf(line, sizeof line, " %d", s.sizes[j]); text += line; }
+        }
+        text += "\n";
+    }
+    for (int k = 0; k < plan->n_sync; ++k) {
+        const gacer_sync &e = plan->sync[k];
+        std::snprintf(line, sizeof line, "sync %d %d %d %d %d\n", e.src_tenant, e.src_op, e.dst_tenant, e.dst_op, e.when);
+        text += line;
+    }
+    *len = text.size() + 1;
+    if (!buf || cap == 0) return GACER_OK;
+    if (cap < text.size() + 1) return GACER_EINVAL;
+    std::memcpy(buf, text.c_str(), text.size() + 1);
+    return GACER_OK;
+}
+
+gacer_status gacer_plan_from_text(const char *text, gacer_plan **out)
+{
+    if (!text || !out) return GACER_EINVAL;
+    std::vector<gacer_split> splits;
+    std::vector<gacer_sync> syncs;
+    std::vector<std::vector<int>> lists;
+    std::vector<size_t> list_of;                      // per split: index into lists, or npos
+    const char *p = text;
+    bool header = false;
+    while (*p) {
+        const char *eol = std::strchr(p, '\n');
+        const std::string line(p, eol ? (size_t)(eol - p) : std::strlen(p));
+        p = eol ? eol + 1 : p + line.size();
+        if (line.find_first_not_of(" \t\r") == std::string::npos) continue;
+        int a[5], used = 0;
+        if (!header) {
+            int version = 0;
+            if (std::sscanf(line.c_str(), "gacer-plan %d", &version) != 1 || version != 1) return GACER_EPLAN;
+            header = true;
+        } else if (std::sscanf(line.c_str(), "split %d %d %d %d %d%n", &a[0], &a[1], &a[2], &a[3], &a[4], &used) == 5) {
+            if (a[2] < 0 || a[2] > 2 || a[3] < 1 || a[3] > 8) return GACER_EPLAN;
+            std::vector<int> sizes;
+            const char *q = line.c_str() + used;
+            int v = 0, adv = 0;
+            while (std::sscanf(q, " %d%n", &v, &adv) == 1) { sizes.push_back(v); q += adv; }
+            if (q[std::strspn(q, " \t\r")] != 0) return GACER_EPLAN;
+            if (!sizes.empty() && (int)sizes.size() != a[3]) return GACER_EPLAN;
+            splits.push_back({a[0], a[1], (gacer_axis)a[2], a[3], nullptr, a[4] ? 1 : 0});
+            list_of.push_back(sizes.empty() ? (size_t)-1 : lists.size());
+            if (!sizes.empty()) lists.push_back(sizes);
+        } else if (std::sscanf(line.c_str(), "sync %d %d %d %d %d%n", &a[0], &a[1], &a[2], &a[3], &a[4], &used) == 5 &&
+                   line.find_first_not_of(" \t\r", (size_t)used) == std::string::npos) {
+            syncs.push_back({a[0], a[1], a[2], a[3], a[4]});
+        } else {
+            return GACER_EPLAN;
+        }
+    }
+    if (!header) return GACER_EPLAN;
+    for (size_t k = 0; k < splits.size(); ++k)
+        if (list_of[k] != (size_t)-1) splits[k].sizes = lists[list_of[k]].data();
+    gacer_plan *pl = make_plan(splits, syncs);
+    if (!pl) return GACER_ENOMEM;
+    *out = pl;
+    return GACER_OK;
+}
+
 void gacer_plan_free(gacer_plan *p)
 {
     if (!p) return;

@@ -437,3 +437,47 @@ def test_sibling_flag_in_plans(ctx):
     bad = (B.gacer_split * 1)(B.gacer_split(0, 0, B.GACER_AXIS_BATCH, 8, None, 1))              # factor > batch, sibling or not
     plan = B.gacer_plan(1, bad, 0, None)
     assert B.gacer_set_plan(ctx, C.byref(plan)) == B.GACER_EPLAN
+
+
+def test_plan_text_round_trip(ctx):
+    """Offline deployment (Section 4.4): a plan survives being written out and read back, chunk lists, sibling flags and
+    hub edges included, and the parsed plan installs; malformed text is refused."""
+    tenants = [synth.small_resnet("f32", 6), synth.small_mbv2("f32", 4)]
+    st, keep = load(ctx, tenants)
+    assert st == B.GACER_OK
+    flat = (C.c_int * 4)(2, 5, 3, 9)
+    edges = C.POINTER(B.gacer_plan)()
+    assert B.gacer_plan_from_pointers(ctx, flat, 2, C.byref(edges)) == B.GACER_OK
+    sizes = (C.c_int * 3)(3, 2, 1)
+    sp = (B.gacer_split * 3)(B.gacer_split(0, 0, B.GACER_AXIS_BATCH, 3, sizes, 1), B.gacer_split(0, 2, B.GACER_AXIS_COUT, 2, None, 0),
+                             B.gacer_split(1, 1, B.GACER_AXIS_BATCH, 4, None, 1))
+    plan = B.gacer_plan(3, sp, edges.contents.n_sync, edges.contents.sync)
+    n = C.c_size_t()
+    assert B.gacer_plan_to_text(C.byref(plan), None, 0, C.byref(n)) == B.GACER_OK and n.value > 20
+    buf = C.create_string_buffer(n.value)
+    assert B.gacer_plan_to_text(C.byref(plan), buf, n.value - 1, C.byref(n)) == B.GACER_EINVAL        # too small
+    assert B.gacer_plan_to_text(C.byref(plan), buf, n.value, C.byref(n)) == B.GACER_OK
+    text = buf.value.decode()
+    assert text.splitlines()[0] == "gacer-plan 1" and "split 0 0 1 3 1 3 2 1" in text.splitlines()
+    back = C.POINTER(B.gacer_plan)()
+    assert B.gacer_plan_from_text(buf.value, C.byref(back)) == B.GACER_OK
+    b = back.contents
+    assert b.n_split == 3 and b.n_sync == plan.n_sync
+    assert [b.split[0].sizes[j] for j in range(3)] == [3, 2, 1] and b.split[0].sibling == 1 and not b.split[1].sizes
+    assert [(b.split[k].tenant, b.split[k].op, b.split[k].axis, b.split[k].factor, b.split[k].sibling) for k in range(3)] == \
+        [(0, 0, 1, 3, 1), (0, 2, 2, 2, 0), (1, 1, 1, 4, 1)]
+    for k in range(plan.n_sync):
+        assert tuple(getattr(b.sync[k], f) for f in ("src_tenant", "src_op", "dst_tenant", "dst_op", "when")) == \
+            tuple(getattr(plan.sync[k], f) for f in ("src_tenant", "src_op", "dst_tenant", "dst_op", "when"))
+    assert B.gacer_set_plan(ctx, back) == B.GACER_OK, B.gacer_last_error(ctx)
+    buf2 = C.create_string_buffer(n.value)
+    assert B.gacer_plan_to_text(back, buf2, n.value, C.byref(n)) == B.GACER_OK and buf2.value == buf.value
+    B.gacer_plan_free(back)
+    B.gacer_plan_free(edges)
+    for bad in (b"", b"split 0 0 1 2 0\n", b"gacer-plan 2\n", b"gacer-plan 1\nsplit 0 0 1 2\n", b"gacer-plan 1\nsplit 0 0 1 3 0 2 1\n",
+                b"gacer-plan 1\nsync 0 1 1 0\n", b"gacer-plan 1\nsplit 0 0 7 2 0\n", b"gacer-plan 1\nhello\n", b"gacer-plan 1\nsplit 0 0 1 2 0 4 x\n"):
+        out = C.POINTER(B.gacer_plan)()
+        assert B.gacer_plan_from_text(bad, C.byref(out)) == B.GACER_EPLAN, bad
+    empty = C.POINTER(B.gacer_plan)()
+    assert B.gacer_plan_from_text(b"gacer-plan 1\n", C.byref(empty)) == B.GACER_OK and empty.contents.n_split == 0
+    B.gacer_plan_free(empty)
