@@ -226,6 +226,16 @@ __device__ __forceinline__ void igemm_epilogue(const GemmArgs &a, f32x16 (&acc)[
         }
 }
 
+// Workgroups are handed to the 8 XCDs round-robin by their index, and each XCD has its own L2.  Neighbouring tiles share
+// operand rows (the halo of a k x k window, the A rows of tiles that differ only in n, the B rows of tiles that differ
+// only in m), so tile numbers are dealt such that every XCD works on one contiguous run of them: workgroup b -> XCD
+// b % 8 -> the (b / 8)-th tile of that XCD's run.  Whether the runs are bands of m or bands of n is tile_order()'s choice.
+__device__ __forceinline__ int xcd_contiguous(int b, int n)
+{
+    const int q = n >> 3, r = n & 7, x = b & 7;
+    return __builtin_amdgcn_readfirstlane(x * q + min(x, r) + (b >> 3));
+}
+
 template <int DT, int BM, int BN, int WM, int WN, int KV, int LOAD>
 __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 {
@@ -250,8 +260,10 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
-    const int tile_m = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / tiles_n));
-    const int tile_n = (int)blockIdx.x - tile_m * tiles_n;
+    const int tile = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
+    const int tiles_m = (int)gridDim.x / tiles_n;
+    const int tile_m = __builtin_amdgcn_readfirstlane(a.n_major ? tile % tiles_m : tile / tiles_n);
+    const int tile_n = __builtin_amdgcn_readfirstlane(a.n_major ? tile / tiles_m : tile % tiles_n);
     const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
 
     const int z = blockIdx.z;
@@ -566,8 +578,10 @@ void igemm_dma_kernel(GemmArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
-    const int tile_m = __builtin_amdgcn_readfirstlane((int)(blockIdx.x / tiles_n));
-    const int tile_n = (int)blockIdx.x - tile_m * tiles_n;
+    const int tile = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
+    const int tiles_m = (int)gridDim.x / tiles_n;
+    const int tile_m = __builtin_amdgcn_readfirstlane(a.n_major ? tile % tiles_m : tile / tiles_n);
+    const int tile_n = __builtin_amdgcn_readfirstlane(a.n_major ? tile / tiles_m : tile % tiles_n);
     const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
 
     const int z = blockIdx.z;
@@ -992,6 +1006,18 @@ static void launch_finish(const GemmArgs &a, hipStream_t s)
         GACER_LAUNCH((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
 }
 
+// Tile numbering of a launch.  m-major numbering gives every XCD a band of output rows: A is fetched into one L2 only,
+// B into every L2 that holds a band; n-major numbering is the mirror image.  Takes the order that moves fewer bytes
+// into the L2s (late convolution layers have far more weights than activations, early ones the opposite).
+static int tile_order(const GemmArgs &a, int tiles_m, int tiles_n, int esz)
+{
+    const double Ml = a.m_hi - a.m_lo, Nl = a.n_hi - a.n_lo;
+    const double A = Ml * a.stride * a.stride * (double)(a.K / (a.kh * a.kw)) * esz;     // input pixels behind the output rows
+    const double B = Nl * (double)a.K * esz;
+    const double m_major = A + (tiles_m < 8 ? tiles_m : 8) * B, n_major = B + (tiles_n < 8 ? tiles_n : 8) * A;
+    return n_major < m_major ? 1 : 0;
+}
+
 // ------------------------------------------------------------------------------------------------
 template <int DT, int BM, int BN, int WM, int WN, int KV>
 static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, int phase)
@@ -1022,14 +1048,16 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
         if (ks > 1) launch_finish<T>(a, s);
         return li;
     }
+    GemmArgs b = a;
+    b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
     if (a.b_trans)
-        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, b);
     else if (!vec_ok)
-        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, b);
     else if (taps)
-        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_TAPS>), grid, block, 0, s, b);
     else
-        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, a);
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_VEC>), grid, block, 0, s, b);
     if (ks > 1 && phase == 0) launch_finish<T>(a, s);
     return li;
 }
@@ -1063,8 +1091,10 @@ static LaunchInfo go_dma(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok
         if (ks > 1) launch_finish<T>(a, s);
         return li;
     }
-    if (taps) GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, true>), grid, block, 0, s, a);
-    else GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, false>), grid, block, 0, s, a);
+    GemmArgs b = a;
+    b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
+    if (taps) GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, true>), grid, block, 0, s, b);
+    else GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, false>), grid, block, 0, s, b);
     if (ks > 1 && phase == 0) launch_finish<T>(a, s);
     return li;
 }

@@ -46,6 +46,7 @@ struct GemmArgs {
     // operator from its unsplit shape, so every decomposition adds in the same order.
     int ksplit, kb_per_slice;
     float *ws;
+    int n_major;               // set by the launcher: tiles are numbered n-major (1) or m-major (0), see tile_order()
 };
 
 // Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).
