@@ -30,7 +30,7 @@ HBM_PEAK = 8.0e12
 TRAFFIC = {
     2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": None, "write_bytes": None, "sources_sha256": ""},
 }
-TRAFFIC_SOURCES = ["igemm.hip", "device_util.h", "kernels.h", "executor.cpp"]
+TRAFFIC_SOURCES = ["igemm.hip", "stream_ops.hip", "device_util.h", "kernels.h"]
 
 
 def sources_digest():

@@ -300,6 +300,16 @@ gacer_status gacer_release_graphs(gacer_ctx *ctx);
 gacer_status gacer_set_issue_threads(gacer_ctx *ctx, int enable);
 
 /*
+ * Checking mode for finding a missing dependency or a failing launch (the regulation of Section 4.3 is only correct if
+ * the sync pointers order everything that needs ordering): with enable != 0, gacer_run and gacer_run_static wait
+ * for every kernel and read the device's status before issuing the next one, so the launches of all tenants run one
+ * at a time in issue order, captured graphs are not replayed, and a failure is reported as
+ * GACER_EHIP with the tenant, operator, chunk, kernel name and workgroup count of the launch that caused it.  Outputs
+ * must be bit-identical to those of the ordinary mode; if they are not, the plan lacks an edge.  Not for timing.
+ */
+gacer_status gacer_set_sync_every_launch(gacer_ctx *ctx, int enable);
+
+/*
  * Stream placement aid.  The device runs the streams of a process on a small number of hardware queues, and kernels of
  * two streams that landed on the same queue never overlap: tenants on such streams run one after the other however
  * the plan orders them (Section 2.1's concurrent streams silently turn sequential).  This call finds out, by

@@ -70,6 +70,9 @@ struct Ctx {
     std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
     hipGraphExec_t graph_exec[3] = {nullptr, nullptr, nullptr};   // captured round per mode (optional)
     bool issue_threads = false;                     // one host thread per tenant enqueues that tenant's stream
+    bool sync_every_launch = false;                 // checking mode: wait for, and check, every kernel before the next is issued
+    bool capturing = false;                         // a stream capture is open: nothing may synchronise
+    std::string launch_detail;                      // checking mode: which launch failed
     std::vector<float *> ws_run;                    // split-K workspace each tenant uses in the call in progress
     Trace *trace = nullptr;                         // set while gacer_trace_run issues its rounds
     double last_issue_ms = 0;                       // host time the last gacer_run spent enqueueing

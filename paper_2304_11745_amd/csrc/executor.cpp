@@ -29,6 +29,15 @@ using namespace gacer;
         if (e_ != hipSuccess) return fail(ctx, GACER_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));  \
     } while (0)
 
+// issue_op under the checking mode names the launch that failed
+#define ISSUE(ctx, call)                                                                                    \
+    do {                                                                                                    \
+        (ctx)->launch_detail.clear();                                                                       \
+        hipError_t e_ = (call);                                                                             \
+        if (e_ != hipSuccess && !(ctx)->launch_detail.empty()) return fail(ctx, GACER_EHIP, "%s", (ctx)->launch_detail.c_str()); \
+        if (e_ != hipSuccess) return fail(ctx, GACER_EHIP, "issuing an operator failed: %s", hipGetErrorString(e_)); \
+    } while (0)
+
 // Workspace of gacer_run_static: device memory that belongs to the loaded code object, so that an entry point which
 // may not allocate still has somewhere to put split-K partial tiles.  Every GPU the library runs on holds its own copy
 // until the process ends.  In host code the array's name is only a stand-in; its device address is taken once per
@@ -842,6 +851,20 @@ hipError_t issue_op(Ctx *c, int t, int i, const OpExec &e, hipStream_t s, bool w
                 launch_timer = nullptr;
             }
         }
+    } else if (c->sync_every_launch && !c->capturing) {
+        // checking mode: every kernel is waited for and its status read before anything else is issued, so that a
+        // failure is reported with the launch that caused it
+        for (size_t j = 0; j < e.chunks.size(); ++j) {
+            hipStream_t sj = (j & 1) ? s2 : s;
+            const LaunchInfo li = enqueue(e.chunks[j], sj, false, 0, ws);
+            if ((err = hipStreamSynchronize(sj)) != hipSuccess || (err = hipGetLastError()) != hipSuccess) {
+                char buf[256];
+                std::snprintf(buf, sizeof buf, "tenant %d op %d chunk %zu (%s, %d workgroups): %s", t, i, j, li.kernel, li.workgroups,
+                              hipGetErrorString(err));
+                c->launch_detail = buf;
+                return err;
+            }
+        }
     } else {
         for (size_t j = 0; j < e.chunks.size(); ++j) enqueue(e.chunks[j], (j & 1) ? s2 : s, false, 0, ws);
     }
@@ -892,7 +915,7 @@ gacer_status issue_round(Ctx *c, int mode, int round)
     if (mode == GACER_MODE_SEQUENTIAL) {
         for (int t = 0; t < NT; ++t)
             for (int i = 0; i < (int)c->plain_exec[t].size(); ++i)
-                HIPCHK(c, issue_op(c, t, i, c->plain_exec[t][i], s0, false, round, nullptr));
+                ISSUE(c, issue_op(c, t, i, c->plain_exec[t][i], s0, false, round, nullptr));
         return GACER_OK;
     }
     hipEvent_t fork = c->join_events[NT];
@@ -903,7 +926,7 @@ gacer_status issue_round(Ctx *c, int mode, int round)
     const auto &order = plan ? c->plan_order : c->par_order;
     const auto &ex = plan ? c->plan_exec : c->plain_exec;
     for (const auto &to : order)
-        HIPCHK(c, issue_op(c, to.first, to.second, ex[to.first][to.second], c->tenants[to.first].stream, plan, round, nullptr));
+        ISSUE(c, issue_op(c, to.first, to.second, ex[to.first][to.second], c->tenants[to.first].stream, plan, round, nullptr));
     for (int t = 1; t < NT; ++t)
         if (c->tenants[t].stream != s0) {
             HIPCHK(c, hipEventRecord(c->join_events[t], c->tenants[t].stream));
@@ -1003,7 +1026,7 @@ gacer_status run_rounds(Ctx *c, int mode, int rounds, bool allow_graph)
 {
     hipStream_t s0 = c->tenants[0].stream;
     const auto host_t0 = std::chrono::steady_clock::now();
-    const bool graph = allow_graph && c->graph_exec[mode];
+    const bool graph = allow_graph && c->graph_exec[mode] && !c->sync_every_launch;   // the checking mode issues every launch itself
     const bool threaded = c->issue_threads && mode != GACER_MODE_SEQUENTIAL && !graph && c->tenants.size() > 1 && distinct_streams(c);
     gacer_status st = GACER_OK;
     if (threaded) {
@@ -1094,7 +1117,9 @@ gacer_status gacer_capture(gacer_ctx *c, int mode)
     for (Tenant &t : c->tenants) HIPCHK(c, hipStreamSynchronize(t.stream));
     use_tenant_workspaces(c);
     HIPCHK(c, hipStreamBeginCapture(s0, hipStreamCaptureModeRelaxed));
+    c->capturing = true;
     st = issue_round(c, mode, 0);
+    c->capturing = false;
     hipGraph_t graph = nullptr;
     const hipError_t e_end = hipStreamEndCapture(s0, &graph);
     if (st != GACER_OK || e_end != hipSuccess || !graph) {
@@ -1123,6 +1148,13 @@ gacer_status gacer_set_issue_threads(gacer_ctx *c, int enable)
 {
     if (!c) return GACER_EINVAL;
     c->issue_threads = enable != 0;
+    return GACER_OK;
+}
+
+gacer_status gacer_set_sync_every_launch(gacer_ctx *c, int enable)
+{
+    if (!c) return GACER_EINVAL;
+    c->sync_every_launch = enable != 0;
     return GACER_OK;
 }
 

@@ -565,13 +565,22 @@ void igemm_dma_kernel(GemmArgs a)
     constexpr int R256 = 256 / ROWB;            // tile rows per 256 bytes of LDS (one sweep over the 64 banks)
     constexpr int PATCH = 32 * 36 * 4;          // bytes of one wave's epilogue patch
     constexpr bool OWN_PATCH = STAGE < PATCH * ((4 + NS - 1) / NS);
-    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && BM % RPP == 0 && BN % RPP == 0 && NS >= 3 && NS <= 4 && (KV == 4 || KV == 8), "tile shape");
+    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && BM % RPP == 0 && BN % RPP == 0 && NS >= 3 && NS <= 8 && (KV == 4 || KV == 8), "tile shape");
     static_assert((NS - 2) * (AV + BV) < 64, "outstanding loads exceed the counter");
 
     __shared__ __align__(1024) unsigned char st0[STAGE];
     __shared__ __align__(1024) unsigned char st1[STAGE];
     __shared__ __align__(1024) unsigned char st2[STAGE];
     __shared__ __align__(1024) unsigned char st3[NS > 3 ? STAGE : 16];
+    __shared__ __align__(1024) unsigned char st4[NS > 4 ? STAGE : 16];
+    __shared__ __align__(1024) unsigned char st5[NS > 5 ? STAGE : 16];
+    __shared__ __align__(1024) unsigned char st6[NS > 6 ? STAGE : 16];
+    __shared__ __align__(1024) unsigned char st7[NS > 7 ? STAGE : 16];
+    // the stages are separate arrays and always named by a compile-time index, so that the compiler can tell a stage
+    // being filled from the one being read (it would otherwise wait for every outstanding load before each LDS read)
+    auto stage_at = [&](int i) -> unsigned char * {
+        return i == 0 ? st0 : i == 1 ? st1 : i == 2 ? st2 : i == 3 ? st3 : i == 4 ? st4 : i == 5 ? st5 : i == 6 ? st6 : st7;
+    };
     __shared__ __align__(16) unsigned char own_patch[OWN_PATCH ? 4 * PATCH : 16];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -638,31 +647,36 @@ void igemm_dma_kernel(GemmArgs a)
         ksx = tap - kr * a.kw;
     }
 
-    // requests this thread's slots of the next K block into `stage` (one call per block, ascending)
+    // Requests for the next K block (one block per step, ascending).  A block is AV + BV loads per thread; they are issued
+    // one at a time (request_part) so that a step can spread them between its MFMA groups: the unit that moves global
+    // data into LDS takes the loads of all four waves in turn, and a wave that queues several at once is held there
+    // while its matrix core runs dry.
     const int wave_slot = wave * 1024;
-    auto request = [&](unsigned char *stage) {
-        const bool k_ok = kv < k_end;
+    bool rq_ok = false;
+    unsigned rq_da = 0, rq_db = 0, rq_tap = 31u;
+    auto request_begin = [&]() {
+        rq_ok = kv < k_end;
+        rq_db = (unsigned)(kv * ESZ);
         if constexpr (TAPS) {
-            const unsigned delta = (unsigned)((((int64_t)kr * a.W + ksx) * a.x_pix + kci) * ESZ);
-            const unsigned tp = k_ok ? (unsigned)(kr * a.kw + ksx) : 31u;      // bit 31 is never set
-#pragma unroll
-            for (int i = 0; i < AV; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, GACER_LDS(stage + i * RPP * ROWB + wave_slot), 16,
-                                                         (int)(((a_hm[i] >> tp) & 1u) ? a_off[i] + delta : OOB), 0, 0, 0);
+            rq_da = (unsigned)((((int64_t)kr * a.W + ksx) * a.x_pix + kci) * ESZ);
+            rq_tap = rq_ok ? (unsigned)(kr * a.kw + ksx) : 31u;                 // bit 31 is never set
         } else {
-            const unsigned delta = (unsigned)(kv * ESZ);
-#pragma unroll
-            for (int i = 0; i < AV; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, GACER_LDS(stage + i * RPP * ROWB + wave_slot), 16,
-                                                         (int)((k_ok && a_hm[i]) ? a_off[i] + delta : OOB), 0, 0, 0);
+            rq_da = rq_db;
         }
-        {
-            const unsigned delta = (unsigned)(kv * ESZ);
-#pragma unroll
-            for (int i = 0; i < BV; ++i)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, GACER_LDS(stage + (BM + i * RPP) * ROWB + wave_slot), 16,
-                                                         (int)((k_ok && b_off[i] != OOB) ? b_off[i] + delta : OOB), 0, 0, 0);
+    };
+    auto request_part = [&](unsigned char *stage, int p) {                      // p in [0, AV + BV), a compile-time constant
+        if (p < AV) {
+            const int i = p;
+            const bool ok = TAPS ? (((a_hm[i] >> rq_tap) & 1u) != 0) : (rq_ok && a_hm[i]);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, GACER_LDS(stage + i * RPP * ROWB + wave_slot), 16,
+                                                     (int)(ok ? a_off[i] + rq_da : OOB), 0, 0, 0);
+        } else {
+            const int i = p - AV;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, GACER_LDS(stage + (BM + i * RPP) * ROWB + wave_slot), 16,
+                                                     (int)((rq_ok && b_off[i] != OOB) ? b_off[i] + rq_db : OOB), 0, 0, 0);
         }
+    };
+    auto request_end = [&]() {
         kv += BK;
         if constexpr (TAPS) {
             kci += BK;
@@ -681,6 +695,12 @@ void igemm_dma_kernel(GemmArgs a)
             }
         }
     };
+    auto request = [&](unsigned char *stage) {                                  // a whole block at once (pipeline fill)
+        request_begin();
+#pragma unroll
+        for (int p = 0; p < AV + BV; ++p) request_part(stage, p);
+        request_end();
+    };
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -691,37 +711,42 @@ void igemm_dma_kernel(GemmArgs a)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     const int lrow = lane & 31, lhalf = lane >> 5;
-    // fragment reads: tile row lrow (+ a multiple of 32, which leaves the swizzle unchanged), logical chunk 2 ks + lhalf
+    // fragment reads: tile row lrow (+ a multiple of 32, which leaves the swizzle unchanged), logical chunk 2 g + lhalf
     const int frag_lo = (lhalf ^ ((lrow / R256) % KV)) * 16;
     const int a_row0 = (wm * (BM / WM) + lrow) * ROWB, b_row0 = (BM + wn * (BN / WN) + lrow) * ROWB;
-    auto compute = [&](const unsigned char *stage) {
+    constexpr int G = KV / 2;                   // k groups (32 bytes of k) per block; group g lives in register set g & 1
+    uint4 fa[2][TM], fb[2][TN];
 #pragma unroll
-        for (int ks = 0; ks < KV / 2; ++ks) {
-            const int col = frag_lo ^ (ks * 32);
-            uint4 fa[TM], fb[TN];
+    for (int i = 0; i < TM; ++i) fa[1][i] = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *(const uint4 *)(stage + a_row0 + i * 32 * ROWB + col);
+    for (int j = 0; j < TN; ++j) fb[1][j] = make_uint4(0u, 0u, 0u, 0u);
+    auto fragments = [&](const unsigned char *stage, int g, int set) {
+        const int col = frag_lo ^ (g * 32);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = *(const uint4 *)(stage + b_row0 + j * 32 * ROWB + col);
-            if constexpr (DT == DT_BF16) {
+        for (int i = 0; i < TM; ++i) fa[set][i] = *(const uint4 *)(stage + a_row0 + i * 32 * ROWB + col);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[set][j] = *(const uint4 *)(stage + b_row0 + j * 32 * ROWB + col);
+    };
+    auto mfmas = [&](int set) {
+        if constexpr (DT == DT_BF16) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[set][i]),
+                                                                        __builtin_bit_cast(bf16x8, fb[set][j]), acc[i][j], 0, 0, 0);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i]),
-                                                                            __builtin_bit_cast(bf16x8, fb[j]), acc[i][j], 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const float av = __uint_as_float(e == 0 ? fa[i].x : e == 1 ? fa[i].y : e == 2 ? fa[i].z : fa[i].w);
-                            const float bv = __uint_as_float(e == 0 ? fb[j].x : e == 1 ? fb[j].y : e == 2 ? fb[j].z : fb[j].w);
-                            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
-                        }
-            }
+                    for (int j = 0; j < TN; ++j) {
+                        const uint4 &va = fa[set][i], &vb = fb[set][j];
+                        const float av = __uint_as_float(e == 0 ? va.x : e == 1 ? va.y : e == 2 ? va.z : va.w);
+                        const float bv = __uint_as_float(e == 0 ? vb.x : e == 1 ? vb.y : e == 2 ? vb.z : vb.w);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[i][j], 0, 0, 0);
+                    }
         }
     };
 
@@ -735,37 +760,43 @@ void igemm_dma_kernel(GemmArgs a)
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
     };
-    // one step: request block kb + NS - 1 into the stage that block kb - 1 has just left, consume block kb
-#define GACER_STEP(cur, into) do { request(into); compute(cur); meet(0); } while (0)
+    // One step consumes block kb from `cur` and requests block kb + NS - 1 into the stage that block kb - 1 has left.
+    // The step is rotated by one k group: the fragments of the last group of a block are in registers (set 1) when the
+    // barrier is passed, and its MFMAs run first in the next step, covering the LDS latency of that step's first
+    // fragments.  Slot 0 of a step is therefore the previous block's last group (before the first block: zeros, which
+    // leave the accumulators at zero), slots 1 .. G - 1 are groups 0 .. G - 2 of this block.  Each slot issues the
+    // fragment reads of the group after it and its share of the block's global requests, then its MFMAs; the
+    // scheduling barriers keep that order in the generated code.  The chain of every accumulator still walks k upwards.
+    constexpr int SCHED_ALU_MAY_CROSS = 0x2 | 0x4;       // vector and scalar ALU may move across; memory operations and MFMAs stay put
+    auto step = [&](const unsigned char *cur, unsigned char *into) {
+        request_begin();
+#pragma unroll
+        for (int slot = 0; slot < G; ++slot) {
+            fragments(cur, slot, slot & 1);
+#pragma unroll
+            for (int p = slot * (AV + BV) / G; p < (slot + 1) * (AV + BV) / G; ++p) request_part(into, p);
+            if (slot == G - 1) request_end();   // address arithmetic for the next block: free to mix with the MFMAs below
+            __builtin_amdgcn_sched_barrier(SCHED_ALU_MAY_CROSS);
+            mfmas((slot & 1) ^ 1);
+            __builtin_amdgcn_sched_barrier(SCHED_ALU_MAY_CROSS);
+        }
+        meet(0);
+    };
 
-    request(st0);
-    request(st1);
-    if constexpr (NS > 3) request(st2);
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) request(stage_at(i));
     meet(0);                                    // block kb_lo has landed
     const int n_blocks = nkb - kb_lo;
     int done = 0;
-    if constexpr (NS == 3) {
-        for (; done + 3 <= n_blocks; done += 3) {       // whole rounds over the stages; a single loop exit keeps one accumulator set
-            GACER_STEP(st0, st2);
-            GACER_STEP(st1, st0);
-            GACER_STEP(st2, st1);
-        }
-        const int rest = n_blocks - done;
-        if (rest >= 1) GACER_STEP(st0, st2);
-        if (rest >= 2) GACER_STEP(st1, st0);
-    } else {
-        for (; done + 4 <= n_blocks; done += 4) {
-            GACER_STEP(st0, st3);
-            GACER_STEP(st1, st0);
-            GACER_STEP(st2, st1);
-            GACER_STEP(st3, st2);
-        }
-        const int rest = n_blocks - done;
-        if (rest >= 1) GACER_STEP(st0, st3);
-        if (rest >= 2) GACER_STEP(st1, st0);
-        if (rest >= 3) GACER_STEP(st2, st1);
+    for (; done + NS <= n_blocks; done += NS) { // whole rounds over the stages; a single loop exit keeps one accumulator set
+#pragma unroll
+        for (int i = 0; i < NS; ++i) step(stage_at(i), stage_at((i + NS - 1) % NS));
     }
-#undef GACER_STEP
+    const int rest = n_blocks - done;
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+        if (rest > i) step(stage_at(i), stage_at((i + NS - 1) % NS));
+    mfmas(1);                                   // last group of the last block
     meet(1);                                    // trailing requests (all beyond K: zeros) have landed; the epilogue reuses the stages
 
     float *patch;
@@ -773,7 +804,7 @@ void igemm_dma_kernel(GemmArgs a)
         patch = (float *)(own_patch + wave * PATCH);
     } else {
         const int which = wave % NS;
-        unsigned char *base = which == 0 ? st0 : which == 1 ? st1 : which == 2 ? st2 : st3;
+        unsigned char *base = stage_at(which);
         patch = (float *)(base + (wave / NS) * PATCH);
     }
     igemm_epilogue<DT, BM, BN, WM, WN>(a, acc, patch, m0, n0, wm, wn, lane, slice, y_off);
@@ -1209,7 +1240,7 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
             return go_dma<DT, 128, 128, 2, 2, 4, 4>(a, s, dry, vec_ok, phase);
         }
         if (shape == 1) return go_dma<DT, 128, 64, 2, 2, 8, 3>(a, s, dry, vec_ok, phase);
-        if (long_k) return go_dma<DT, 64, 64, 2, 2, 8, 4>(a, s, dry, vec_ok, phase);
+        if (long_k && DT == DT_BF16) return go_dma<DT, 64, 64, 2, 2, 8, 4>(a, s, dry, vec_ok, phase);   // measured: a fourth stage pays for bf16 only
         return go_dma<DT, 64, 64, 2, 2, 8, 3>(a, s, dry, vec_ok, phase);
     }
     if (a.b_trans || a.K <= 16 * VEC || !vec_ok) {   // short K, or the latency-bound gather loader (more waves per unit): 64-byte blocks

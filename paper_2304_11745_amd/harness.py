@@ -177,6 +177,10 @@ class Session:
         """One host thread per tenant enqueues that tenant's stream (Section 2.1 deployment model)."""
         B.check(self.ctx, B.gacer_set_issue_threads(self.ctx, 1 if enable else 0))
 
+    def set_sync_every_launch(self, enable=True):
+        """Checking mode: every kernel is waited for and checked before the next is issued."""
+        B.check(self.ctx, B.gacer_set_sync_every_launch(self.ctx, 1 if enable else 0))
+
     def release_graphs(self):
         B.check(self.ctx, B.gacer_release_graphs(self.ctx))
 

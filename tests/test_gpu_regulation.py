@@ -215,3 +215,35 @@ def test_sibling_stream_decomposition(gpu):
     starts = {op: min(c["start_ms"] for c in ch.values()) for op, ch in by_op.items()}
     assert all(starts[op + 1] >= ends[op] - 1e-6 for op in by_op if op + 1 in by_op)
     sess.close()
+
+
+def test_sync_every_launch_gives_the_same_bits(gpu):
+    """The checking mode (every kernel waited for and checked before the next is issued) serialises all launches in
+    issue order.  A plan whose sync pointers, fork/join events and workspace parts order everything that needs ordering
+    gives the same bits either way; a captured graph is bypassed while the mode is on."""
+    from paper_2304_11745_amd import binding as B
+    tenants, data = synth.build_config(2, "small")
+    sess = gpu.Session(tenants, data)
+    n_ops = [len(t.ops) for t in tenants]
+    batch = tenants[0].batch
+    splits = [(0, i, "batch", [batch - batch // 2, batch // 2], True) for i in range(0, n_ops[0], 2)] + sess.uniform_splits("cout", 2, tenants=[1])
+    sess.set_plan(splits, sess.edges_from_pointers([[n // 3, 2 * n // 3] for n in n_ops]))
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_PLAN, 2)
+    base = [sess.output_bytes(i) for i in range(len(tenants))]
+    sess.capture(B.GACER_MODE_PLAN)
+    for threads in (False, True):
+        sess.set_issue_threads(threads)
+        sess.set_sync_every_launch(True)
+        for mode in (B.GACER_MODE_PLAN, B.GACER_MODE_STREAM_PARALLEL, B.GACER_MODE_SEQUENTIAL):
+            sess.poison_outputs()
+            sess.run(mode, 2)
+            assert [sess.output_bytes(i) for i in range(len(tenants))] == base, f"mode {mode}, threads={threads}: checking mode changed the bits"
+        sess.poison_outputs()
+        sess.run_static(B.GACER_MODE_PLAN, 1)
+        assert [sess.output_bytes(i) for i in range(len(tenants))] == base
+        sess.set_sync_every_launch(False)
+        sess.poison_outputs()
+        sess.run(B.GACER_MODE_PLAN, 2)
+        assert [sess.output_bytes(i) for i in range(len(tenants))] == base
+    sess.close()
