@@ -24,11 +24,15 @@ PEAK = {"f32": 157.3e12, "bf16": 2.5e15}        # dense MFMA FLOP/s, MI355X
 HBM_PEAK = 8.0e12
 
 
-# HBM traffic of the dominant kernel per launch, from two rocprofv3 counter passes (FETCH_SIZE, WRITE_SIZE, KiB per
-# dispatch, scaled by what the same counters read for a plain copy of known size).  Valid only for the kernel
-# sources the counters were taken with: the digest below covers them, any change resets `traffic` to null.
+# HBM-side traffic of the dominant kernel per launch, from two rocprofv3 counter passes (FETCH_SIZE, WRITE_SIZE, KiB per
+# dispatch, scaled by what the same counters read for a plain copy of known size).  Valid only for the kernel sources the
+# counters were taken with (the digest below covers them: any change resets `traffic` to null) and for the plan they were
+# taken on: per-launch bytes change when the chosen plan decomposes operators of this kernel, so `traffic` is reported only
+# when the kernel's launches per round equal the profiled count; the profiled figure itself is always given beside it.
 TRAFFIC = {
-    2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": None, "write_bytes": None, "sources_sha256": ""},
+    2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": 13.22e6, "write_bytes": 6.22e6, "plan": "unsplit",
+        "launches_per_round": 16, "algorithmic_bytes": 10.62e6,
+        "sources_sha256": "1f249aadbaf9cbbaf5a4bf7da47e2906d622aaf9540f1a374d0daff8963c0404"},
 }
 TRAFFIC_SOURCES = ["igemm.hip", "stream_ops.hip", "device_util.h", "kernels.h"]
 
@@ -42,11 +46,16 @@ def sources_digest():
     return h.hexdigest()
 
 
-def measured_traffic(config, kernel):
+def measured_traffic(config, kernel, launches_per_round):
+    """(traffic, profiled): bytes per launch for the roofline object (None unless kernel, sources and launch count match
+    what the counters were taken on) and the profiled record itself (None unless kernel and sources match)."""
     t = TRAFFIC.get(config)
     if not t or t["kernel"] != kernel or t["fetch_bytes"] is None or t["sources_sha256"] != sources_digest():
-        return None
-    return t["fetch_bytes"] + t["write_bytes"]
+        return None, None
+    profiled = {"bytes_per_launch": t["fetch_bytes"] + t["write_bytes"], "fetch_bytes": t["fetch_bytes"],
+                "write_bytes": t["write_bytes"], "algorithmic_bytes_per_launch": t["algorithmic_bytes"],
+                "plan": t["plan"], "launches_per_round": t["launches_per_round"]}
+    return (profiled["bytes_per_launch"] if launches_per_round == t["launches_per_round"] else None), profiled
 
 
 def log(*a):
@@ -165,14 +174,18 @@ def dominant_roofline(trace, dtype, config):
     dom = max(per_kernel, key=lambda n: per_kernel[n]["ms"])
     d = per_kernel[dom]
     avg_ms = d["ms"] / d["launches"]
+    traffic, profiled = measured_traffic(config, dom, d["launches"])
     if d["flops"] > 0:
         achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
-                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": measured_traffic(config, dom)}
+                "frac": achieved / (PEAK[dtype] / 1e12), "traffic": traffic}
     else:
         achieved = d["bytes"] / d["launches"] / (avg_ms * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK / 1e9, "unit": "GB/s",
-                "frac": achieved / (HBM_PEAK / 1e9), "traffic": measured_traffic(config, dom)}
+                "frac": achieved / (HBM_PEAK / 1e9), "traffic": traffic}
+    if profiled:
+        roof["traffic_profiled"] = profiled
+    roof["algorithmic_bytes_per_launch"] = d["bytes"] / d["launches"]
     roof.update({"kernel": dom, "launches_per_round": d["launches"], "avg_launch_us": avg_ms * 1e3,
                  "share_of_kernel_time": d["ms"] / sum(k["ms"] for k in per_kernel.values()),
                  "duration_basis": "kernel begin/end stamped by the runtime on the launch (what a profiler's kernel trace reports), "

@@ -897,7 +897,10 @@ gacer_status ensure_plan_events(Ctx *c)
 
 gacer_status ensure_events(Ctx *c, int rounds)
 {
-    while ((int)c->t_start.size() < rounds) {
+    // the per-round timing events are made in blocks of 128 rounds, so that a caller who warms up with a few rounds
+    // and then times many does not pay for event creation inside the timed call
+    const int want = (rounds + 127) / 128 * 128;
+    while ((int)c->t_start.size() < want) {
         hipEvent_t a, b;
         HIPCHK(c, hipEventCreate(&a));
         c->t_start.push_back(a);
