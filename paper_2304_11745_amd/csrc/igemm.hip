@@ -236,6 +236,22 @@ __device__ __forceinline__ int xcd_contiguous(int b, int n)
     return __builtin_amdgcn_readfirstlane(x * q + min(x, r) + (b >> 3));
 }
 
+// n / d with the pair the launcher prepared for d (set_divisors): one multiply-high and a shift instead of the two dozen
+// instructions of a division by a run-time value; exact for 0 <= n < 2^31.
+__device__ __forceinline__ int div_by(int n, const unsigned (&d)[2])
+{
+    return d[0] ? (int)(__umulhi((unsigned)n, d[0]) >> d[1]) : n;
+}
+
+// One validity bit per tap (bit r * kw + q) of a window whose origin is (ih0, iw0): rows and columns are tested once each.
+__device__ __forceinline__ unsigned tap_mask(int ih0, int iw0, int H, int W, int kh, int kw)
+{
+    unsigned cols = 0, tm = 0;
+    for (int q = 0; q < kw; ++q) cols |= (unsigned)(iw0 + q >= 0 && iw0 + q < W) << q;
+    for (int r = 0; r < kh; ++r) tm |= (ih0 + r >= 0 && ih0 + r < H) ? cols << (r * kw) : 0u;
+    return tm;
+}
+
 template <int DT, int BM, int BN, int WM, int WN, int KV, int LOAD>
 __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 {
@@ -286,8 +302,8 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         const int m = m0 + row;
         const bool ok = (row < BM) && (m < a.m_hi);
         const int mm = ok ? m : a.m_lo;
-        const int img = mm / HoWo, rem = mm - img * HoWo;
-        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        const int img = div_by(mm, a.div_howo), rem = mm - img * HoWo;
+        const int oh = div_by(rem, a.div_wo), ow = rem - oh * a.Wo;
         const int ih0 = oh * a.stride - a.pad, iw0 = ow * a.stride - a.pad;
         const int64_t e0 = (int64_t)img * a.x_img + ((int64_t)ih0 * a.W + iw0) * a.x_pix;   // may be negative at the border
         a_off[i] = ok ? (unsigned)(int)(e0 * ESZ) : OOB;
@@ -296,12 +312,8 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         for (int q = 0; q < a.kw; ++q) wmk |= (unsigned)(iw0 + q >= 0 && iw0 + q < a.W) << q;
         a_hm[i] = ok ? hm : 0u;
         a_wm[i] = wmk;
-        if constexpr (TAPS) {                   // one validity bit per tap (kh*kw <= 31 on this path): bit r*kw + q
-            unsigned tm = 0;
-            for (int r = 0; r < a.kh; ++r)
-                for (int q = 0; q < a.kw; ++q) tm |= ((hm >> r) & (wmk >> q) & 1u) << (r * a.kw + q);
-            a_hm[i] = ok ? tm : 0u;
-        }
+        if constexpr (TAPS)                     // one validity bit per tap (kh*kw <= 31 on this path): bit r*kw + q
+            a_hm[i] = ok ? tap_mask(ih0, iw0, a.H, a.W, a.kh, a.kw) : 0u;
     }
     // ---- per-thread B rows: byte offset of the weight row, and whether the row exists ----
     unsigned b_off[BV];
@@ -326,9 +338,9 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     int kv = kb_lo * BK + vcol * VEC;
     int kr = 0, ksx = 0, kci = kv;
     if constexpr (TAPS) {
-        const int tap = kv / a.Cin;
+        const int tap = div_by(kv, a.div_cin);
         kci = kv - tap * a.Cin;
-        kr = tap / a.kw;
+        kr = div_by(tap, a.div_kw);
         ksx = tap - kr * a.kw;
     }
 
@@ -425,9 +437,9 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                 ksx = w2 ? 0 : ksx;
                 kr += w2 ? 1 : 0;
             } else {
-                const int tap = kv / a.Cin;
+                const int tap = div_by(kv, a.div_cin);
                 kci = kv - tap * a.Cin;
-                kr = tap / a.kw;
+                kr = div_by(tap, a.div_kw);
                 ksx = tap - kr * a.kw;
             }
         }
@@ -612,16 +624,12 @@ void igemm_dma_kernel(GemmArgs a)
         const int m = m0 + vrow + i * RPP;
         const bool ok = m < a.m_hi;
         const int mm = ok ? m : a.m_lo;
-        const int img = mm / HoWo, rem = mm - img * HoWo;
-        const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+        const int img = div_by(mm, a.div_howo), rem = mm - img * HoWo;
+        const int oh = div_by(rem, a.div_wo), ow = rem - oh * a.Wo;
         const int ih0 = oh * a.stride - a.pad, iw0 = ow * a.stride - a.pad;
         const int64_t e0 = (int64_t)img * a.x_img + ((int64_t)ih0 * a.W + iw0) * a.x_pix;   // may be negative at the border
         a_off[i] = ok ? (unsigned)(int)(e0 * ESZ) : OOB;
-        unsigned tm = 0;
-        for (int r = 0; r < a.kh; ++r)
-            for (int q = 0; q < a.kw; ++q)
-                tm |= (unsigned)(ih0 + r >= 0 && ih0 + r < a.H && iw0 + q >= 0 && iw0 + q < a.W) << (r * a.kw + q);
-        a_hm[i] = ok ? tm : 0u;
+        a_hm[i] = ok ? tap_mask(ih0, iw0, a.H, a.W, a.kh, a.kw) : 0u;
     }
     unsigned b_off[BV];
 #pragma unroll
@@ -641,9 +649,9 @@ void igemm_dma_kernel(GemmArgs a)
     int kv = kb_lo * BK + lcol * VEC;
     int kr = 0, ksx = 0, kci = kv;
     if constexpr (TAPS) {
-        const int tap = kv / a.Cin;
+        const int tap = div_by(kv, a.div_cin);
         kci = kv - tap * a.Cin;
-        kr = tap / a.kw;
+        kr = div_by(tap, a.div_kw);
         ksx = tap - kr * a.kw;
     }
 
@@ -688,9 +696,9 @@ void igemm_dma_kernel(GemmArgs a)
                 ksx = w2 ? 0 : ksx;
                 kr += w2 ? 1 : 0;
             } else {
-                const int tap = kv / a.Cin;
+                const int tap = div_by(kv, a.div_cin);
                 kci = kv - tap * a.Cin;
-                kr = tap / a.kw;
+                kr = div_by(tap, a.div_kw);
                 ksx = tap - kr * a.kw;
             }
         }
@@ -862,8 +870,8 @@ __global__ __launch_bounds__(THREADS) void rowgemm_kernel(GemmArgs a)
             e0 = (int64_t)mm * a.x_pix;
         } else {
             const int HoWo = a.Ho * a.Wo;
-            const int img = mm / HoWo, rem = mm - img * HoWo;
-            const int oh = rem / a.Wo, ow = rem - oh * a.Wo;
+            const int img = div_by(mm, a.div_howo), rem = mm - img * HoWo;
+            const int oh = div_by(rem, a.div_wo), ow = rem - oh * a.Wo;
             e0 = (int64_t)img * a.x_img + ((int64_t)oh * a.stride * a.W + ow * a.stride) * a.x_pix;
         }
         a_off = ok ? (unsigned)(e0 * ESZ) : OOB;
@@ -1037,6 +1045,26 @@ static void launch_finish(const GemmArgs &a, hipStream_t s)
         GACER_LAUNCH((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
 }
 
+// (mul, shift) with n / d == (n * mul) >> (32 + shift) for every 0 <= n < 2^31: mul = ceil(2^(31 + c) / d), c = ceil(log2 d),
+// shift = c - 1; the error term n * (mul * d - 2^(31+c)) stays below 2^(31+c) because n < 2^31 <= 2^(31+c) / d.  d = 1 is
+// marked by mul = 0 (the quotient is n itself).
+static void divisor(int d, unsigned (&out)[2])
+{
+    if (d <= 1) { out[0] = 0u; out[1] = 0u; return; }
+    int c = 0;
+    while ((1ll << c) < d) ++c;
+    const unsigned long long two_k = 1ull << (31 + c);
+    out[0] = (unsigned)((two_k + (unsigned long long)d - 1) / (unsigned long long)d);
+    out[1] = (unsigned)(c - 1);
+}
+static void set_divisors(GemmArgs &b)
+{
+    divisor(b.Ho * b.Wo, b.div_howo);
+    divisor(b.Wo, b.div_wo);
+    divisor(b.Cin, b.div_cin);
+    divisor(b.kw, b.div_kw);
+}
+
 // Tile numbering of a launch.  m-major numbering gives every XCD a band of output rows: A is fetched into one L2 only,
 // B into every L2 that holds a band; n-major numbering is the mirror image.  Takes the order that moves fewer bytes
 // into the L2s (late convolution layers have far more weights than activations, early ones the opposite).
@@ -1081,6 +1109,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     }
     GemmArgs b = a;
     b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
+    set_divisors(b);
     if (a.b_trans)
         GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, b);
     else if (!vec_ok)
@@ -1124,6 +1153,7 @@ static LaunchInfo go_dma(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok
     }
     GemmArgs b = a;
     b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
+    set_divisors(b);
     if (taps) GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, true>), grid, block, 0, s, b);
     else GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, false>), grid, block, 0, s, b);
     if (ks > 1 && phase == 0) launch_finish<T>(a, s);
@@ -1148,7 +1178,9 @@ static int rows_lds(int tn, int K, int esz)
 template <int DT, int TN, int G>
 static LaunchInfo go_rows_g(const GemmArgs &a, hipStream_t s, const LaunchInfo &li, int groups)
 {
-    GACER_LAUNCH((rowgemm_kernel<DT, TN, G>), dim3((a.m_hi - a.m_lo + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, a);
+    GemmArgs b = a;
+    set_divisors(b);
+    GACER_LAUNCH((rowgemm_kernel<DT, TN, G>), dim3((a.m_hi - a.m_lo + 127) / 128, groups), dim3(THREADS), li.lds_bytes, s, b);
     return li;
 }
 

@@ -47,6 +47,8 @@ struct GemmArgs {
     int ksplit, kb_per_slice;
     float *ws;
     int n_major;               // set by the launcher: tiles are numbered n-major (1) or m-major (0), see tile_order()
+    // set by the launcher: n / d for 0 <= n < 2^31 as (n * mul) >> (32 + shift), mul = 0 meaning d = 1; d = Ho*Wo, Wo, Cin, kw
+    unsigned div_howo[2], div_wo[2], div_cin[2], div_kw[2];
 };
 
 // Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).
