@@ -275,15 +275,14 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
     const int tile = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
-    const int tiles_m = (int)gridDim.x / tiles_n;
-    const int tile_m = __builtin_amdgcn_readfirstlane(a.n_major ? tile % tiles_m : tile / tiles_n);
-    const int tile_n = __builtin_amdgcn_readfirstlane(a.n_major ? tile / tiles_m : tile % tiles_n);
+    const int by_m = div_by(tile, a.div_tiles_m), by_n = div_by(tile, a.div_tiles_n);
+    const int tile_m = __builtin_amdgcn_readfirstlane(a.n_major ? tile - by_m * a.tiles_m : by_n);
+    const int tile_n = __builtin_amdgcn_readfirstlane(a.n_major ? by_m : tile - by_n * a.tiles_n);
     const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
 
     const int z = blockIdx.z;
-    const int zq = __builtin_amdgcn_readfirstlane(z / a.zh);
+    const int zq = __builtin_amdgcn_readfirstlane(div_by(z, a.div_zh));
     const int zb = a.z_lo + zq, zh = z - zq * a.zh;
     const int64_t x_zoff = zb * a.x_zb + zh * a.x_zh, w_zoff = zb * a.w_zb + zh * a.w_zh;
     const __amdgpu_buffer_rsrc_t xr = make_rsrc((const T *)a.x + x_zoff, a.x_bytes - x_zoff * ESZ);
@@ -598,15 +597,14 @@ void igemm_dma_kernel(GemmArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int tiles_n = (a.n_hi - a.n_lo + BN - 1) / BN;
     const int tile = xcd_contiguous((int)blockIdx.x, (int)gridDim.x);
-    const int tiles_m = (int)gridDim.x / tiles_n;
-    const int tile_m = __builtin_amdgcn_readfirstlane(a.n_major ? tile % tiles_m : tile / tiles_n);
-    const int tile_n = __builtin_amdgcn_readfirstlane(a.n_major ? tile / tiles_m : tile % tiles_n);
+    const int by_m = div_by(tile, a.div_tiles_m), by_n = div_by(tile, a.div_tiles_n);
+    const int tile_m = __builtin_amdgcn_readfirstlane(a.n_major ? tile - by_m * a.tiles_m : by_n);
+    const int tile_n = __builtin_amdgcn_readfirstlane(a.n_major ? by_m : tile - by_n * a.tiles_n);
     const int m0 = a.m_lo + tile_m * BM, n0 = a.n_lo + tile_n * BN;
 
     const int z = blockIdx.z;
-    const int zq = __builtin_amdgcn_readfirstlane(z / a.zh);
+    const int zq = __builtin_amdgcn_readfirstlane(div_by(z, a.div_zh));
     const int zb = a.z_lo + zq, zh = z - zq * a.zh;
     const int64_t x_zoff = zb * a.x_zb + zh * a.x_zh, w_zoff = zb * a.w_zb + zh * a.w_zh;
     const __amdgpu_buffer_rsrc_t xr = make_rsrc((const T *)a.x + x_zoff, a.x_bytes - x_zoff * ESZ);
@@ -1057,6 +1055,14 @@ static void divisor(int d, unsigned (&out)[2])
     out[0] = (unsigned)((two_k + (unsigned long long)d - 1) / (unsigned long long)d);
     out[1] = (unsigned)(c - 1);
 }
+static void set_tiling(GemmArgs &b, int tiles_m, int tiles_n)
+{
+    b.tiles_m = tiles_m;
+    b.tiles_n = tiles_n;
+    divisor(tiles_m, b.div_tiles_m);
+    divisor(tiles_n, b.div_tiles_n);
+    divisor(b.zh, b.div_zh);
+}
 static void set_divisors(GemmArgs &b)
 {
     divisor(b.Ho * b.Wo, b.div_howo);
@@ -1110,6 +1116,7 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     GemmArgs b = a;
     b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
     set_divisors(b);
+    set_tiling(b, tiles_m, tiles_n);
     if (a.b_trans)
         GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, b);
     else if (!vec_ok)
@@ -1154,6 +1161,7 @@ static LaunchInfo go_dma(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok
     GemmArgs b = a;
     b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
     set_divisors(b);
+    set_tiling(b, tiles_m, tiles_n);
     if (taps) GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, true>), grid, block, 0, s, b);
     else GACER_LAUNCH((igemm_dma_kernel<DT, BM, BN, WM, WN, KV, NS, false>), grid, block, 0, s, b);
     if (ks > 1 && phase == 0) launch_finish<T>(a, s);

@@ -49,6 +49,9 @@ struct GemmArgs {
     int n_major;               // set by the launcher: tiles are numbered n-major (1) or m-major (0), see tile_order()
     // set by the launcher: n / d for 0 <= n < 2^31 as (n * mul) >> (32 + shift), mul = 0 meaning d = 1; d = Ho*Wo, Wo, Cin, kw
     unsigned div_howo[2], div_wo[2], div_cin[2], div_kw[2];
+    // set by the launcher of the tiled kernels: tiles along m and n of this launch, divisors for them and for zh
+    int tiles_m, tiles_n;
+    unsigned div_tiles_m[2], div_tiles_n[2], div_zh[2];
 };
 
 // Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).
