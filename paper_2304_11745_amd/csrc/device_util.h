@@ -16,6 +16,24 @@
 
 namespace gacer {
 
+// Division of an index by a run-time extent d that the launcher knows: the launcher prepares (mul, shift) with
+// n / d == (n * mul) >> (32 + shift) for every 0 <= n < 2^31 -- mul = ceil(2^(31 + c) / d), c = ceil(log2 d), shift = c - 1;
+// the error term n * (mul * d - 2^(31+c)) stays below 2^(31+c) because n < 2^31 <= 2^(31+c) / d -- and the kernel spends
+// one multiply-high and a shift instead of the dozens of instructions of a division.  d = 1 is marked by mul = 0.
+inline void divisor(int d, unsigned (&out)[2])
+{
+    if (d <= 1) { out[0] = 0u; out[1] = 0u; return; }
+    int c = 0;
+    while ((1ll << c) < d) ++c;
+    const unsigned long long two_k = 1ull << (31 + c);
+    out[0] = (unsigned)((two_k + (unsigned long long)d - 1) / (unsigned long long)d);
+    out[1] = (unsigned)(c - 1);
+}
+__device__ __forceinline__ int div_by(int n, const unsigned (&d)[2])
+{
+    return d[0] ? (int)(__umulhi((unsigned)n, d[0]) >> d[1]) : n;
+}
+
 __device__ __forceinline__ float ld_f32(const float *p, int64_t i) { return p[i]; }
 __device__ __forceinline__ float ld_f32(const unsigned short *p, int64_t i) { return __uint_as_float(((unsigned)p[i]) << 16); }
 

@@ -236,13 +236,6 @@ __device__ __forceinline__ int xcd_contiguous(int b, int n)
     return __builtin_amdgcn_readfirstlane(x * q + min(x, r) + (b >> 3));
 }
 
-// n / d with the pair the launcher prepared for d (set_divisors): one multiply-high and a shift instead of the two dozen
-// instructions of a division by a run-time value; exact for 0 <= n < 2^31.
-__device__ __forceinline__ int div_by(int n, const unsigned (&d)[2])
-{
-    return d[0] ? (int)(__umulhi((unsigned)n, d[0]) >> d[1]) : n;
-}
-
 // One validity bit per tap (bit r * kw + q) of a window whose origin is (ih0, iw0): rows and columns are tested once each.
 __device__ __forceinline__ unsigned tap_mask(int ih0, int iw0, int H, int W, int kh, int kw)
 {
@@ -1043,18 +1036,6 @@ static void launch_finish(const GemmArgs &a, hipStream_t s)
         GACER_LAUNCH((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
 }
 
-// (mul, shift) with n / d == (n * mul) >> (32 + shift) for every 0 <= n < 2^31: mul = ceil(2^(31 + c) / d), c = ceil(log2 d),
-// shift = c - 1; the error term n * (mul * d - 2^(31+c)) stays below 2^(31+c) because n < 2^31 <= 2^(31+c) / d.  d = 1 is
-// marked by mul = 0 (the quotient is n itself).
-static void divisor(int d, unsigned (&out)[2])
-{
-    if (d <= 1) { out[0] = 0u; out[1] = 0u; return; }
-    int c = 0;
-    while ((1ll << c) < d) ++c;
-    const unsigned long long two_k = 1ull << (31 + c);
-    out[0] = (unsigned)((two_k + (unsigned long long)d - 1) / (unsigned long long)d);
-    out[1] = (unsigned)(c - 1);
-}
 static void set_tiling(GemmArgs &b, int tiles_m, int tiles_n)
 {
     b.tiles_m = tiles_m;

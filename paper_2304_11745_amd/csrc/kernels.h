@@ -66,6 +66,9 @@ struct StreamArgs {
     float eps;
     int n_lo, n_hi, c_lo, c_hi;
     int64_t rows_per_item;     // row operators: rows (positions) per batch item
+    // set by the launcher (see GemmArgs): divisors for the channel vectors per position, the positions (or position
+    // tiles) per output row, and the output rows per image of this launch
+    unsigned div_cv[2], div_w[2], div_h[2];
 };
 
 // Per-kernel timing (measurement aid): while `launch_timer` points at an event pair on the calling thread, every

@@ -24,12 +24,10 @@ __global__ __launch_bounds__(TPB) void dwconv_kernel(StreamArgs a)
     const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * CV;
     const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (idx >= total) return;
-    const int cv = (int)(idx % CV);
-    int64_t p = idx / CV;
-    const int ow = (int)(p % a.Wo);
-    p /= a.Wo;
-    const int oh = (int)(p % a.Ho);
-    const int n = a.n_lo + (int)(p / a.Ho);
+    const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
+    const int p1 = div_by(p0, a.div_w), ow = p0 - p1 * a.Wo;
+    const int p2 = div_by(p1, a.div_h), oh = p1 - p2 * a.Ho;
+    const int n = a.n_lo + p2;
     const int c = a.c_lo + cv * V;
     const T *x = (const T *)a.x;
     const T *w = (const T *)a.w;
@@ -120,12 +118,10 @@ __global__ __launch_bounds__(TPB, 4) void dwconv3_kernel(StreamArgs a)
     const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * WT * CV;
     const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (idx >= total) return;
-    const int cv = (int)(idx % CV);
-    int64_t p = idx / CV;
-    const int wt = (int)(p % WT);
-    p /= WT;
-    const int oh = (int)(p % a.Ho);
-    const int n = a.n_lo + (int)(p / a.Ho);
+    const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
+    const int p1 = div_by(p0, a.div_w), wt = p0 - p1 * WT;
+    const int p2 = div_by(p1, a.div_h), oh = p1 - p2 * a.Ho;
+    const int n = a.n_lo + p2;
     const int c = a.c_lo + cv * V;
     const int ow0 = wt * TW;
     const __amdgpu_buffer_rsrc_t xr = make_rsrc(a.x, (int64_t)a.N * a.H * a.W * a.C * ESZ);
@@ -198,12 +194,10 @@ __global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
     const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * CV;
     const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (idx >= total) return;
-    const int cv = (int)(idx % CV);
-    int64_t p = idx / CV;
-    const int ow = (int)(p % a.Wo);
-    p /= a.Wo;
-    const int oh = (int)(p % a.Ho);
-    const int n = a.n_lo + (int)(p / a.Ho);
+    const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
+    const int p1 = div_by(p0, a.div_w), ow = p0 - p1 * a.Wo;
+    const int p2 = div_by(p1, a.div_h), oh = p1 - p2 * a.Ho;
+    const int n = a.n_lo + p2;
     const int c = a.c_lo + cv * V;
     const T *x = (const T *)a.x;
     float m[V];
@@ -260,8 +254,8 @@ __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
     const int64_t total = (int64_t)(a.n_hi - a.n_lo) * P * CV;
     const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (idx >= total) return;
-    const int cv = (int)(idx % CV);
-    const int64_t pos = (int64_t)a.n_lo * P + idx / CV;
+    const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
+    const int64_t pos = (int64_t)a.n_lo * P + p0;
     const int c = a.c_lo + cv * V;
     const int64_t o = pos * a.C + c;
     const Vec<T, V> xv = ld_vec<T, V>((const T *)a.x, o);
@@ -455,6 +449,16 @@ static bool vec_ok(const StreamArgs &a)
            aligned16(a.x2) && aligned16(a.res) && aligned16(a.w);
 }
 
+// the launch's copy of the arguments with the divisors of its index decomposition: V channels per vector, TW positions per tile
+static StreamArgs with_divisors(const StreamArgs &a, int V, int TW)
+{
+    StreamArgs b = a;
+    divisor((a.c_hi - a.c_lo) / V, b.div_cv);
+    divisor((a.Wo + TW - 1) / TW, b.div_w);
+    divisor(a.Ho, b.div_h);
+    return b;
+}
+
 static LaunchInfo info(int64_t wgs, const char *kernel)
 {
     LaunchInfo li;
@@ -471,21 +475,21 @@ static LaunchInfo info(int64_t wgs, const char *kernel)
     if (a.dtype == DT_BF16) {                                                                              \
         if (vec_ok<unsigned short, 8>(a)) {                                                                \
             const int64_t g = (outs / 8 + TPB - 1) / TPB;                                                  \
-            if (!dry && g) GACER_LAUNCH((KERNEL<unsigned short, 8>), dim3((unsigned)g), dim3(TPB), 0, s, a); \
+            if (!dry && g) GACER_LAUNCH((KERNEL<unsigned short, 8>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 8, 1)); \
             return info(g, NAME);                                                                               \
         }                                                                                                  \
         const int64_t g = (outs + TPB - 1) / TPB;                                                          \
-        if (!dry && g) GACER_LAUNCH((KERNEL<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);     \
+        if (!dry && g) GACER_LAUNCH((KERNEL<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 1, 1));     \
         return info(g, NAME);                                                                                   \
     }                                                                                                      \
     if (vec_ok<float, 4>(a)) {                                                                             \
         const int64_t g = (outs / 4 + TPB - 1) / TPB;                                                      \
-        if (!dry && g) GACER_LAUNCH((KERNEL<float, 4>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
+        if (!dry && g) GACER_LAUNCH((KERNEL<float, 4>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 4, 1));      \
         return info(g, NAME);                                                                                   \
     }                                                                                                      \
     {                                                                                                      \
         const int64_t g = (outs + TPB - 1) / TPB;                                                          \
-        if (!dry && g) GACER_LAUNCH((KERNEL<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);      \
+        if (!dry && g) GACER_LAUNCH((KERNEL<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 1, 1));      \
         return info(g, NAME);                                                                                   \
     }
 
@@ -498,8 +502,8 @@ LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
             const int64_t tiles = tiles_for(a.stride == 1 ? DW_TW<4, 1>::value : DW_TW<4, 2>::value);
             const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 4) + TPB - 1) / TPB;
             if (!dry && g) {
-                if (a.stride == 1) GACER_LAUNCH((dwconv3_kernel<unsigned short, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-                else GACER_LAUNCH((dwconv3_kernel<unsigned short, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                if (a.stride == 1) GACER_LAUNCH((dwconv3_kernel<unsigned short, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 4, DW_TW<4, 1>::value));
+                else GACER_LAUNCH((dwconv3_kernel<unsigned short, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 4, DW_TW<4, 2>::value));
             }
             return info(g, "dwconv3x3");
         }
@@ -507,8 +511,8 @@ LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
             const int64_t tiles = tiles_for(a.stride == 1 ? DW_TW<4, 1>::value : DW_TW<4, 2>::value);
             const int64_t g = (tiles * ((a.c_hi - a.c_lo) / 4) + TPB - 1) / TPB;
             if (!dry && g) {
-                if (a.stride == 1) GACER_LAUNCH((dwconv3_kernel<float, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, a);
-                else GACER_LAUNCH((dwconv3_kernel<float, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, a);
+                if (a.stride == 1) GACER_LAUNCH((dwconv3_kernel<float, 4, 1>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 4, DW_TW<4, 1>::value));
+                else GACER_LAUNCH((dwconv3_kernel<float, 4, 2>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 4, DW_TW<4, 2>::value));
             }
             return info(g, "dwconv3x3");
         }
