@@ -980,7 +980,8 @@ __global__ __launch_bounds__(THREADS) void splitk_finish(GemmArgs a)
     const int64_t total = (int64_t)(a.m_hi - a.m_lo) * Nl;
     const int64_t idx = ((int64_t)blockIdx.x * THREADS + threadIdx.x) * FV;
     if (idx >= total) return;
-    const int m = a.m_lo + (int)(idx / Nl), n = a.n_lo + (int)(idx % Nl);
+    const int mr = div_by((int)idx, a.div_nl);          // idx < 2^31: the launched sub-range holds fewer elements
+    const int m = a.m_lo + mr, n = a.n_lo + ((int)idx - mr * Nl);
     const int64_t o = (int64_t)m * a.y_row + n;
     // bias and residual are requested together with the slices: one global round trip for the whole kernel
     float bv[FV], rv[FV];
@@ -1030,10 +1031,12 @@ static void launch_finish(const GemmArgs &a, hipStream_t s)
     const int Nl = a.n_hi - a.n_lo;
     const int64_t total = (int64_t)(a.m_hi - a.m_lo) * Nl;
     const bool v4 = Nl % 4 == 0 && a.n_lo % 4 == 0 && a.y_row % 4 == 0 && (((uintptr_t)a.ws) & 15) == 0 && (((uintptr_t)a.y) & 15) == 0;
+    GemmArgs b = a;
+    divisor(Nl, b.div_nl);
     if (v4)
-        GACER_LAUNCH((splitk_finish<T, 4>), dim3((unsigned)((total / 4 + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
+        GACER_LAUNCH((splitk_finish<T, 4>), dim3((unsigned)((total / 4 + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, b);
     else
-        GACER_LAUNCH((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, a);
+        GACER_LAUNCH((splitk_finish<T, 1>), dim3((unsigned)((total + THREADS - 1) / THREADS)), dim3(THREADS), 0, s, b);
 }
 
 static void set_tiling(GemmArgs &b, int tiles_m, int tiles_n)

@@ -52,6 +52,7 @@ struct GemmArgs {
     // set by the launcher of the tiled kernels: tiles along m and n of this launch, divisors for them and for zh
     int tiles_m, tiles_n;
     unsigned div_tiles_m[2], div_tiles_n[2], div_zh[2];
+    unsigned div_nl[2];        // set by the launcher of the finishing pass: divisor for n_hi - n_lo
 };
 
 // Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).
