@@ -101,6 +101,45 @@ def model_makespan(sess, B, rows, splits, P):
     return {"makespan_ms": round(mk.value, 4), "residue": round(R.value, 4)}
 
 
+def calibrated_table(sess, B, rows, measured_unsplit_ms):
+    """The lookup table with every W scaled by one factor, chosen so that the model's completion time of the unsplit plan
+    equals the measured one.  W from launch geometry says how full a launch makes the chip by its own limiter; how much
+    two launches really slow each other is a property of the chip that one measured round can supply."""
+    import ctypes as C
+    n = len(rows)
+    none_P = [[] for _ in sess.tenants]
+
+    def scaled(gamma):
+        out = (B.gacer_prof * n)()
+        C.memmove(out, rows, C.sizeof(B.gacer_prof) * n)
+        for r in out:
+            if r.tenant >= 0:
+                r.cu_share = min(1.0, max(r.cu_share * gamma, 1.0 / 2048))
+        return out
+
+    def makespan(gamma):
+        m = model_makespan(sess, B, scaled(gamma), [], none_P)
+        return m["makespan_ms"] if m else None
+
+    lo, hi = 1.0 / 64, 64.0
+    m_lo, m_hi = makespan(lo), makespan(hi)
+    if m_lo is None or m_hi is None:
+        return None, None
+    if measured_unsplit_ms <= m_lo:
+        gamma = lo
+    elif measured_unsplit_ms >= m_hi:
+        gamma = hi
+    else:
+        for _ in range(40):                     # bisection in log space; the model's makespan grows with gamma
+            mid = (lo * hi) ** 0.5
+            if makespan(mid) < measured_unsplit_ms:
+                lo = mid
+            else:
+                hi = mid
+        gamma = (lo * hi) ** 0.5
+    return scaled(gamma), gamma
+
+
 def choose_plan(sess, B, trial_rounds):
     """Candidates: the searched plan (Algorithm 1 + spatial regulation on the profiled table), plain stream-parallel, and
     uniform sweeps; each is measured for a few rounds next to what the model predicts for it; the fastest is refined
@@ -126,6 +165,18 @@ def choose_plan(sess, B, trial_rounds):
         ms = sess.run(B.GACER_MODE_PLAN, trial_rounds)
         results[name] = statistics.median(ms)
         model[name] = model_makespan(sess, B, rows, sp, Pm)
+    # the search again, on the table calibrated against the measured unsplit round
+    cal_rows, gamma = calibrated_table(sess, B, rows, results["unsplit"])
+    cal_info = None
+    if cal_rows is not None:
+        c_splits, c_syncs, c_P, c_R = sess.search(cal_rows, 100)
+        cands["searched-calibrated"] = (c_splits, c_syncs, c_P)
+        sess.set_plan(c_splits, c_syncs)
+        sess.run(B.GACER_MODE_PLAN, 3)
+        results["searched-calibrated"] = statistics.median(sess.run(B.GACER_MODE_PLAN, trial_rounds))
+        model["searched-calibrated"] = model_makespan(sess, B, cal_rows, c_splits, c_P)
+        cal_info = {"w_scale": round(gamma, 4), "pointers": c_P, "splits": len(c_splits), "model_residue": c_R,
+                    "model_unsplit": model_makespan(sess, B, cal_rows, [], none_P)}
     best = min(results, key=results.get)
     sp, sy, _ = cands[best]
     t0 = time.perf_counter()
@@ -141,7 +192,7 @@ def choose_plan(sess, B, trial_rounds):
             "searched_splits": len(splits), "model_residue": R,
             "trial_ms": {k: round(v, 4) for k, v in results.items()},
             "model_vs_measured": {k: {"model": model[k], "measured_ms": round(results[k], 4)} for k in cands},
-            "chosen": chosen, "chosen_kind": kind}
+            "calibrated_search": cal_info, "chosen": chosen, "chosen_kind": kind}
     sess.set_plan(sp, sy)
     return info
 
