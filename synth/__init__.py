@@ -7,7 +7,7 @@ It contains none of the method's arithmetic: no convolution, no scheduling,
 no plan handling.
 """
 from .rng import splitmix64_uniform, splitmix64_normal, bf16_round  # noqa: F401
-from .graphs import (Op, Tenant, toy_cnn, toy_mlp, resnet18, resnet50, vgg16,  # noqa: F401
-                     mobilenetv2, bert_base, small_cnn, small_mbv2, small_resnet, small_bert,
+from .graphs import (Op, Tenant, toy_cnn, toy_mlp, resnet18, resnet34, resnet50, resnet101, vgg16,  # noqa: F401
+                     alexnet, mobilenetv2, bert_base, small_cnn, small_alexnet, small_mbv2, small_resnet, small_bert,
                      materialise, gemm_macs, tenant_params)
 from .configs import build_config, CONFIG_NAMES  # noqa: F401

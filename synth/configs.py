@@ -1,4 +1,4 @@
-"""The five multi-tenant workloads and their seeded data.
+"""The multi-tenant workloads and their seeded data.
 
 Each configuration is a list of tenants that share one GPU.  Images are
 224x224x3 tensors drawn from U[-1,1), standing in for the ImageNet-sized
@@ -16,6 +16,8 @@ CONFIG_NAMES = {
     3: "resnet50(16)+vgg16(8)+mobilenetv2(32) bf16 224x224",
     4: "2x{resnet18,resnet50,mobilenetv2,vgg16}(1) bf16 224x224",
     5: "bert-base-s128(8)+resnet50(32)+vgg16(16)+mobilenetv2(64) bf16",
+    # a tenant mix of the evaluation itself (Section 5.2 and Table 2, "ALEX+V16+R18"; batch sizes are not stated there)
+    6: "alexnet(8)+vgg16(8)+resnet18(8) f32 224x224",
 }
 
 
@@ -35,6 +37,8 @@ def _tenants(config: int, scale: str):
         if config == 5:
             return [G.small_bert(dt, 3), G.small_resnet(dt, 4, bottleneck=True), G.small_cnn(dt, 2),
                     G.small_mbv2(dt, 6)]
+        if config == 6:
+            return [G.small_alexnet("f32", 3), G.small_cnn("f32", 2), G.small_resnet("f32", 3)]
     if config == 2:
         return [G.resnet18("f32", 8), G.mobilenetv2("f32", 8)]
     if config == 3:
@@ -45,6 +49,8 @@ def _tenants(config: int, scale: str):
     if config == 5:
         return [G.bert_base("bf16", 8, 128), G.resnet50("bf16", 32), G.vgg16("bf16", 16),
                 G.mobilenetv2("bf16", 64)]
+    if config == 6:
+        return [G.alexnet("f32", 8), G.vgg16("f32", 8), G.resnet18("f32", 8)]
     raise ValueError(f"unknown config {config}")
 
 

@@ -235,6 +235,42 @@ def resnet50(dtype="bf16", batch=16, hw=224):
     return _resnet("resnet50", dtype, batch, hw, [3, 4, 6, 3], [64, 128, 256, 512], True, 1000)
 
 
+def resnet34(dtype="f32", batch=8, hw=224):
+    return _resnet("resnet34", dtype, batch, hw, [3, 4, 6, 3], [64, 128, 256, 512], False, 1000)
+
+
+def resnet101(dtype="bf16", batch=8, hw=224):
+    return _resnet("resnet101", dtype, batch, hw, [3, 4, 23, 3], [64, 128, 256, 512], True, 1000)
+
+
+# ----------------------------------------------------------------------------
+# AlexNet (Krizhevsky et al. 2012, the single-tower form of Krizhevsky 2014):
+# 11x11 s4 p2, 5x5 p2, three 3x3 p1 convolutions with ReLU, 3x3 s2 max-pools
+# after the first, second and fifth, flatten in (c,h,w) order, FC-ReLU,
+# FC-ReLU, FC.  No normalisation layers.
+# ----------------------------------------------------------------------------
+def _alexnet(name, dtype, batch, hw, widths, fc, classes):
+    c1, c2, c3, c4, c5 = widths
+    b = _B(name, dtype, batch)
+    x = b.tensor(batch, 3, hw, hw)
+    y = b.conv(x, c1, 11, 4, 2, "relu")
+    y = b.maxpool(y, 3, 2, 0)
+    y = b.conv(y, c2, 5, 1, 2, "relu")
+    y = b.maxpool(y, 3, 2, 0)
+    y = b.conv(y, c3, 3, 1, 1, "relu")
+    y = b.conv(y, c4, 3, 1, 1, "relu")
+    y = b.conv(y, c5, 3, 1, 1, "relu")
+    y = b.maxpool(y, 3, 2, 0)
+    y = b.gemm(y, fc, "relu", flatten=True)
+    y = b.gemm(y, fc, "relu", flatten=True)
+    y = b.gemm(y, classes, flatten=True)
+    return b.done(x, y)
+
+
+def alexnet(dtype="f32", batch=8, hw=224):
+    return _alexnet("alexnet", dtype, batch, hw, (64, 192, 384, 256, 256), 4096, 1000)
+
+
 # ----------------------------------------------------------------------------
 # VGG-16 (Simonyan & Zisserman 2015, configuration D): 13 conv3x3 p1 + ReLU,
 # five 2x2 s2 max-pools, flatten in (c,h,w) order, FC-ReLU, FC-ReLU, FC.
@@ -323,6 +359,11 @@ def bert_base(dtype="bf16", batch=8, seq=128):
 def small_cnn(dtype="f32", batch=3, hw=20):
     """VGG-shaped: conv/pool/flatten-FC with channel counts that are not tile multiples."""
     return _vgg("small_vgg", dtype, batch, hw, [24, "M", 40, 40, "M"], 72, 10)
+
+
+def small_alexnet(dtype="f32", batch=3, hw=67):
+    """AlexNet-shaped: the 11x11 stride-4 and 5x5 windows, unpadded 3x3 stride-2 pools, odd channel counts."""
+    return _alexnet("small_alexnet", dtype, batch, hw, (12, 20, 28, 24, 24), 40, 10)
 
 
 def small_resnet(dtype="f32", batch=3, hw=40, bottleneck=False):

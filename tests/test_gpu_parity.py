@@ -94,7 +94,7 @@ def test_config1_toy_pair(gpu):
     _check_all_modes_and_plans(gpu, tenants, data, plans, check_intermediate=True)
 
 
-@pytest.mark.parametrize("config", [2, 3, 4, 5])
+@pytest.mark.parametrize("config", [c for c in sorted(synth.CONFIG_NAMES) if c > 1])
 def test_small_families(gpu, config):
     tenants, data = synth.build_config(config, "small")
     _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)

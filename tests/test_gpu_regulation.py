@@ -140,7 +140,7 @@ def test_profile_table(gpu):
     sess.close()
 
 
-@pytest.mark.parametrize("config", [2, 3, 4, 5])
+@pytest.mark.parametrize("config", [c for c in sorted(synth.CONFIG_NAMES) if c > 1])
 def test_searched_plan_end_to_end(gpu, config):
     """profile -> gacer_search -> gacer_set_plan -> run: bit-identical to the sequential unsplit run and within tolerance
     of the oracle; then the measured refinement (gacer_refine) on top, same checks."""

@@ -69,7 +69,7 @@ def test_state_and_argument_errors(ctx):
     B.gacer_destroy(None)
 
 
-@pytest.mark.parametrize("config", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("config", sorted(synth.CONFIG_NAMES))
 def test_all_configs_load_and_count_launches(ctx, config):
     tenants, _ = synth.build_config(config, "full", with_data=False)
     st, keep = load(ctx, tenants)

@@ -40,8 +40,8 @@ def test_bf16_round_ties_to_even():
 
 
 def test_published_model_totals(golden_dir):
-    build = {"resnet18": synth.resnet18, "resnet50": synth.resnet50, "vgg16": synth.vgg16,
-             "mobilenetv2": synth.mobilenetv2, "bert_base": synth.bert_base}
+    build = {"resnet18": synth.resnet18, "resnet34": synth.resnet34, "resnet50": synth.resnet50, "resnet101": synth.resnet101,
+             "vgg16": synth.vgg16, "alexnet": synth.alexnet, "mobilenetv2": synth.mobilenetv2, "bert_base": synth.bert_base}
     for line in open(os.path.join(golden_dir, "model_totals.txt")):
         if line.startswith("#"):
             continue
@@ -53,14 +53,15 @@ def test_published_model_totals(golden_dir):
 
 
 def test_final_feature_maps():
-    for f, c in [(synth.resnet18, 512), (synth.resnet50, 2048), (synth.vgg16, 512), (synth.mobilenetv2, 1280)]:
+    for f, c, hw in [(synth.resnet18, 512, 7), (synth.resnet34, 512, 7), (synth.resnet50, 2048, 7), (synth.resnet101, 2048, 7),
+                     (synth.vgg16, 512, 7), (synth.mobilenetv2, 1280, 7), (synth.alexnet, 256, 6)]:
         t = f("f32", 1)
         gap_or_fc = next(op for op in t.ops if op.kind in ("gavgpool", "gemm"))
-        assert t.tensors[gap_or_fc.in0] == (1, c, 7, 7)
+        assert t.tensors[gap_or_fc.in0] == (1, c, hw, hw)
 
 
 def test_graphs_are_topologically_ordered():
-    for cfg in range(1, 6):
+    for cfg in sorted(synth.CONFIG_NAMES):
         tenants, _ = synth.build_config(cfg, "full", with_data=False)
         for t in tenants:
             written = {t.input}
