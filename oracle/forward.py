@@ -18,7 +18,7 @@ import numpy as np
 
 from .build import build
 
-_ACT = {"none": 0, "relu": 1, "relu6": 2, "gelu": 3}
+_ACT = {"none": 0, "relu": 1, "relu6": 2, "gelu": 3, "hswish": 4, "hsigmoid": 5}
 _lib = None
 _fp = ctypes.POINTER(ctypes.c_float)
 
@@ -120,6 +120,34 @@ def affine_act(x, scale, shift, res, act, n_rng=None, c_rng=None, out=None):
     return y
 
 
+def scale(x, gate, act, n_rng=None, c_rng=None, out=None):
+    N, C, H, W = x.shape
+    y = np.zeros_like(x) if out is None else out
+    n_lo, n_hi = n_rng or (0, N)
+    c_lo, c_hi = c_rng or (0, C)
+    lib().orc_scale(_p(x), _p(gate), _p(y), N, C, H * W, _ACT[act], n_lo, n_hi, c_lo, c_hi)
+    return y
+
+
+def concat(a, b, n_rng=None, c_rng=None, out=None):
+    N, Ca, H, W = a.shape
+    Cb = b.shape[1]
+    y = np.zeros((N, Ca + Cb, H, W), np.float32) if out is None else out
+    n_lo, n_hi = n_rng or (0, N)
+    c_lo, c_hi = c_rng or (0, Ca + Cb)
+    lib().orc_concat(_p(a), _p(b), _p(y), N, Ca, Cb, H * W, n_lo, n_hi, c_lo, c_hi)
+    return y
+
+
+def avgpool(x, k, stride, n_rng=None, c_rng=None, out=None):
+    N, C, H, W = x.shape
+    y = np.zeros((N, C, (H - k) // stride + 1, (W - k) // stride + 1), np.float32) if out is None else out
+    n_lo, n_hi = n_rng or (0, N)
+    c_lo, c_hi = c_rng or (0, C)
+    lib().orc_avgpool(_p(x), _p(y), N, C, H, W, k, stride, n_lo, n_hi, c_lo, c_hi)
+    return y
+
+
 def add(a, b, act, n_rng=None, out=None):
     y = np.zeros_like(a) if out is None else out
     per = a[0].size
@@ -200,6 +228,12 @@ def _eval_op(t, op, T, P, y, n_rng, c_rng):
         gavgpool(x, n_rng, c_rng, y)
     elif k == "affine":
         affine_act(x, P[op.scale], P[op.shift], res, op.act, n_rng, c_rng, y)
+    elif k == "scale":
+        scale(x, T[op.in1], op.act, n_rng, c_rng, y)
+    elif k == "concat":
+        concat(x, T[op.in1], n_rng, c_rng, y)
+    elif k == "avgpool":
+        avgpool(x, op.kh, op.stride, n_rng, c_rng, y)
     elif k == "add":
         add(x, T[op.in1], op.act, n_rng, y)
     elif k == "act":

@@ -21,7 +21,14 @@
 #include <stddef.h>
 #include <stdint.h>
 
-enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3, ACT_HSWISH = 4, ACT_HSIGMOID = 5 };
+
+/* The piecewise-linear gate of MobileNetV3 (Howard et al. 2019, Section 5.2): ReLU6(v + 3) / 6. */
+static double hard_sigmoid(double v)
+{
+    const double t = v + 3.0;
+    return (t < 0.0 ? 0.0 : (t > 6.0 ? 6.0 : t)) / 6.0;
+}
 
 static double apply_act(double v, int act)
 {
@@ -29,6 +36,8 @@ static double apply_act(double v, int act)
     case ACT_RELU:  return v > 0.0 ? v : 0.0;
     case ACT_RELU6: return v < 0.0 ? 0.0 : (v > 6.0 ? 6.0 : v);
     case ACT_GELU:  return 0.5 * v * (1.0 + erf(v / sqrt(2.0)));   /* exact (erf) form */
+    case ACT_HSWISH:   return v * hard_sigmoid(v);
+    case ACT_HSIGMOID: return hard_sigmoid(v);
     default:        return v;
     }
 }
@@ -207,6 +216,49 @@ void orc_affine_act(const float *x, const float *scale, const float *shift, cons
                 if (res) v += (double)res[o];
                 y[o] = (float)apply_act(v, act);
             }
+}
+
+/* Channel gate (squeeze-and-excitation): y[n,c,i] = act(x[n,c,i] * g[n,c]) over a logical [N][C][HW] tensor. */
+void orc_scale(const float *x, const float *g, float *y, int N, int C, int HW, int act,
+               int n_lo, int n_hi, int c_lo, int c_hi)
+{
+    (void)N;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = n_lo; n < n_hi; ++n)
+        for (int c = c_lo; c < c_hi; ++c)
+            for (int i = 0; i < HW; ++i) {
+                const size_t o = ((size_t)n * C + c) * HW + i;
+                y[o] = (float)apply_act((double)x[o] * (double)g[(size_t)n * C + c], act);
+            }
+}
+
+/* Channel concatenation of a [N][Ca][HW] and a [N][Cb][HW] tensor: y[n,c] = c < Ca ? a[n,c] : b[n,c-Ca]. */
+void orc_concat(const float *a, const float *b, float *y, int N, int Ca, int Cb, int HW,
+                int n_lo, int n_hi, int c_lo, int c_hi)
+{
+    (void)N;
+    for (int n = n_lo; n < n_hi; ++n)
+        for (int c = c_lo; c < c_hi; ++c)
+            for (int i = 0; i < HW; ++i)
+                y[((size_t)n * (Ca + Cb) + c) * HW + i] = c < Ca ? a[((size_t)n * Ca + c) * HW + i] : b[((size_t)n * Cb + (c - Ca)) * HW + i];
+}
+
+/* Unpadded mean pooling: y[n,c,oh,ow] = (1/k^2) * sum_{r,s<k} x[n,c,oh*stride+r,ow*stride+s]. */
+void orc_avgpool(const float *x, float *y, int N, int C, int H, int W, int k, int stride,
+                 int n_lo, int n_hi, int c_lo, int c_hi)
+{
+    const int Ho = (H - k) / stride + 1, Wo = (W - k) / stride + 1;
+    (void)N;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = n_lo; n < n_hi; ++n)
+        for (int c = c_lo; c < c_hi; ++c)
+            for (int oh = 0; oh < Ho; ++oh)
+                for (int ow = 0; ow < Wo; ++ow) {
+                    double acc = 0.0;
+                    for (int r = 0; r < k; ++r)
+                        for (int s = 0; s < k; ++s) acc += (double)x[(((size_t)n * C + c) * H + oh * stride + r) * W + ow * stride + s];
+                    y[(((size_t)n * C + c) * Ho + oh) * Wo + ow] = (float)(acc / (double)(k * k));
+                }
 }
 
 /* y = act(a + b), elementwise over [lo, hi). */

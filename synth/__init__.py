@@ -8,6 +8,7 @@ no plan handling.
 """
 from .rng import splitmix64_uniform, splitmix64_normal, bf16_round  # noqa: F401
 from .graphs import (Op, Tenant, toy_cnn, toy_mlp, resnet18, resnet34, resnet50, resnet101, vgg16,  # noqa: F401
-                     alexnet, mobilenetv2, bert_base, small_cnn, small_alexnet, small_mbv2, small_resnet, small_bert,
+                     alexnet, mobilenetv2, mobilenetv3_large, densenet121, bert_base, small_cnn, small_alexnet,
+                     small_mbv2, small_mbv3, small_densenet, small_resnet, small_bert,
                      materialise, gemm_macs, tenant_params)
 from .configs import build_config, CONFIG_NAMES  # noqa: F401

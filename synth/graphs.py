@@ -18,8 +18,8 @@ import numpy as np
 from .rng import splitmix64_uniform, splitmix64_normal, bf16_round
 
 KINDS = ("conv", "dwconv", "gemm", "bgemm_qk", "bgemm_pv", "maxpool", "gavgpool",
-         "affine", "add", "layernorm", "softmax", "act")
-ACTS = ("none", "relu", "relu6", "gelu")
+         "affine", "add", "layernorm", "softmax", "act", "scale", "concat", "avgpool")
+ACTS = ("none", "relu", "relu6", "gelu", "hswish", "hsigmoid")
 BN_EPS = 1e-5
 LN_EPS = 1e-12
 
@@ -138,6 +138,38 @@ class _B:
         n, c, h, w = self.shape(a)
         y = self.tensor(n, c, h, w)
         self.t.ops.append(Op("add", a, y, in1=b, cin=c, cout=c, act=act))
+        return y
+
+    def bn_affine(self, x, act="none"):
+        """An unfoldable BatchNorm (one that follows a concatenation) as a per-channel affine: gamma 1, beta 0, mean 0, var 1."""
+        n, c, h, w = self.shape(x)
+        y = self.tensor(n, c, h, w)
+        sc = self.param((c,), "ones", fold=1.0 / math.sqrt(1.0 + BN_EPS))
+        sh = self.param((c,), "zeros")
+        self.t.ops.append(Op("affine", x, y, scale=sc, shift=sh, cin=c, cout=c, act=act))
+        return y
+
+    def scale(self, x, gate, act="none"):
+        """y[n,c,h,w] = act(x[n,c,h,w] * gate[n,c]): the channel gate of a squeeze-and-excitation block."""
+        n, c, h, w = self.shape(x)
+        assert self.shape(gate) == (n, c, 1, 1)
+        y = self.tensor(n, c, h, w)
+        self.t.ops.append(Op("scale", x, y, in1=gate, cin=c, cout=c, act=act))
+        return y
+
+    def concat(self, a, b):
+        """Channel concatenation: out[:, :ca] = a, out[:, ca:] = b."""
+        n, ca, h, w = self.shape(a)
+        nb, cb, hb, wb = self.shape(b)
+        assert (n, h, w) == (nb, hb, wb)
+        y = self.tensor(n, ca + cb, h, w)
+        self.t.ops.append(Op("concat", a, y, in1=b, cin=ca, cout=ca + cb))
+        return y
+
+    def avgpool(self, x, k, stride):
+        n, c, h, w = self.shape(x)
+        y = self.tensor(n, c, (h - k) // stride + 1, (w - k) // stride + 1)
+        self.t.ops.append(Op("avgpool", x, y, cin=c, cout=c, kh=k, kw=k, stride=stride, pad=0))
         return y
 
     def act(self, x, act):
@@ -327,6 +359,85 @@ def mobilenetv2(dtype="f32", batch=8, hw=224):
 
 
 # ----------------------------------------------------------------------------
+# MobileNetV3-Large (Howard et al. 2019, Table 1): inverted residuals with 3x3
+# or 5x5 depthwise windows, ReLU or hard-swish, and squeeze-and-excitation
+# gates (global mean -> FC-ReLU -> FC-hard-sigmoid -> channel scale) between
+# the depthwise and the projection convolution; the gate's inner width is a
+# quarter of the expanded width rounded to a multiple of 8.
+# ----------------------------------------------------------------------------
+def _round8(v, d=8):
+    r = max(d, int(v + d / 2) // d * d)
+    return r + d if r < 0.9 * v else r
+
+
+def _mbv3(name, dtype, batch, hw, stem, settings, last_conv, last_fc, classes):
+    b = _B(name, dtype, batch)
+    x = b.tensor(batch, 3, hw, hw)
+    y = b.conv(x, stem, 3, 2, 1, "hswish", bn=True)
+    for k, exp, c, se, nl, s in settings:
+        cin = b.shape(y)[1]
+        z = y
+        if exp != cin:
+            z = b.conv(z, exp, 1, 1, 0, nl, bn=True)
+        z = b.conv(z, exp, k, s, (k - 1) // 2, nl, bn=True, groups=exp)
+        if se:
+            g = b.gavgpool(z)
+            g = b.gemm(g, _round8(exp // 4), "relu", flatten=True)
+            g = b.gemm(g, exp, "hsigmoid", flatten=True)
+            z = b.scale(z, g)
+        res = y if (s == 1 and cin == c) else -1
+        y = b.conv(z, c, 1, 1, 0, "none", res=res, bn=True)
+    y = b.conv(y, last_conv, 1, 1, 0, "hswish", bn=True)
+    y = b.gavgpool(y)
+    y = b.gemm(y, last_fc, "hswish", flatten=True)
+    y = b.gemm(y, classes, flatten=True)
+    return b.done(x, y)
+
+
+def mobilenetv3_large(dtype="bf16", batch=8, hw=224):
+    R, H = "relu", "hswish"
+    settings = [(3, 16, 16, False, R, 1), (3, 64, 24, False, R, 2), (3, 72, 24, False, R, 1),
+                (5, 72, 40, True, R, 2), (5, 120, 40, True, R, 1), (5, 120, 40, True, R, 1),
+                (3, 240, 80, False, H, 2), (3, 200, 80, False, H, 1), (3, 184, 80, False, H, 1), (3, 184, 80, False, H, 1),
+                (3, 480, 112, True, H, 1), (3, 672, 112, True, H, 1),
+                (5, 672, 160, True, H, 2), (5, 960, 160, True, H, 1), (5, 960, 160, True, H, 1)]
+    return _mbv3("mobilenetv3_large", dtype, batch, hw, 16, settings, 960, 1280, 1000)
+
+
+# ----------------------------------------------------------------------------
+# DenseNet-121 (Huang et al. 2017), growth rate 32, bottleneck width 4, blocks
+# of 6/12/24/16 layers.  A dense layer is BN-ReLU-conv1x1-BN-ReLU-conv3x3 and
+# its output is concatenated to everything before it; a transition is
+# BN-ReLU-conv1x1 (half the channels) and a 2x2 mean pool.  BatchNorms that
+# follow a convolution are folded into it; the ones that follow a
+# concatenation cannot be and stay as per-channel affine operators.
+# ----------------------------------------------------------------------------
+def _densenet(name, dtype, batch, hw, growth, blocks, init, bn_size, classes):
+    b = _B(name, dtype, batch)
+    x = b.tensor(batch, 3, hw, hw)
+    y = b.conv(x, init, 7, 2, 3, "relu", bn=True)
+    y = b.maxpool(y, 3, 2, 1)
+    for bi, layers in enumerate(blocks):
+        for _ in range(layers):
+            z = b.bn_affine(y, "relu")
+            z = b.conv(z, bn_size * growth, 1, 1, 0, "relu", bn=True)
+            z = b.conv(z, growth, 3, 1, 1, "none")
+            y = b.concat(y, z)
+        if bi + 1 < len(blocks):
+            z = b.bn_affine(y, "relu")
+            z = b.conv(z, b.shape(y)[1] // 2, 1, 1, 0, "none")
+            y = b.avgpool(z, 2, 2)
+    y = b.bn_affine(y, "relu")
+    y = b.gavgpool(y)
+    y = b.gemm(y, classes, flatten=True)
+    return b.done(x, y)
+
+
+def densenet121(dtype="bf16", batch=8, hw=224):
+    return _densenet("densenet121", dtype, batch, hw, 32, [6, 12, 24, 16], 64, 4, 1000)
+
+
+# ----------------------------------------------------------------------------
 # BERT-base-shaped encoder (Devlin et al. 2019), post-LN blocks.  The input is
 # the already-embedded sequence; an embedding LayerNorm comes first.
 # ----------------------------------------------------------------------------
@@ -373,6 +484,17 @@ def small_resnet(dtype="f32", batch=3, hw=40, bottleneck=False):
 
 def small_mbv2(dtype="f32", batch=3, hw=36):
     return _mbv2("small_mbv2", dtype, batch, hw, 8, [(1, 8, 1, 1), (6, 16, 2, 2), (6, 24, 2, 1)], 64, 10)
+
+
+def small_mbv3(dtype="f32", batch=3, hw=36):
+    R, H = "relu", "hswish"
+    settings = [(3, 8, 8, False, R, 1), (3, 24, 12, False, R, 2), (5, 40, 12, True, R, 1), (3, 48, 20, True, H, 2),
+                (5, 64, 20, True, H, 1)]
+    return _mbv3("small_mbv3", dtype, batch, hw, 8, settings, 72, 96, 10)
+
+
+def small_densenet(dtype="f32", batch=3, hw=40):
+    return _densenet("small_densenet", dtype, batch, hw, 8, [2, 3], 12, 2, 10)
 
 
 def small_bert(dtype="f32", batch=3, seq=24):
@@ -432,9 +554,11 @@ def gemm_macs(t: Tenant) -> int:
 
 
 def tenant_params(t: Tenant) -> int:
-    """Number of conv / GEMM weights and biases."""
+    """Number of conv / GEMM weights and biases and of per-channel affine parameters."""
     total = 0
     for op in t.ops:
         if op.kind in ("conv", "dwconv", "gemm"):
             total += int(np.prod(t.params[op.w].shape)) + int(np.prod(t.params[op.bias].shape))
+        elif op.kind == "affine":
+            total += int(np.prod(t.params[op.scale].shape)) + int(np.prod(t.params[op.shift].shape))
     return total

@@ -180,6 +180,46 @@ def test_bf16_rounding_hand_table():
     assert np.array_equal(F.round_bf16(r), synth.bf16_round(r))
 
 
+def test_hard_swish_sigmoid_values():
+    """ReLU6(v + 3) / 6 and v times that: the break points, the linear part and both saturated ends by hand."""
+    x = np.array([[-4.0, -3.0, -1.5, 0.0, 1.0, 3.0, 5.0]], np.float32).reshape(1, 7, 1, 1)
+    assert np.allclose(F.act(x, "hsigmoid").ravel(), [0.0, 0.0, 0.25, 0.5, 4.0 / 6.0, 1.0, 1.0], rtol=0, atol=1e-7)
+    assert np.allclose(F.act(x, "hswish").ravel(), [0.0, 0.0, -0.375, 0.0, 4.0 / 6.0, 3.0, 5.0], rtol=0, atol=1e-7)
+
+
+def test_scale_concat_avgpool_hand():
+    x = np.arange(2 * 2 * 2 * 2, dtype=np.float32).reshape(2, 2, 2, 2)
+    g = np.array([[[[2.0]], [[-1.0]]], [[[0.5]], [[0.0]]]], np.float32)          # gate per (image, channel)
+    y = F.scale(x, g, "none")
+    assert np.array_equal(y[0, 0], 2 * x[0, 0]) and np.array_equal(y[0, 1], -x[0, 1])
+    assert np.array_equal(y[1, 0], 0.5 * x[1, 0]) and np.all(y[1, 1] == 0)
+    assert np.array_equal(F.scale(x, g, "relu")[0, 1], np.zeros((2, 2), np.float32))
+    b = -np.ones((2, 3, 2, 2), np.float32)
+    c = F.concat(x, b)
+    assert c.shape == (2, 5, 2, 2) and np.array_equal(c[:, :2], x) and np.all(c[:, 2:] == -1)
+    # a chunk of channels that straddles the seam writes exactly its own range
+    part = np.full((2, 5, 2, 2), 7.0, np.float32)
+    F.concat(x, b, None, (1, 3), part)
+    assert np.array_equal(part[:, 1], x[:, 1]) and np.all(part[:, 2] == -1) and np.all(part[:, [0, 3, 4]] == 7)
+    r = np.arange(16, dtype=np.float32).reshape(1, 1, 4, 4)
+    assert np.array_equal(F.avgpool(r, 2, 2), np.array([[[[2.5, 4.5], [10.5, 12.5]]]], np.float32))
+    assert np.array_equal(F.avgpool(r, 3, 1), np.array([[[[5.0, 6.0], [9.0, 10.0]]]], np.float32))
+
+
+def test_scale_concat_avgpool_hard_acts_vs_torch():
+    x, g, b = rnd((3, 6, 5, 7), 41, -4, 4), rnd((3, 6, 1, 1), 42), rnd((3, 4, 5, 7), 43)
+    tx, tg, tb = [torch.from_numpy(v).double() for v in (x, g, b)]
+    for act, f in (("none", lambda v: v), ("hswish", tF.hardswish), ("hsigmoid", tF.hardsigmoid)):
+        assert np.allclose(F.scale(x, g, act), f(tx * tg).numpy(), rtol=1e-6, atol=1e-7)
+        assert np.allclose(F.act(x, act), f(tx).numpy(), rtol=1e-6, atol=1e-7)
+    assert np.array_equal(F.concat(x, b), torch.cat([tx, tb], 1).float().numpy())
+    for k, s in ((2, 2), (3, 2), (3, 1)):
+        assert np.allclose(F.avgpool(x, k, s), tF.avg_pool2d(tx, k, s).numpy(), rtol=1e-6, atol=1e-7)
+    w, bias = rnd((5, 6, 1, 1), 44), rnd((5,), 45)
+    ref = tF.hardswish(tF.conv2d(tx, torch.from_numpy(w).double(), torch.from_numpy(bias).double())).numpy()
+    assert np.allclose(F.conv2d(x, w, bias, None, 1, 0, 1, "hswish"), ref, rtol=1e-6, atol=1e-6)
+
+
 # ---- library referee (torch CPU, fp64) --------------------------------------------------------
 @pytest.mark.parametrize("k,stride,pad,groups,cin,cout", [(3, 1, 1, 1, 5, 7), (3, 2, 1, 1, 4, 6), (7, 2, 3, 1, 3, 8),
                                                            (1, 2, 0, 1, 6, 4), (3, 2, 1, 6, 6, 6), (3, 1, 1, 2, 4, 6)])
@@ -231,7 +271,8 @@ def _torch_forward(t, x, params):
     """Independent walk of the same graph with torch CPU fp64 ops."""
     T = {t.input: torch.from_numpy(x).double()}
     P = [torch.from_numpy(p).double() for p in params]
-    actf = {"none": lambda v: v, "relu": torch.relu, "relu6": lambda v: torch.clamp(v, 0, 6), "gelu": tF.gelu}
+    actf = {"none": lambda v: v, "relu": torch.relu, "relu6": lambda v: torch.clamp(v, 0, 6), "gelu": tF.gelu,
+            "hswish": tF.hardswish, "hsigmoid": tF.hardsigmoid}
     for op in t.ops:
         a = T[op.in0]
         r = T[op.res] if op.res >= 0 else 0
@@ -249,6 +290,12 @@ def _torch_forward(t, x, params):
             y = actf[op.act](a + T[op.in1])
         elif op.kind == "act":
             y = actf[op.act](a)
+        elif op.kind == "scale":
+            y = actf[op.act](a * T[op.in1])
+        elif op.kind == "concat":
+            y = torch.cat([a, T[op.in1]], dim=1)
+        elif op.kind == "avgpool":
+            y = tF.avg_pool2d(a, op.kh, op.stride)
         elif op.kind == "maxpool":
             y = tF.max_pool2d(a, op.kh, op.stride, op.pad)
         elif op.kind == "gavgpool":
@@ -292,8 +339,8 @@ def eltwise_mix(dtype="f32", batch=3):
     return b.done(x, y)
 
 
-@pytest.mark.parametrize("maker", [synth.toy_cnn, synth.toy_mlp, synth.small_cnn, synth.small_resnet,
-                                   synth.small_mbv2, synth.small_bert, eltwise_mix])
+@pytest.mark.parametrize("maker", [synth.toy_cnn, synth.toy_mlp, synth.small_cnn, synth.small_alexnet, synth.small_resnet,
+                                   synth.small_mbv2, synth.small_mbv3, synth.small_densenet, synth.small_bert, eltwise_mix])
 def test_graph_walk_vs_torch_fp64(maker):
     t = maker("f32")
     x, p = synth.materialise(t, 5)
@@ -303,7 +350,8 @@ def test_graph_walk_vs_torch_fp64(maker):
     assert np.abs(y - ref).max() <= 2e-5 * np.abs(ref).max()
 
 
-@pytest.mark.parametrize("maker", [synth.small_cnn, synth.small_resnet, synth.small_mbv2, synth.small_bert, eltwise_mix])
+@pytest.mark.parametrize("maker", [synth.small_cnn, synth.small_resnet, synth.small_mbv2, synth.small_mbv3, synth.small_densenet,
+                                   synth.small_bert, eltwise_mix])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_oracle_split_invariance(maker, dtype):
     """Decomposition (Eq. 5) must not change the oracle's own result, bit for bit."""

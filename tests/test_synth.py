@@ -41,7 +41,8 @@ def test_bf16_round_ties_to_even():
 
 def test_published_model_totals(golden_dir):
     build = {"resnet18": synth.resnet18, "resnet34": synth.resnet34, "resnet50": synth.resnet50, "resnet101": synth.resnet101,
-             "vgg16": synth.vgg16, "alexnet": synth.alexnet, "mobilenetv2": synth.mobilenetv2, "bert_base": synth.bert_base}
+             "vgg16": synth.vgg16, "alexnet": synth.alexnet, "mobilenetv2": synth.mobilenetv2, "bert_base": synth.bert_base,
+             "mobilenetv3_large": synth.mobilenetv3_large, "densenet121": synth.densenet121}
     for line in open(os.path.join(golden_dir, "model_totals.txt")):
         if line.startswith("#"):
             continue
@@ -54,10 +55,11 @@ def test_published_model_totals(golden_dir):
 
 def test_final_feature_maps():
     for f, c, hw in [(synth.resnet18, 512, 7), (synth.resnet34, 512, 7), (synth.resnet50, 2048, 7), (synth.resnet101, 2048, 7),
-                     (synth.vgg16, 512, 7), (synth.mobilenetv2, 1280, 7), (synth.alexnet, 256, 6)]:
+                     (synth.vgg16, 512, 7), (synth.mobilenetv2, 1280, 7), (synth.alexnet, 256, 6),
+                     (synth.mobilenetv3_large, 960, 7), (synth.densenet121, 1024, 7)]:
         t = f("f32", 1)
-        gap_or_fc = next(op for op in t.ops if op.kind in ("gavgpool", "gemm"))
-        assert t.tensors[gap_or_fc.in0] == (1, c, hw, hw)
+        last_spatial = [op for op in t.ops if t.tensors[op.in0][2] > 1][-1]          # the pool (or flattening FC) in front of the classifier
+        assert last_spatial.kind in ("gavgpool", "gemm") and t.tensors[last_spatial.in0] == (1, c, hw, hw)
 
 
 def test_graphs_are_topologically_ordered():
