@@ -62,10 +62,16 @@ typedef enum {
     GACER_ADD = 8,        /* y = act(in0 + in1)                                              */
     GACER_LAYERNORM = 9,  /* over c, of (in0 + res); scale = gamma, shift = beta, alpha = eps */
     GACER_SOFTMAX = 10,   /* over c                                                          */
-    GACER_ACT = 11        /* y = act(x)                                                      */
+    GACER_ACT = 11,       /* y = act(x)                                                      */
+    GACER_SCALE = 12,     /* y[n,c,h,w] = act(in0[n,c,h,w] * in1[n,c]): squeeze-and-excitation gate */
+    GACER_CONCAT = 13,    /* y[:, :cin] = in0, y[:, cin:] = in1 (channel concatenation)      */
+    GACER_AVGPOOL = 14    /* unpadded window mean (kh = kw, stride)                          */
 } gacer_opkind;
 
-typedef enum { GACER_ACT_NONE = 0, GACER_ACT_RELU = 1, GACER_ACT_RELU6 = 2, GACER_ACT_GELU = 3 } gacer_act;
+/* HSWISH(v) = v * HSIGMOID(v), HSIGMOID(v) = min(max(v + 3, 0), 6) / 6 */
+typedef enum {
+    GACER_ACT_NONE = 0, GACER_ACT_RELU = 1, GACER_ACT_RELU6 = 2, GACER_ACT_GELU = 3, GACER_ACT_HSWISH = 4, GACER_ACT_HSIGMOID = 5
+} gacer_act;
 
 /* Decomposition axis of an operator (Eq. 5 decomposes along batch; the output-channel
  * axis is this library's second axis).  Chunk j of `factor` covers a contiguous sub-range;
@@ -89,6 +95,8 @@ typedef struct {
  *   BGEMM_PV: in0 = probabilities (n=B*groups, c=S, h=S, w=1), in1 = qkv tokens, cout = head
  *         size; out (n=B, c=D, h=S, w=1): out[b,i,hd*cout+d] = sum_j p[b*heads+hd,j,i] * v[b,j,hd,d].
  *   MAXPOOL: kh (=kw), stride, pad.   LAYERNORM: alpha = epsilon.
+ *   SCALE: in1 has shape (n, c, 1, 1) for in0 = (n, c, h, w).   CONCAT: cin = c(in0), cout = c(in0) + c(in1), same n, h, w.
+ *   AVGPOOL: kh (=kw), stride, pad must be 0; out h = (h-kh)/stride+1.
  */
 typedef struct {
     gacer_opkind kind;

@@ -16,8 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libgacer.so")
 GACER_OK, GACER_EINVAL, GACER_ESHAPE, GACER_EPLAN, GACER_ESTATE, GACER_ENOMEM, GACER_EHIP = range(7)
 GACER_F32, GACER_BF16 = 0, 1
 (GACER_CONV2D, GACER_DWCONV2D, GACER_GEMM, GACER_BGEMM_QK, GACER_BGEMM_PV, GACER_MAXPOOL, GACER_GAVGPOOL,
- GACER_AFFINE_ACT, GACER_ADD, GACER_LAYERNORM, GACER_SOFTMAX, GACER_ACT) = range(12)
-GACER_ACT_NONE, GACER_ACT_RELU, GACER_ACT_RELU6, GACER_ACT_GELU = range(4)
+ GACER_AFFINE_ACT, GACER_ADD, GACER_LAYERNORM, GACER_SOFTMAX, GACER_ACT, GACER_SCALE, GACER_CONCAT, GACER_AVGPOOL) = range(15)
+GACER_ACT_NONE, GACER_ACT_RELU, GACER_ACT_RELU6, GACER_ACT_GELU, GACER_ACT_HSWISH, GACER_ACT_HSIGMOID = range(6)
 GACER_AXIS_NONE, GACER_AXIS_BATCH, GACER_AXIS_COUT = range(3)
 GACER_MODE_PLAN, GACER_MODE_SEQUENTIAL, GACER_MODE_STREAM_PARALLEL = range(3)
 

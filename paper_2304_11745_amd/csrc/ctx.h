@@ -8,7 +8,7 @@
 
 namespace gacer {
 
-enum LaunchKind { LK_IGEMM, LK_DWCONV, LK_MAXPOOL, LK_GAVGPOOL, LK_ELTWISE, LK_LAYERNORM, LK_SOFTMAX };
+enum LaunchKind { LK_IGEMM, LK_DWCONV, LK_MAXPOOL, LK_GAVGPOOL, LK_ELTWISE, LK_LAYERNORM, LK_SOFTMAX, LK_CONCAT };
 
 struct Launch {
     LaunchKind kind;

@@ -44,11 +44,19 @@ __device__ __forceinline__ unsigned short to_bf16(float f)      // round to near
 __device__ __forceinline__ void st_f32(float *p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void st_f32(unsigned short *p, int64_t i, float v) { p[i] = to_bf16(v); }
 
+// hard-sigmoid min(max(v + 3, 0), 6) / 6, and hard-swish = v times that (act is ACT_HSIGMOID or ACT_HSWISH)
+__device__ __forceinline__ float hard_act(float v, int act)
+{
+    const float t = __builtin_amdgcn_fmed3f(__fadd_rn(v, 3.f), 0.f, 6.f);
+    return __fdiv_rn(act == ACT_HSWISH ? __fmul_rn(v, t) : t, 6.f);
+}
+
 __device__ __forceinline__ float activate(float v, int act)
 {
     if (act == ACT_RELU) return __builtin_fmaxf(v, 0.f);
     if (act == ACT_RELU6) return __builtin_amdgcn_fmed3f(v, 0.f, 6.f);
     if (act == ACT_GELU) return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
+    if (act == ACT_HSWISH || act == ACT_HSIGMOID) return hard_act(v, act);
     return v;
 }
 

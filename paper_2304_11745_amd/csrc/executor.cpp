@@ -85,7 +85,8 @@ bool axis_legal(gacer_opkind kind, gacer_axis axis)
     if (axis == GACER_AXIS_BATCH) return true;
     if (axis == GACER_AXIS_COUT)
         return kind == GACER_CONV2D || kind == GACER_DWCONV2D || kind == GACER_GEMM || kind == GACER_MAXPOOL ||
-               kind == GACER_GAVGPOOL || kind == GACER_AFFINE_ACT;
+               kind == GACER_GAVGPOOL || kind == GACER_AFFINE_ACT || kind == GACER_SCALE || kind == GACER_CONCAT ||
+               kind == GACER_AVGPOOL;
     return false;
 }
 
@@ -195,9 +196,13 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
         s.eps = op.alpha;
         s.n_lo = b_lo * q_out; s.n_hi = b_hi * q_out; s.c_lo = c_lo; s.c_hi = c_hi;
         s.rows_per_item = (int64_t)q_out * out.h * out.w;
+        s.gate = nullptr; s.c_split = 0; s.pool_avg = 0;
         switch (op.kind) {
         case GACER_DWCONV2D: l.kind = LK_DWCONV; break;
         case GACER_MAXPOOL: l.kind = LK_MAXPOOL; break;
+        case GACER_AVGPOOL: l.kind = LK_MAXPOOL; s.pool_avg = 1; break;
+        case GACER_SCALE: l.kind = LK_ELTWISE; s.gate = s.x2; s.x2 = nullptr; s.scale = s.shift = nullptr; break;
+        case GACER_CONCAT: l.kind = LK_CONCAT; s.c_split = (int)in.c; s.C = (int)out.c; break;
         case GACER_GAVGPOOL: l.kind = LK_GAVGPOOL; break;
         case GACER_LAYERNORM: l.kind = LK_LAYERNORM; s.n_lo = b_lo; s.n_hi = b_hi; break;
         case GACER_SOFTMAX: l.kind = LK_SOFTMAX; s.n_lo = b_lo; s.n_hi = b_hi; break;
@@ -223,6 +228,7 @@ LaunchInfo enqueue(const Launch &l, hipStream_t s, bool dry, int phase, float *w
         return launch_igemm(l.g, s, dry, phase);
     case LK_DWCONV: return launch_dwconv(l.s, s, dry);
     case LK_MAXPOOL: return launch_maxpool(l.s, s, dry);
+    case LK_CONCAT: return launch_concat(l.s, s, dry);
     case LK_GAVGPOOL: return launch_gavgpool(l.s, s, dry);
     case LK_LAYERNORM: return launch_layernorm(l.s, s, dry);
     case LK_SOFTMAX: return launch_softmax(l.s, s, dry);
@@ -271,8 +277,8 @@ static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, cons
         if (i < 0) return !required;
         return i < t.n_tensors && written[i] != 0;
     };
-    if ((int)op.kind < 0 || (int)op.kind > (int)GACER_ACT) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown kind", ti, oi);
-    if ((int)op.act < 0 || (int)op.act > (int)GACER_ACT_GELU) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown activation", ti, oi);
+    if ((int)op.kind < 0 || (int)op.kind > (int)GACER_AVGPOOL) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown kind", ti, oi);
+    if ((int)op.act < 0 || (int)op.act > (int)GACER_ACT_HSIGMOID) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown activation", ti, oi);
     if (!idx_ok(op.in0, true)) return bad("in0 missing or not written by an earlier operator");
     if (!idx_ok(op.in1, false) || !idx_ok(op.res, false)) return bad("in1/res not written by an earlier operator");
     if (op.out < 0 || op.out >= t.n_tensors) return bad("out index out of range");
@@ -322,9 +328,27 @@ static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, cons
         if (in.n != out.n || in.c != out.c || out.h != (in.h + 2 * op.pad - op.kh) / op.stride + 1 ||
             out.w != (in.w + 2 * op.pad - op.kh) / op.stride + 1) return bad("output extent mismatch");
         break;
+    case GACER_AVGPOOL:
+        if (op.kh < 1 || op.stride < 1 || op.pad != 0 || op.kh > in.h || op.kh > in.w) return bad("bad window (mean pooling is unpadded)");
+        if (in.n != out.n || in.c != out.c || out.h != (in.h - op.kh) / op.stride + 1 || out.w != (in.w - op.kh) / op.stride + 1)
+            return bad("output extent mismatch");
+        break;
     case GACER_GAVGPOOL:
         if (in.n != out.n || in.c != out.c || out.h != 1 || out.w != 1) return bad("out must be (n,c,1,1)");
         break;
+    case GACER_SCALE: {
+        if (!idx_ok(op.in1, true) || !same_shape(in, out)) return bad("scale needs in0 of the output shape and a gate in1");
+        const gacer_tensor &g = t.tensors[op.in1];
+        if (g.n != in.n || g.c != in.c || g.h != 1 || g.w != 1) return bad("gate must be (n,c,1,1)");
+        break;
+    }
+    case GACER_CONCAT: {
+        if (!idx_ok(op.in1, true)) return bad("concat needs two inputs");
+        const gacer_tensor &b = t.tensors[op.in1];
+        if (in.n != out.n || b.n != out.n || in.h != out.h || b.h != out.h || in.w != out.w || b.w != out.w || in.c + b.c != out.c ||
+            op.cin != in.c || op.cout != out.c) return bad("concat: out must be (n, c(in0)+c(in1), h, w) with cin = c(in0)");
+        break;
+    }
     case GACER_AFFINE_ACT:
         if (!op.scale || !op.shift) return fail(c, GACER_EINVAL, "tenant %d op %d: null scale/shift", ti, oi);
         if (!same_shape(in, out)) return bad("in/out shapes differ");
@@ -1232,7 +1256,8 @@ static void launch_work(const Launch &l, double *flops, double *bytes)
     if (l.kind == LK_LAYERNORM || l.kind == LK_SOFTMAX) in_pos = out_pos = 1;
     if (l.kind == LK_GAVGPOOL) out_pos = 1;
     double b = items * C * (in_pos + out_pos) * esz;
-    if (s.x2) b += items * C * in_pos * esz;
+    if (s.x2 && l.kind != LK_CONCAT) b += items * C * in_pos * esz;      // a concatenation reads C channels in total from its two inputs
+    if (s.gate) b += items * C * esz;
     if (s.res) b += items * C * out_pos * esz;
     if (l.kind == LK_DWCONV) b += C * s.k * s.k * esz;
     *bytes = b;

@@ -49,6 +49,7 @@ __device__ __forceinline__ float act_apply(float v, int act)
     if (act == ACT_RELU) return __builtin_fmaxf(v, 0.f);
     if (act == ACT_RELU6) return __builtin_amdgcn_fmed3f(v, 0.f, 6.f);
     if (act == ACT_GELU) return gelu_erf(v);
+    if (act == ACT_HSWISH || act == ACT_HSIGMOID) return hard_act(v, act);
     return v;
 }
 
@@ -83,6 +84,9 @@ template <int EV> __device__ __forceinline__ void act_vec(float *v, int act)
     } else if (act == ACT_GELU) {
 #pragma unroll
         for (int q = 0; q < EV; ++q) v[q] = gelu_erf(v[q]);
+    } else if (act == ACT_HSWISH || act == ACT_HSIGMOID) {
+#pragma unroll
+        for (int q = 0; q < EV; ++q) v[q] = hard_act(v[q], act);
     }
 }
 
@@ -142,6 +146,7 @@ __device__ __noinline__ void finish_one(float v, float alpha, const float *bias,
     if (act == ACT_RELU) t = __builtin_fmaxf(t, 0.f);
     else if (act == ACT_RELU6) t = __builtin_amdgcn_fmed3f(t, 0.f, 6.f);
     else if (act == ACT_GELU) t = gelu_erf_inl(t);
+    else if (act == ACT_HSWISH || act == ACT_HSIGMOID) t = hard_act(t, act);
     store_out<typename El<DT>::T>(yg, o, t);
 }
 template <int DT>

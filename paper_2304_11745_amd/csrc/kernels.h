@@ -9,7 +9,7 @@
 namespace gacer {
 
 enum { DT_F32 = 0, DT_BF16 = 1 };
-enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_RELU6 = 2, ACT_GELU = 3, ACT_HSWISH = 4, ACT_HSIGMOID = 5 };
 
 // Implicit-GEMM view of conv / GEMM / attention products:  Y[m][n] = sum_k A[m][k] * B[n][k].
 //   rows m  = output positions (image, oh, ow), cols n = output channels, k = (tap r, tap s, ci).
@@ -67,6 +67,9 @@ struct StreamArgs {
     float eps;
     int n_lo, n_hi, c_lo, c_hi;
     int64_t rows_per_item;     // row operators: rows (positions) per batch item
+    const void *gate;          // eltwise: per-(image, channel) factor [N][C] in the tensor dtype, or null
+    int c_split;               // concat: channels of x (the first input); the rest of C come from x2
+    int pool_avg;              // pooling: 0 = window maximum, 1 = unpadded window mean
     // set by the launcher (see GemmArgs): divisors for the channel vectors per position, the positions (or position
     // tiles) per output row, and the output rows per image of this launch
     unsigned div_cv[2], div_w[2], div_h[2];
@@ -87,7 +90,8 @@ LaunchInfo launch_igemm(const GemmArgs &a, hipStream_t s, bool dry, int phase = 
 LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_maxpool(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry);
-LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry);   // affine / add / act
+LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry);   // affine / add / act / channel gate
+LaunchInfo launch_concat(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_layernorm(const StreamArgs &a, hipStream_t s, bool dry);
 LaunchInfo launch_softmax(const StreamArgs &a, hipStream_t s, bool dry);
 // one wavefront that spins for `ticks` of the constant 100 MHz clock (stream placement probe)

@@ -186,7 +186,7 @@ __global__ __launch_bounds__(TPB, 4) void dwconv3_kernel(StreamArgs a)
     }
 }
 
-// ---- max pooling k x k ---------------------------------------------------------------------------
+// ---- pooling k x k: window maximum, or (pool_avg, unpadded) window mean added in row-major order --------
 template <typename T, int V>
 __global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
 {
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
     const T *x = (const T *)a.x;
     float m[V];
 #pragma unroll
-    for (int q = 0; q < V; ++q) m[q] = -INFINITY;
+    for (int q = 0; q < V; ++q) m[q] = a.pool_avg ? 0.f : -INFINITY;
     for (int r = 0; r < a.k; ++r) {
         const int ih = oh * a.stride - a.pad + r;
         if (ih < 0 || ih >= a.H) continue;
@@ -211,12 +211,12 @@ __global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
             if (iw < 0 || iw >= a.W) continue;
             const Vec<T, V> xv = ld_vec<T, V>(x, (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c);
 #pragma unroll
-            for (int q = 0; q < V; ++q) m[q] = fmaxf(m[q], xv.get(q));
+            for (int q = 0; q < V; ++q) m[q] = a.pool_avg ? __fadd_rn(m[q], xv.get(q)) : fmaxf(m[q], xv.get(q));
         }
     }
     Vec<T, V> yv;
 #pragma unroll
-    for (int q = 0; q < V; ++q) yv.set(q, m[q]);
+    for (int q = 0; q < V; ++q) yv.set(q, a.pool_avg ? __fdiv_rn(m[q], (float)(a.k * a.k)) : m[q]);
     st_vec<T, V>((T *)a.y, (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.C + c, yv);
 }
 
@@ -245,7 +245,7 @@ __global__ __launch_bounds__(TPB) void gavgpool_kernel(StreamArgs a)
     }
 }
 
-// ---- y = act(x*scale[c] + shift[c] + res)  |  y = act(x + x2)  |  y = act(x) -------------------------
+// ---- y = act(x*scale[c] + shift[c] + res)  |  y = act(x + x2)  |  y = act(x)  |  y = act(x * gate[n][c]) ------
 template <typename T, int V>
 __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
 {
@@ -259,18 +259,41 @@ __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
     const int c = a.c_lo + cv * V;
     const int64_t o = pos * a.C + c;
     const Vec<T, V> xv = ld_vec<T, V>((const T *)a.x, o);
-    Vec<T, V> bv, rv, yv;
+    Vec<T, V> bv, rv, gv, yv;
     if (a.x2) bv = ld_vec<T, V>((const T *)a.x2, o);
     if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
+    if (a.gate) {                               // image of this position: p0 / (H * W)
+        const int img = a.n_lo + div_by(div_by(p0, a.div_w), a.div_h);
+        gv = ld_vec<T, V>((const T *)a.gate, (int64_t)img * a.C + c);
+    }
 #pragma unroll
     for (int q = 0; q < V; ++q) {
         float v = xv.get(q);
+        if (a.gate) v = __fmul_rn(v, gv.get(q));
         if (a.scale) v = __fmaf_rn(v, a.scale[c + q], a.shift[c + q]);
         if (a.x2) v = __fadd_rn(v, bv.get(q));
         if (a.res) v = __fadd_rn(v, rv.get(q));
         yv.set(q, activate(v, a.act));
     }
     st_vec<T, V>((T *)a.y, o, yv);
+}
+
+// ---- channel concatenation: y[pos][c] = c < c_split ? x[pos][c] : x2[pos][c - c_split] ----------------------
+// A vector never straddles the seam: the launcher takes V > 1 only when c_split is a multiple of V.
+template <typename T, int V>
+__global__ __launch_bounds__(TPB) void concat_kernel(StreamArgs a)
+{
+    const int CV = (a.c_hi - a.c_lo) / V;
+    const int64_t P = (int64_t)a.H * a.W;
+    const int64_t total = (int64_t)(a.n_hi - a.n_lo) * P * CV;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= total) return;
+    const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
+    const int64_t pos = (int64_t)a.n_lo * P + p0;
+    const int c = a.c_lo + cv * V;
+    const Vec<T, V> v = c < a.c_split ? ld_vec<T, V>((const T *)a.x, pos * a.c_split + c)
+                                      : ld_vec<T, V>((const T *)a.x2, pos * (a.C - a.c_split) + (c - a.c_split));
+    st_vec<T, V>((T *)a.y, pos * a.C + c, v);
 }
 
 // ---- row operators: one wavefront per row (position), C features contiguous ---------------------------
@@ -446,7 +469,7 @@ template <typename T, int VFULL>
 static bool vec_ok(const StreamArgs &a)
 {
     return a.C % VFULL == 0 && a.c_lo % VFULL == 0 && (a.c_hi - a.c_lo) % VFULL == 0 && aligned16(a.x) && aligned16(a.y) &&
-           aligned16(a.x2) && aligned16(a.res) && aligned16(a.w);
+           aligned16(a.x2) && aligned16(a.res) && aligned16(a.w) && aligned16(a.gate);
 }
 
 // the launch's copy of the arguments with the divisors of its index decomposition: V channels per vector, TW positions per tile
@@ -531,6 +554,21 @@ LaunchInfo launch_eltwise(const StreamArgs &a, hipStream_t s, bool dry)
 {
     const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.H * a.W * (a.c_hi - a.c_lo);
     GACER_DISPATCH_VEC(eltwise_kernel, "eltwise")
+}
+
+LaunchInfo launch_concat(const StreamArgs &a, hipStream_t s, bool dry)
+{
+    const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.H * a.W * (a.c_hi - a.c_lo);
+    const int full = a.dtype == DT_BF16 ? 8 : 4;
+    if (a.c_split % full) {                      // the seam is not on a vector boundary: element by element
+        const int64_t g = (outs + TPB - 1) / TPB;
+        if (!dry && g) {
+            if (a.dtype == DT_BF16) GACER_LAUNCH((concat_kernel<unsigned short, 1>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 1, 1));
+            else GACER_LAUNCH((concat_kernel<float, 1>), dim3((unsigned)g), dim3(TPB), 0, s, with_divisors(a, 1, 1));
+        }
+        return info(g, "concat");
+    }
+    GACER_DISPATCH_VEC(concat_kernel, "concat")
 }
 
 LaunchInfo launch_gavgpool(const StreamArgs &a, hipStream_t s, bool dry)

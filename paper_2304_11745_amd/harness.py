@@ -13,10 +13,12 @@ from . import binding as B
 _KIND = {"conv": B.GACER_CONV2D, "dwconv": B.GACER_DWCONV2D, "gemm": B.GACER_GEMM, "bgemm_qk": B.GACER_BGEMM_QK,
          "bgemm_pv": B.GACER_BGEMM_PV, "maxpool": B.GACER_MAXPOOL, "gavgpool": B.GACER_GAVGPOOL,
          "affine": B.GACER_AFFINE_ACT, "add": B.GACER_ADD, "layernorm": B.GACER_LAYERNORM,
-         "softmax": B.GACER_SOFTMAX, "act": B.GACER_ACT}
-_ACT = {"none": B.GACER_ACT_NONE, "relu": B.GACER_ACT_RELU, "relu6": B.GACER_ACT_RELU6, "gelu": B.GACER_ACT_GELU}
+         "softmax": B.GACER_SOFTMAX, "act": B.GACER_ACT, "scale": B.GACER_SCALE, "concat": B.GACER_CONCAT,
+         "avgpool": B.GACER_AVGPOOL}
+_ACT = {"none": B.GACER_ACT_NONE, "relu": B.GACER_ACT_RELU, "relu6": B.GACER_ACT_RELU6, "gelu": B.GACER_ACT_GELU,
+        "hswish": B.GACER_ACT_HSWISH, "hsigmoid": B.GACER_ACT_HSIGMOID}
 AXIS = {"none": B.GACER_AXIS_NONE, "batch": B.GACER_AXIS_BATCH, "cout": B.GACER_AXIS_COUT}
-COUT_SPLITTABLE = ("conv", "dwconv", "gemm", "maxpool", "gavgpool", "affine")
+COUT_SPLITTABLE = ("conv", "dwconv", "gemm", "maxpool", "gavgpool", "affine", "scale", "concat", "avgpool")
 
 
 def _ptr(t):

@@ -18,6 +18,9 @@ CONFIG_NAMES = {
     5: "bert-base-s128(8)+resnet50(32)+vgg16(16)+mobilenetv2(64) bf16",
     # a tenant mix of the evaluation itself (Section 5.2 and Table 2, "ALEX+V16+R18"; batch sizes are not stated there)
     6: "alexnet(8)+vgg16(8)+resnet18(8) f32 224x224",
+    # "R50+V16+M3" and "R101+D121+M3" of the same table, the second one being the mix of more than 200 operators
+    7: "resnet50(16)+vgg16(8)+mobilenetv3-large(32) bf16 224x224",
+    8: "resnet101(8)+densenet121(8)+mobilenetv3-large(8) bf16 224x224",
 }
 
 
@@ -39,6 +42,10 @@ def _tenants(config: int, scale: str):
                     G.small_mbv2(dt, 6)]
         if config == 6:
             return [G.small_alexnet("f32", 3), G.small_cnn("f32", 2), G.small_resnet("f32", 3)]
+        if config == 7:
+            return [G.small_resnet(dt, 4, bottleneck=True), G.small_cnn(dt, 3), G.small_mbv3(dt, 5)]
+        if config == 8:
+            return [G.small_resnet(dt, 2, bottleneck=True), G.small_densenet(dt, 3), G.small_mbv3(dt, 2)]
     if config == 2:
         return [G.resnet18("f32", 8), G.mobilenetv2("f32", 8)]
     if config == 3:
@@ -51,6 +58,10 @@ def _tenants(config: int, scale: str):
                 G.mobilenetv2("bf16", 64)]
     if config == 6:
         return [G.alexnet("f32", 8), G.vgg16("f32", 8), G.resnet18("f32", 8)]
+    if config == 7:
+        return [G.resnet50("bf16", 16), G.vgg16("bf16", 8), G.mobilenetv3_large("bf16", 32)]
+    if config == 8:
+        return [G.resnet101("bf16", 8), G.densenet121("bf16", 8), G.mobilenetv3_large("bf16", 8)]
     raise ValueError(f"unknown config {config}")
 
 

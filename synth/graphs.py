@@ -99,7 +99,7 @@ class _B:
                              stride=stride, pad=pad, groups=groups, act=act))
         return y
 
-    def gemm(self, x, cout, act="none", res=-1, flatten=False):
+    def gemm(self, x, cout, act="none", res=-1, flatten=False, fold=1.0):
         n, c, h, w = self.shape(x)
         if flatten:
             cin = c * h * w
@@ -107,7 +107,7 @@ class _B:
         else:
             cin = c
             y = self.tensor(n, cout, h, w)
-        wi = self.param((cout, cin), "he_uniform", cin)
+        wi = self.param((cout, cin), "he_uniform", cin, fold)
         bi = self.param((cout,), "zeros")
         self.t.ops.append(Op("gemm", x, y, res=res, w=wi, bias=bi, cin=cin, cout=cout, act=act))
         return y
@@ -365,6 +365,12 @@ def mobilenetv2(dtype="f32", batch=8, hw=224):
 # the depthwise and the projection convolution; the gate's inner width is a
 # quarter of the expanded width rounded to a multiple of 8.
 # ----------------------------------------------------------------------------
+# The gate's second FC is drawn this much smaller than He-uniform: without trained weights and without normalisation the
+# activations grow to a few hundred, and a hard-sigmoid fed with values of that size is a switch (0 or 1, flipping on a
+# rounding error) instead of the smooth gate it is in a trained network; this keeps its input in the linear range.
+SE_GATE_FOLD = 1.0 / 32.0
+
+
 def _round8(v, d=8):
     r = max(d, int(v + d / 2) // d * d)
     return r + d if r < 0.9 * v else r
@@ -383,7 +389,7 @@ def _mbv3(name, dtype, batch, hw, stem, settings, last_conv, last_fc, classes):
         if se:
             g = b.gavgpool(z)
             g = b.gemm(g, _round8(exp // 4), "relu", flatten=True)
-            g = b.gemm(g, exp, "hsigmoid", flatten=True)
+            g = b.gemm(g, exp, "hsigmoid", flatten=True, fold=SE_GATE_FOLD)
             z = b.scale(z, g)
         res = y if (s == 1 and cin == c) else -1
         y = b.conv(z, c, 1, 1, 0, "none", res=res, bn=True)

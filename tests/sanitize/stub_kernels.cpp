@@ -14,6 +14,7 @@ LaunchInfo launch_dwconv(const StreamArgs &, hipStream_t, bool) { return geometr
 LaunchInfo launch_maxpool(const StreamArgs &, hipStream_t, bool) { return geometry("maxpool", 1); }
 LaunchInfo launch_gavgpool(const StreamArgs &, hipStream_t, bool) { return geometry("gavgpool", 1); }
 LaunchInfo launch_eltwise(const StreamArgs &, hipStream_t, bool) { return geometry("eltwise", 1); }
+LaunchInfo launch_concat(const StreamArgs &, hipStream_t, bool) { return geometry("concat", 1); }
 LaunchInfo launch_layernorm(const StreamArgs &, hipStream_t, bool) { return geometry("layernorm", 1); }
 LaunchInfo launch_softmax(const StreamArgs &, hipStream_t, bool) { return geometry("softmax", 1); }
 void launch_spin(hipStream_t, unsigned long long) {}

@@ -15,8 +15,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 KIND = {"conv": B.GACER_CONV2D, "dwconv": B.GACER_DWCONV2D, "gemm": B.GACER_GEMM, "bgemm_qk": B.GACER_BGEMM_QK,
         "bgemm_pv": B.GACER_BGEMM_PV, "maxpool": B.GACER_MAXPOOL, "gavgpool": B.GACER_GAVGPOOL,
         "affine": B.GACER_AFFINE_ACT, "add": B.GACER_ADD, "layernorm": B.GACER_LAYERNORM,
-        "softmax": B.GACER_SOFTMAX, "act": B.GACER_ACT}
-ACT = {"none": 0, "relu": 1, "relu6": 2, "gelu": 3}
+        "softmax": B.GACER_SOFTMAX, "act": B.GACER_ACT, "scale": B.GACER_SCALE, "concat": B.GACER_CONCAT,
+        "avgpool": B.GACER_AVGPOOL}
+ACT = {"none": 0, "relu": 1, "relu6": 2, "gelu": 3, "hswish": 4, "hsigmoid": 5}
 FAKE = 0x10000      # 16-byte aligned, never dereferenced: nothing is launched in these tests
 
 
@@ -103,6 +104,33 @@ def test_shape_validation(ctx):
     assert st == B.GACER_EINVAL
     st, _ = load(ctx, tenants)
     assert st == B.GACER_OK
+
+
+def test_shape_validation_of_gate_concat_and_mean_pool(ctx):
+    """Squeeze-and-excitation gate, channel concatenation, unpadded mean pooling: each shape rule rejects its violation."""
+    for maker, kind in ((synth.small_mbv3, "scale"), (synth.small_densenet, "concat"), (synth.small_densenet, "avgpool")):
+        tenants = [maker("f32", 2)]
+        k = next(i for i, op in enumerate(tenants[0].ops) if op.kind == kind)
+        st, _ = load(ctx, tenants)
+        assert st == B.GACER_OK, B.gacer_last_error(ctx)
+
+        def wrong_second_input(d):
+            d[0].ops[k].in1 = d[0].ops[k].in0     # a gate must be (n,c,1,1); a concatenation's channels must add up
+        def no_second_input(d):
+            d[0].ops[k].in1 = -1
+        def padded(d):
+            d[0].ops[k].pad = 1
+        def wrong_cin(d):
+            d[0].ops[k].cin += 1
+        for bad in {"scale": (wrong_second_input, no_second_input), "concat": (wrong_second_input, no_second_input, wrong_cin),
+                    "avgpool": (padded,)}[kind]:
+            st, _ = load(ctx, tenants, bad)
+            assert st == B.GACER_ESHAPE and b"tenant 0 op %d" % k in B.gacer_last_error(ctx), (kind, bad.__name__)
+
+    def unknown_act(d):
+        d[0].ops[0].act = 6
+    st, _ = load(ctx, [synth.small_mbv3("f32", 2)], unknown_act)
+    assert st == B.GACER_EINVAL
 
 
 def _plan(splits=(), syncs=()):
