@@ -122,6 +122,39 @@ def test_small_families_all_kinds(gpu, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_gate_concat_mean_pool_ragged(gpu, dtype):
+    """Channel gate, concatenation and mean pooling at extents that leave the vector paths: a seam that is not a multiple
+    of a 16-byte vector, odd channel counts, 3x3 stride-1 and stride-2 mean windows, hard-swish / hard-sigmoid after
+    convolutions, depthwise convolutions, FCs, a K-sliced product and standalone operators; every intermediate tensor
+    against the oracle, every decomposition bit-exact."""
+    from synth import graphs as G
+    tenants = []
+    for ti, (cin, c1, c2, hw) in enumerate([(5, 13, 6, 11), (8, 24, 16, 14), (3, 40, 7, 9)]):
+        b = G._B(f"ragged{ti}", dtype, 3)
+        x = b.tensor(3, cin, hw, hw)
+        a = b.conv(x, c1, 3, 1, 1, "hswish")
+        z = b.conv(a, c2, 1, 1, 0, "hsigmoid")
+        y = b.concat(a, z)                                   # seam at c1: 13 and 40 are no vector multiples in bf16, 13 in neither
+        g = b.gavgpool(y)
+        g = b.gemm(g, 10, "relu", flatten=True)
+        g = b.gemm(g, c1 + c2, "hsigmoid", flatten=True, fold=0.25)
+        y = b.scale(y, g, "none" if ti else "hswish")
+        y = b.conv(y, c1 + c2, 5, 1, 2, "hswish", groups=c1 + c2)
+        y = b.avgpool(y, 3, 1 + ti % 2)
+        y = b.concat(y, b.act(y, "hswish"))
+        y = b.avgpool(y, 2, 2)
+        y = b.gemm(y, 9, "hswish", flatten=True)
+        tenants.append(b.done(x, y))
+    b = G._B("long_k_hswish", dtype, 2)                      # few tiles and a long K: the K-sliced path and its finishing pass
+    x = b.tensor(2, 256, 6, 6)
+    y = b.conv(x, 72, 3, 1, 1, "hswish")
+    y = b.conv(y, 40, 3, 1, 1, "hsigmoid")
+    tenants.append(b.done(x, y))
+    data = [G.materialise(t, 99, i << 20) for i, t in enumerate(tenants)]
+    _check_all_modes_and_plans(gpu, tenants, data, _sweep_plans, check_intermediate=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_random_conv_shapes(gpu, dtype):
     """Seeded random convolution / depthwise / FC shapes (ragged M, N and K tails, odd channel counts, strides, paddings,
     residuals, every activation): parity with the oracle on every intermediate tensor, bit-exactness under uniform and
