@@ -32,7 +32,7 @@ HBM_PEAK = 8.0e12
 TRAFFIC = {
     2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": 13.21e6, "write_bytes": 6.22e6, "plan": "unsplit",
         "launches_per_round": 16, "algorithmic_bytes": 10.62e6,
-        "sources_sha256": "8062ff971198b1f8c78e39a92b66d3da1cd1132053e7e1326527a12378ec5019"},
+        "sources_sha256": "aa9df6adc67269e63d8e3d91261679c12564a98e3924ae8e1f17b55503e24ec2"},
 }
 TRAFFIC_SOURCES = ["igemm.hip", "stream_ops.hip", "device_util.h", "kernels.h"]
 

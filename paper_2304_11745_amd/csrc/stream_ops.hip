@@ -234,8 +234,18 @@ __global__ __launch_bounds__(TPB) void gavgpool_kernel(StreamArgs a)
     const int HW = a.H * a.W;
     const T *x = (const T *)a.x;
     float s = 0.f;
-    if (c < a.c_hi)
-        for (int p = q; p < HW; p += 4) s = __fadd_rn(s, ld_f32(x, ((int64_t)n * HW + p) * a.C + c));
+    if (c < a.c_hi) {
+        const T *xc = x + (int64_t)n * HW * a.C + c;
+        int p = q;
+        for (; p + 28 < HW; p += 32) {           // eight loads in flight, added in the order of the plain loop below
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = ld_f32(xc, (int64_t)(p + 4 * u) * a.C);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s = __fadd_rn(s, v[u]);
+        }
+        for (; p < HW; p += 4) s = __fadd_rn(s, ld_f32(xc, (int64_t)p * a.C));
+    }
     part[q][threadIdx.x & 63] = s;
     __syncthreads();
     if (q == 0 && c < a.c_hi) {
