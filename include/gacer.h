@@ -318,6 +318,21 @@ gacer_status gacer_set_issue_threads(gacer_ctx *ctx, int enable);
 gacer_status gacer_set_sync_every_launch(gacer_ctx *ctx, int enable);
 
 /*
+ * Launch fusion (on by default).  A tenant of very short kernels spends as much time between kernels as inside them -- the
+ * issuing overhead that the granularity discussion of Section 5.4 attributes to having more operators -- so where the plan
+ * allows, an AFFINE_ACT operator (no residual; activation none, ReLU or ReLU6) and the 1x1 stride-1 convolution that
+ * consumes it are issued as ONE kernel: the product applies the affine operator's arithmetic while it loads its A tile and
+ * also writes the affine operator's output tensor, which then exists as if its own kernel had run.  Outputs and every
+ * intermediate tensor keep the bits of the unfused kernels.  A pair is left alone when the plan decomposes either operator,
+ * when the affine operator's completion is the source of a sync edge, and when its tensors or parameter vectors are not
+ * 16-byte aligned or its channel count is not a multiple of a 16-byte vector.  In traces and launch counts the affine
+ * operator of a fused pair has no launch of its own; the fused kernel's name starts with "igemm_affine_".  enable = 0 issues
+ * every operator on its own (the lookup table of gacer_profile always describes the unfused operators).  Re-installs the
+ * current plan.
+ */
+gacer_status gacer_set_fuse_affine(gacer_ctx *ctx, int enable);
+
+/*
  * Stream placement aid.  The device runs the streams of a process on a small number of hardware queues, and kernels of
  * two streams that landed on the same queue never overlap: tenants on such streams run one after the other however
  * the plan orders them (Section 2.1's concurrent streams silently turn sequential).  This call finds out, by

@@ -24,7 +24,7 @@ GACER_MODE_PLAN, GACER_MODE_SEQUENTIAL, GACER_MODE_STREAM_PARALLEL = range(3)
 EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_plan", "gacer_plan_from_pointers",
            "gacer_run", "gacer_profile", "gacer_search", "gacer_model_residue", "gacer_plan_free",
            "gacer_last_error", "gacer_launch_count", "gacer_trace_run", "gacer_issue_stats", "gacer_capture",
-           "gacer_release_graphs", "gacer_set_issue_threads", "gacer_set_sync_every_launch", "gacer_probe_stream_queues", "gacer_place_streams",
+           "gacer_release_graphs", "gacer_set_issue_threads", "gacer_set_sync_every_launch", "gacer_set_fuse_affine", "gacer_probe_stream_queues", "gacer_place_streams",
            "gacer_refine", "gacer_run_static", "gacer_plan_to_text",
            "gacer_plan_from_text"]
 
@@ -102,6 +102,7 @@ def _load():
     lib.gacer_capture.argtypes = [ctx, C.c_int]
     lib.gacer_set_issue_threads.argtypes = [ctx, C.c_int]
     lib.gacer_set_sync_every_launch.argtypes = [ctx, C.c_int]
+    lib.gacer_set_fuse_affine.argtypes = [ctx, C.c_int]
     lib.gacer_release_graphs.argtypes = [ctx]
     lib.gacer_issue_stats.argtypes = [ctx, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.gacer_probe_stream_queues.argtypes = [C.POINTER(C.c_void_p), C.c_int, C.POINTER(C.c_int)]
@@ -134,6 +135,7 @@ gacer_issue_stats = lib.gacer_issue_stats
 gacer_capture = lib.gacer_capture
 gacer_set_issue_threads = lib.gacer_set_issue_threads
 gacer_set_sync_every_launch = lib.gacer_set_sync_every_launch
+gacer_set_fuse_affine = lib.gacer_set_fuse_affine
 gacer_release_graphs = lib.gacer_release_graphs
 gacer_probe_stream_queues = lib.gacer_probe_stream_queues
 gacer_place_streams = lib.gacer_place_streams

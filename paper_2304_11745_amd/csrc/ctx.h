@@ -70,6 +70,7 @@ struct Ctx {
     std::vector<hipEvent_t> t_start, t_end;         // per round, timing enabled
     hipGraphExec_t graph_exec[3] = {nullptr, nullptr, nullptr};   // captured round per mode (optional)
     bool issue_threads = false;                     // one host thread per tenant enqueues that tenant's stream
+    bool fuse_affine = true;                        // a per-channel affine operator + the 1x1 convolution that reads it run as one launch where allowed
     bool sync_every_launch = false;                 // checking mode: wait for, and check, every kernel before the next is issued
     bool capturing = false;                         // a stream capture is open: nothing may synchronise
     std::string launch_detail;                      // checking mode: which launch failed

@@ -44,11 +44,14 @@ __device__ __forceinline__ unsigned short to_bf16(float f)      // round to near
 __device__ __forceinline__ void st_f32(float *p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void st_f32(unsigned short *p, int64_t i, float v) { p[i] = to_bf16(v); }
 
-// hard-sigmoid min(max(v + 3, 0), 6) / 6, and hard-swish = v times that (act is ACT_HSIGMOID or ACT_HSWISH)
+// hard-sigmoid min(max(v + 3, 0), 6) / 6, and hard-swish = v times that (act is ACT_HSIGMOID or ACT_HSWISH).  The sixth is a
+// multiplication by the rounded constant: four instructions, small enough to sit in every unrolled epilogue (a correctly
+// rounded division is a dozen more per element, and kernels that never take this branch still pay for fetching around it).
 __device__ __forceinline__ float hard_act(float v, int act)
 {
-    const float t = __builtin_amdgcn_fmed3f(__fadd_rn(v, 3.f), 0.f, 6.f);
-    return __fdiv_rn(act == ACT_HSWISH ? __fmul_rn(v, t) : t, 6.f);
+    asm volatile("");                           // keeps the (launch-uniform) branch around this a branch: as selects, every element of every kernel would pay for it
+    const float s = __fmul_rn(__builtin_amdgcn_fmed3f(__fadd_rn(v, 3.f), 0.f, 6.f), 0.16666667163372039794921875f);
+    return act == ACT_HSWISH ? __fmul_rn(v, s) : s;
 }
 
 __device__ __forceinline__ float activate(float v, int act)
@@ -58,6 +61,22 @@ __device__ __forceinline__ float activate(float v, int act)
     if (act == ACT_GELU) return __fmul_rn(__fmul_rn(0.5f, v), __fadd_rn(1.f, erff(__fmul_rn(v, 0.70710678118654752440f))));
     if (act == ACT_HSWISH || act == ACT_HSIGMOID) return hard_act(v, act);
     return v;
+}
+
+// Activation of N values at once: `act` is uniform over the launch, so one branch is taken per group of values instead of
+// one per value (per value, the compiler threads every element through its own run of scalar branches).
+template <int N> __device__ __forceinline__ void activate_n(float *v, int act)
+{
+    if (act == ACT_RELU) {
+#pragma unroll
+        for (int q = 0; q < N; ++q) v[q] = __builtin_fmaxf(v[q], 0.f);
+    } else if (act == ACT_RELU6) {
+#pragma unroll
+        for (int q = 0; q < N; ++q) v[q] = __builtin_amdgcn_fmed3f(v[q], 0.f, 6.f);
+    } else if (act != ACT_NONE) {
+#pragma unroll
+        for (int q = 0; q < N; ++q) v[q] = activate(v[q], act);
+    }
 }
 
 // 16-byte vector of V elements of type T, unpacked to / packed from float.

@@ -434,6 +434,55 @@ static void plan_workspaces(Ctx *c, std::vector<Tenant> &ts)
     }
 }
 
+// ---- per-channel affine + the 1x1 convolution that reads it, as one launch --------------------------------------------------
+// A network whose BatchNorms follow concatenations (DenseNet) runs an affine + ReLU kernel over all features in front of
+// every bottleneck convolution; in a chain of kernels a few microseconds long that launch costs as much as the work.  Where
+// it can, the executor issues operator i (affine, no residual, activation none / ReLU / ReLU6) and operator i + 1 (1x1
+// convolution, stride 1, reading i's output) as one launch of the product, whose A loader applies the affine operator's
+// arithmetic on the way in and also writes operator i's output tensor; operator i then has no launch of its own.  Both give
+// the bits of the two stand-alone kernels.  Not fused: pairs of which either operator is decomposed by the plan, pairs whose
+// first operator's completion is a sync pointer's source, operands that are not 16-byte aligned or whose channel count is
+// not a multiple of a 16-byte vector.
+static bool aligned16p(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+static bool fusable_pair(const Tenant &T, int i)
+{
+    if (i + 1 >= (int)T.ops.size()) return false;
+    const gacer_op &af = T.ops[i], &pw = T.ops[i + 1];
+    if (af.kind != GACER_AFFINE_ACT || pw.kind != GACER_CONV2D) return false;
+    if (af.res >= 0 || (af.act != GACER_ACT_NONE && af.act != GACER_ACT_RELU && af.act != GACER_ACT_RELU6)) return false;
+    if (pw.kh != 1 || pw.kw != 1 || pw.stride != 1 || pw.pad != 0 || pw.groups != 1 || pw.in0 != af.out || pw.res == af.out) return false;
+    const gacer_tensor &in = T.tensors[af.in0], &mid = T.tensors[af.out];
+    const int vec = T.dtype == GACER_BF16 ? 8 : 4;
+    if (in.c % vec) return false;
+    return aligned16p(in.dptr) && aligned16p(mid.dptr) && aligned16p(af.scale) && aligned16p(af.shift) && aligned16p(pw.w);
+}
+
+// `pw` is the unsplit launch of operator i + 1; turns it into the fused launch of operators i and i + 1
+static void fuse_into(Launch &pw, const Tenant &T, int i)
+{
+    const gacer_op &af = T.ops[i];
+    GemmArgs &g = pw.g;
+    g.x = T.tensors[af.in0].dptr;               // same shape as the tensor the product read before: strides and bounds stay
+    g.pre_scale = af.scale; g.pre_shift = af.shift; g.pre_y = T.tensors[af.out].dptr; g.pre_act = (int)af.act;
+}
+
+template <typename Decomposed, typename Recorded>
+static void fuse_affine_pairs(Ctx *c, std::vector<std::vector<OpExec>> &ex, Decomposed decomposed, Recorded recorded)
+{
+    if (!c->fuse_affine) return;
+    for (size_t t = 0; t < c->tenants.size(); ++t) {
+        const Tenant &T = c->tenants[t];
+        for (int i = 0; i + 1 < (int)T.ops.size(); ++i) {
+            if (!fusable_pair(T, i) || decomposed((int)t, i) || decomposed((int)t, i + 1) || recorded((int)t, i)) continue;
+            if (ex[t][i].chunks.size() != 1 || ex[t][i + 1].chunks.size() != 1) continue;
+            fuse_into(ex[t][i + 1].chunks[0], T, i);
+            ex[t][i].chunks.clear();
+            ++i;                                 // the product is taken
+        }
+    }
+}
+
 static void expand_plain(Ctx *c)
 {
     c->plain_exec.assign(c->tenants.size(), {});
@@ -446,6 +495,7 @@ static void expand_plain(Ctx *c)
             c->plain_exec[t][i].chunks.push_back(make_launch(T, (int)i, 0, T.batch, 0, (int)T.tensors[T.ops[i].out].c));
         longest = std::max(longest, T.ops.size());
     }
+    fuse_affine_pairs(c, c->plain_exec, [](int, int) { return false; }, [](int, int) { return false; });
     for (size_t i = 0; i < longest; ++i)
         for (size_t t = 0; t < c->tenants.size(); ++t)
             if (i < c->tenants[t].ops.size()) c->par_order.push_back({(int)t, (int)i});
@@ -567,6 +617,9 @@ static gacer_status install_plan(Ctx *c, const std::vector<gacer_split> &splits,
         auto &w = ex[e.dst_tenant][e.dst_op].waits;
         if (std::find(w.begin(), w.end(), id) == w.end()) w.push_back(id);
     }
+    fuse_affine_pairs(c, ex,
+                      [&](int t, int i) { auto it = smap.find({t, i}); return it != smap.end() && it->second.factor > 1; },
+                      [&](int t, int i) { return ex[t][i].record >= 0; });
     for (Tenant &t : c->tenants) (void)hipStreamSynchronize(t.stream);
     drop_graphs(c);                      // captured rounds belong to the plan they were captured under
     c->splits = splits;
@@ -1178,6 +1231,21 @@ gacer_status gacer_set_issue_threads(gacer_ctx *c, int enable)
     return GACER_OK;
 }
 
+gacer_status gacer_set_fuse_affine(gacer_ctx *c, int enable)
+{
+    if (!c) return GACER_EINVAL;
+    c->fuse_affine = enable != 0;
+    if (!c->loaded) return GACER_OK;
+    expand_plain(c);
+    const std::vector<gacer_split> sp = c->splits;          // chunk lists stay alive in c->split_sizes while the plan is rebuilt
+    const std::vector<std::vector<int>> keep = c->split_sizes;
+    std::vector<gacer_split> again = sp;
+    for (size_t k = 0; k < again.size(); ++k)
+        if (again[k].sizes) again[k].sizes = keep[k].data();
+    const std::vector<gacer_sync> sy = c->syncs;
+    return install_plan(c, again, sy);
+}
+
 gacer_status gacer_set_sync_every_launch(gacer_ctx *c, int enable)
 {
     if (!c) return GACER_EINVAL;
@@ -1245,6 +1313,10 @@ static void launch_work(const Launch &l, double *flops, double *bytes)
         *flops = 2.0 * M * N * g.K * z;
         const double rows_in = M / ((double)g.Ho * g.Wo) * g.H * g.W;      // input positions of the launched images
         *bytes = (rows_in * g.Cin + N * g.K + M * N * (g.res ? 2.0 : 1.0)) * esz * z + (g.bias ? N * 4.0 : 0.0);
+        if (g.pre_scale) {                      // fused affine: one FMA per A element, its output written once, its two vectors read
+            *flops += 2.0 * M * g.Cin;
+            *bytes += M * g.Cin * esz + 8.0 * g.Cin;
+        }
         return;
     }
     const StreamArgs &s = l.s;

@@ -25,7 +25,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 static constexpr int THREADS = 256;
-enum { LOAD_VEC = 0, LOAD_GATHER = 1, LOAD_BT = 2, LOAD_TAPS = 3 };
+enum { LOAD_VEC = 0, LOAD_GATHER = 1, LOAD_BT = 2, LOAD_TAPS = 3, LOAD_AFFINE = 4 };
 
 __device__ __forceinline__ float bf16_to_f32(unsigned short v) { return __uint_as_float(((unsigned)v) << 16); }
 __device__ __forceinline__ unsigned short f32_to_bf16(float f)     // round to nearest even (hardware conversion)
@@ -358,9 +358,15 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     }
 
     uint4 ra[2][AV], rb[2][BREG];
+    // LOAD_AFFINE: scale and shift of this thread's channels of the block in flight, and the block's first channel
+    constexpr bool PRE = LOAD == LOAD_AFFINE;
+    constexpr int PV = PRE ? 2 * (VEC / 4) : 1;
+    uint4 rp[2][PV];
+    int rkv[2] = {0, 0};
+    const bool pre_store = PRE && n0 == 0;      // the tile column that covers output channel 0 writes the affine tensor
 
     // loads the next K block of this thread (blocks are requested in ascending order, one call per block)
-    auto load_global = [&](uint4 *pa, uint4 *pb) {
+    auto load_global = [&](uint4 *pa, uint4 *pb, uint4 *pp, int &pkv) {
         if constexpr (LOAD == LOAD_GATHER) {
             // element-wise gather: any Cin, any alignment (stem convolutions, ragged K)
             T ea[AV][VEC], eb[BV][VEC];
@@ -422,6 +428,16 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
                 }
             }
         }
+        if constexpr (PRE) {                    // beyond K both read zero, so the transformed element is act(0) = 0
+            const __amdgpu_buffer_rsrc_t psr = make_rsrc(a.pre_scale, (int64_t)a.Cin * 4), phr = make_rsrc(a.pre_shift, (int64_t)a.Cin * 4);
+            const bool k_ok = kv < k_end;
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                pp[q] = buf_load16(psr, k_ok ? (unsigned)((kv + 4 * q) * 4) : OOB);
+                pp[VEC / 4 + q] = buf_load16(phr, k_ok ? (unsigned)((kv + 4 * q) * 4) : OOB);
+            }
+            pkv = kv;
+        }
         // advance to the next block
         kv += BK;
         if constexpr (TAPS) {
@@ -442,11 +458,45 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
         }
     };
 
-    auto store_lds = [&](int buf, const uint4 *pa, const uint4 *pb) {
+    auto store_lds = [&](int buf, const uint4 *pa, const uint4 *pb, const uint4 *pp, int pkv) {
+        float sc[VEC], sh[VEC];
+        if constexpr (PRE) {
+#pragma unroll
+            for (int q = 0; q < VEC / 4; ++q) {
+                sc[4 * q] = __uint_as_float(pp[q].x); sc[4 * q + 1] = __uint_as_float(pp[q].y);
+                sc[4 * q + 2] = __uint_as_float(pp[q].z); sc[4 * q + 3] = __uint_as_float(pp[q].w);
+                sh[4 * q] = __uint_as_float(pp[VEC / 4 + q].x); sh[4 * q + 1] = __uint_as_float(pp[VEC / 4 + q].y);
+                sh[4 * q + 2] = __uint_as_float(pp[VEC / 4 + q].z); sh[4 * q + 3] = __uint_as_float(pp[VEC / 4 + q].w);
+            }
+        }
 #pragma unroll
         for (int i = 0; i < AV; ++i) {
             const int row = vrow + i * RPP;
-            if (BM % RPP == 0 || row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = pa[i];
+            uint4 va = pa[i];
+            if constexpr (PRE) {                // the stand-alone operator's arithmetic: one FMA, the activation, one rounding
+                float v[VEC];
+                if constexpr (DT == DT_BF16) {
+                    const unsigned x4[4] = {va.x, va.y, va.z, va.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) { v[2 * q] = __uint_as_float(x4[q] << 16); v[2 * q + 1] = __uint_as_float(x4[q] & 0xFFFF0000u); }
+                } else {
+                    v[0] = __uint_as_float(va.x); v[1] = __uint_as_float(va.y); v[2] = __uint_as_float(va.z); v[3] = __uint_as_float(va.w);
+                }
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) {
+                    const float t = __fmaf_rn(v[q], sc[q], sh[q]);
+                    v[q] = a.pre_act == ACT_RELU ? __builtin_fmaxf(t, 0.f) : a.pre_act == ACT_RELU6 ? __builtin_amdgcn_fmed3f(t, 0.f, 6.f) : t;
+                }
+                if constexpr (DT == DT_BF16) {
+                    va.x = (unsigned)to_bf16(v[0]) | ((unsigned)to_bf16(v[1]) << 16); va.y = (unsigned)to_bf16(v[2]) | ((unsigned)to_bf16(v[3]) << 16);
+                    va.z = (unsigned)to_bf16(v[4]) | ((unsigned)to_bf16(v[5]) << 16); va.w = (unsigned)to_bf16(v[6]) | ((unsigned)to_bf16(v[7]) << 16);
+                } else {
+                    va = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+                }
+                if (pre_store && a_hm[i] && pkv < k_end && (BM % RPP == 0 || row < BM))
+                    *(uint4 *)((T *)a.pre_y + (int64_t)(m0 + row) * a.Cin + pkv) = va;
+            }
+            if (BM % RPP == 0 || row < BM) *(uint4 *)(As + (buf * BM + row) * ROWB + vcol * 16) = va;
         }
         if constexpr (LOAD != LOAD_BT) {
 #pragma unroll
@@ -514,19 +564,19 @@ __global__ __launch_bounds__(THREADS) void igemm_kernel(GemmArgs a)
     // of block kb+2 are issued into register set p before the MFMAs of block kb start.  Loads and LDS
     // stores in the loop body are unconditional (blocks past the end of the slice read as zeros and land in
     // a buffer nobody reads), which keeps the body branch-free and the outstanding-load counts exact.
-    load_global(ra[0], rb[0]);
-    store_lds(0, ra[0], rb[0]);
-    load_global(ra[1], rb[1]);
+    load_global(ra[0], rb[0], rp[0], rkv[0]);
+    store_lds(0, ra[0], rb[0], rp[0], rkv[0]);
+    load_global(ra[1], rb[1], rp[1], rkv[1]);
     __syncthreads();
     int kb = kb_lo;
     for (; kb + 1 < nkb; kb += 2) {             // whole pairs of blocks; a single loop exit keeps one accumulator set
-        load_global(ra[0], rb[0]);
+        load_global(ra[0], rb[0], rp[0], rkv[0]);
         compute(0);
-        store_lds(1, ra[1], rb[1]);
+        store_lds(1, ra[1], rb[1], rp[1], rkv[1]);
         __syncthreads();
-        load_global(ra[1], rb[1]);
+        load_global(ra[1], rb[1], rp[1], rkv[1]);
         compute(1);
-        store_lds(0, ra[0], rb[0]);
+        store_lds(0, ra[0], rb[0], rp[0], rkv[0]);
         __syncthreads();
     }
     if (kb < nkb) compute(0);                   // odd block count: the last block already sits in LDS buffer 0
@@ -1090,10 +1140,10 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     static const std::string shape = std::string(DT == DT_BF16 ? "bf16_" : "f32_") + std::to_string(BM) + "x" + std::to_string(BN) +
                                      "x" + std::to_string(KV * El<DT>::VEC);
     static const std::string n_vec = "igemm_" + shape, n_bt = "igemm_bt_" + shape, n_gather = "igemm_gather_" + shape,
-                             n_taps = "igemm_taps_" + shape;
+                             n_taps = "igemm_taps_" + shape, n_pre = "igemm_affine_" + shape;
     const bool taps = !(a.kh == 1 && a.kw == 1 && a.pad == 0);
     if (taps && a.kh * a.kw > 31) vec_ok = false;      // the tapped loader keeps one validity bit per tap in a 32-bit mask
-    li.kernel = a.b_trans ? n_bt.c_str() : (!vec_ok ? n_gather.c_str() : (taps ? n_taps.c_str() : n_vec.c_str()));
+    li.kernel = a.pre_scale ? n_pre.c_str() : a.b_trans ? n_bt.c_str() : (!vec_ok ? n_gather.c_str() : (taps ? n_taps.c_str() : n_vec.c_str()));
     li.phases = ks > 1 ? 2 : 1;
     if (phase == 2) li.kernel = "splitk_finish";
     if (dry || li.workgroups == 0) return li;
@@ -1106,7 +1156,9 @@ static LaunchInfo go(const GemmArgs &a, hipStream_t s, bool dry, bool vec_ok, in
     b.n_major = tile_order(a, tiles_m, tiles_n, (int)sizeof(T));
     set_divisors(b);
     set_tiling(b, tiles_m, tiles_n);
-    if (a.b_trans)
+    if (a.pre_scale)
+        GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_AFFINE>), grid, block, 0, s, b);
+    else if (a.b_trans)
         GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_BT>), grid, block, 0, s, b);
     else if (!vec_ok)
         GACER_LAUNCH((igemm_kernel<DT, BM, BN, WM, WN, KV, LOAD_GATHER>), grid, block, 0, s, b);
@@ -1230,7 +1282,7 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
                         (a.x_zb % VEC == 0) && (a.x_zh % VEC == 0) && (a.w_zb % VEC == 0) && (a.w_zh % VEC == 0) &&
                         (((uintptr_t)a.x) % 16 == 0) && (((uintptr_t)a.w) % 16 == 0);
     if constexpr (DT == DT_BF16) {
-        if (rows_eligible(a, (int)sizeof(typename El<DT>::T), vec_ok)) return pick_rows<DT>(a, s, dry || phase == 2);
+        if (!a.pre_scale && rows_eligible(a, (int)sizeof(typename El<DT>::T), vec_ok)) return pick_rows<DT>(a, s, dry || phase == 2);
     }
     const int M = a.m_hi - a.m_lo, N = a.n_hi - a.n_lo;
     const int64_t z = (int64_t)a.zb * a.zh * (a.b_trans ? 1 : a.ksplit);
@@ -1255,6 +1307,14 @@ static LaunchInfo pick(const GemmArgs &a, hipStream_t s, bool dry, int phase)
         double best = cost(64, 64, e_small);
         if (cost(128, 64, e_mid) < best * 0.999) { best = cost(128, 64, e_mid); shape = 1; }
         if (bn == 128 && cost(128, 128, 1.0) < best * 0.999) shape = 2;
+    }
+    if (a.pre_scale) {                           // fused per-channel affine: the A tile passes through registers, so the register-staged kernel
+        switch (shape) {                         // (the executor fuses only 16-byte aligned, vector-multiple operands)
+        case 2: return go<DT, 128, 128, 2, 2, 8>(a, s, dry, true, phase);
+        case 1: return go<DT, 128, 64, 2, 2, 8>(a, s, dry, true, phase);
+        case 0: return go<DT, 64, 64, 2, 2, 8>(a, s, dry, true, phase);
+        default: return go<DT, 128, 32, 4, 1, 8>(a, s, dry, true, phase);
+        }
     }
     // Long K rows: the direct-to-LDS pipeline (igemm_dma_kernel) keeps several K blocks in flight and wins once the K
     // loop is long enough to amortise filling its stages (measured layer by layer: from about 1.5 KB of K per row).

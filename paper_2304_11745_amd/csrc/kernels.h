@@ -53,6 +53,14 @@ struct GemmArgs {
     int tiles_m, tiles_n;
     unsigned div_tiles_m[2], div_tiles_n[2], div_zh[2];
     unsigned div_nl[2];        // set by the launcher of the finishing pass: divisor for n_hi - n_lo
+    // Per-channel affine + activation fused in front of a 1x1 product (pre_scale != null): x is the affine operator's INPUT
+    // (same shape as its output, K = Cin channels) and A[m][k] = pre_act(x[m][k] * pre_scale[k] + pre_shift[k]), rounded to
+    // the element type, is formed while the A tile is stored to LDS; the tiles that cover output channel 0 also write it to
+    // pre_y ([rows][Cin]), so the affine operator's output tensor exists as if its own kernel had run.  pre_act is
+    // ACT_NONE, ACT_RELU or ACT_RELU6 (zero stays zero, which the zero fill beyond K relies on).
+    const float *pre_scale, *pre_shift;
+    void *pre_y;
+    int pre_act;
 };
 
 // Channels-last streaming operators.  Sub-range: images [n_lo,n_hi), channels [c_lo,c_hi).

@@ -51,11 +51,12 @@ __global__ __launch_bounds__(TPB) void dwconv_kernel(StreamArgs a)
     if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
 #pragma unroll
     for (int q = 0; q < V; ++q) {
-        float v = acc[q];
-        if (a.bias) v = __fadd_rn(v, a.bias[c + q]);
-        if (a.res) v = __fadd_rn(v, rv.get(q));
-        yv.set(q, activate(v, a.act));
+        if (a.bias) acc[q] = __fadd_rn(acc[q], a.bias[c + q]);
+        if (a.res) acc[q] = __fadd_rn(acc[q], rv.get(q));
     }
+    activate_n<V>(acc, a.act);
+#pragma unroll
+    for (int q = 0; q < V; ++q) yv.set(q, acc[q]);
     st_vec<T, V>((T *)a.y, o, yv);
 }
 
@@ -180,8 +181,9 @@ __global__ __launch_bounds__(TPB, 4) void dwconv3_kernel(StreamArgs a)
             float v = acc[t][q];
             if (a.bias) v = __fadd_rn(v, bias[q]);
             if (a.res) v = __fadd_rn(v, rf[q]);
-            out[q] = activate(v, a.act);
+            out[q] = v;
         }
+        activate_n<V>(out, a.act);
         *(R *)((T *)a.y + o) = Unpack<T, V>::pack(out);
     }
 }
@@ -276,6 +278,7 @@ __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
         const int img = a.n_lo + div_by(div_by(p0, a.div_w), a.div_h);
         gv = ld_vec<T, V>((const T *)a.gate, (int64_t)img * a.C + c);
     }
+    float out[V];
 #pragma unroll
     for (int q = 0; q < V; ++q) {
         float v = xv.get(q);
@@ -283,8 +286,11 @@ __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
         if (a.scale) v = __fmaf_rn(v, a.scale[c + q], a.shift[c + q]);
         if (a.x2) v = __fadd_rn(v, bv.get(q));
         if (a.res) v = __fadd_rn(v, rv.get(q));
-        yv.set(q, activate(v, a.act));
+        out[q] = v;
     }
+    activate_n<V>(out, a.act);
+#pragma unroll
+    for (int q = 0; q < V; ++q) yv.set(q, out[q]);
     st_vec<T, V>((T *)a.y, o, yv);
 }
 

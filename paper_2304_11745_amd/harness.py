@@ -179,6 +179,10 @@ class Session:
         """One host thread per tenant enqueues that tenant's stream (Section 2.1 deployment model)."""
         B.check(self.ctx, B.gacer_set_issue_threads(self.ctx, 1 if enable else 0))
 
+    def set_fuse_affine(self, enable=True):
+        """Affine + consuming 1x1 convolution as one launch where the plan allows (on by default)."""
+        B.check(self.ctx, B.gacer_set_fuse_affine(self.ctx, 1 if enable else 0))
+
     def set_sync_every_launch(self, enable=True):
         """Checking mode: every kernel is waited for and checked before the next is issued."""
         B.check(self.ctx, B.gacer_set_sync_every_launch(self.ctx, 1 if enable else 0))
@@ -216,6 +220,10 @@ class Session:
     def output_bytes(self, ti):
         a = self.acts[ti][self.tenants[ti].output]
         return a.contiguous().view(torch.uint8).cpu().numpy().tobytes()
+
+    def tensor_bytes(self, ti, idx):
+        """Raw bytes of tensor ``idx`` of tenant ``ti`` as stored on the device."""
+        return self.acts[ti][idx].contiguous().view(torch.uint8).cpu().numpy().tobytes()
 
     def poison_outputs(self):
         """Overwrite every non-input tensor with NaN so stale results cannot pass for fresh ones."""

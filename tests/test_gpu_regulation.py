@@ -249,3 +249,54 @@ def test_sync_every_launch_gives_the_same_bits(gpu):
         sess.run(B.GACER_MODE_PLAN, 2)
         assert [sess.output_bytes(i) for i in range(len(tenants))] == base
     sess.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fused_affine_launch_keeps_every_bit(gpu, dtype):
+    """Launch fusion: a per-channel affine + ReLU and the 1x1 convolution that reads it run as one kernel.  Every tensor of
+    every tenant (the affine outputs included, which the fused kernel writes on the side) must hold the bits of the unfused
+    run, in every mode; the trace shows the fused kernel and no launch for the absorbed operator; a plan that decomposes
+    one operator of a pair issues that pair unfused."""
+    from paper_2304_11745_amd import binding as B
+    from synth import graphs as G
+    tenants = [G._densenet("dense_a", dtype, 3, 40, 8, [2, 3], 16, 2, 10), G._densenet("dense_b", dtype, 2, 33, 16, [3, 2], 24, 4, 7),
+               G.small_resnet(dtype, 2)]
+    data = [G.materialise(t, 31, i << 20) for i, t in enumerate(tenants)]
+    sess = gpu.Session(tenants, data)
+
+    def snapshot():
+        return [[sess.tensor_bytes(t, i) for i in range(len(tn.tensors))] for t, tn in enumerate(tenants)]
+    sess.set_fuse_affine(False)
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_SEQUENTIAL, 1)
+    want = snapshot()
+    rows = sess.trace(B.GACER_MODE_STREAM_PARALLEL, 1)
+    assert not any(r["kernel"].startswith("igemm_affine_") for r in rows)
+    n_unfused = len(rows)
+    sess.set_fuse_affine(True)
+    rows = sess.trace(B.GACER_MODE_STREAM_PARALLEL, 1)
+    fused = [r for r in rows if r["kernel"].startswith("igemm_affine_")]
+    pairs = sorted({(r["tenant"], r["op"]) for r in fused})
+    vec = 8 if dtype == "bf16" else 4
+    expect = sorted((ti, k + 1) for ti, t in enumerate(tenants) for k, (a, b) in enumerate(zip(t.ops, t.ops[1:]))
+                    if a.kind == "affine" and b.kind == "conv" and b.kh == 1 and b.in0 == a.out and t.tensors[a.out][1] % vec == 0)
+    assert pairs == expect and len(pairs) >= 10, "every dense layer and transition with a vector-multiple channel count is fused"
+    assert len(rows) == n_unfused - len(pairs)
+    for t, op in pairs:
+        assert tenants[t].ops[op].kind == "conv" and tenants[t].ops[op - 1].kind == "affine"
+        assert not any(r["tenant"] == t and r["op"] == op - 1 for r in rows), "the absorbed affine operator still has a launch"
+    for mode in (B.GACER_MODE_SEQUENTIAL, B.GACER_MODE_STREAM_PARALLEL, B.GACER_MODE_PLAN):
+        sess.poison_outputs()
+        sess.run(mode, 2)
+        assert snapshot() == want, f"mode {mode}: fused launches changed some tensor"
+    # decomposing the product of one pair un-fuses exactly that pair; pointers and other decompositions leave the rest fused
+    t, op = pairs[0]
+    sess.set_plan([(t, op, "cout", 2), (2, 1, "batch", 2)], sess.edges_from_pointers([[5, 9], [4, 12], [3, 6]]))
+    rows = sess.trace(B.GACER_MODE_PLAN, 1)
+    assert any(r["tenant"] == t and r["op"] == op - 1 for r in rows)
+    still = {(r["tenant"], r["op"]) for r in rows if r["kernel"].startswith("igemm_affine_")}
+    assert (t, op) not in still and len(still) >= len(pairs) - 1 - 4      # a pointer that lands on an affine operator un-fuses it too
+    sess.poison_outputs()
+    sess.run(B.GACER_MODE_PLAN, 2)
+    assert snapshot() == want
+    sess.close()

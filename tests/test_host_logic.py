@@ -76,8 +76,23 @@ def test_all_configs_load_and_count_launches(ctx, config):
     st, keep = load(ctx, tenants)
     assert st == B.GACER_OK, B.gacer_last_error(ctx)
     n = C.c_int()
+    assert B.gacer_set_fuse_affine(ctx, 0) == B.GACER_OK
     assert B.gacer_launch_count(ctx, B.GACER_MODE_SEQUENTIAL, C.byref(n)) == B.GACER_OK
     assert n.value == sum(len(t.ops) for t in tenants)
+    # launch fusion: a per-channel affine followed by the 1x1 convolution that reads it is one launch, unless its channel
+    # count is not a multiple of a 16-byte vector
+    def fused_pairs(t):
+        vec, k = (8 if t.dtype == "bf16" else 4), 0
+        for a, b in zip(t.ops, t.ops[1:]):
+            if (a.kind == "affine" and a.res < 0 and a.act in ("none", "relu", "relu6") and b.kind == "conv" and b.kh == 1 and
+                    b.stride == 1 and b.pad == 0 and b.in0 == a.out and t.tensors[a.out][1] % vec == 0):
+                k += 1
+        return k
+    assert B.gacer_set_fuse_affine(ctx, 1) == B.GACER_OK
+    assert B.gacer_launch_count(ctx, B.GACER_MODE_SEQUENTIAL, C.byref(n)) == B.GACER_OK
+    assert n.value == sum(len(t.ops) - fused_pairs(t) for t in tenants)
+    if config == 8:
+        assert sum(fused_pairs(t) for t in tenants) == 61           # DenseNet-121: 58 dense layers and 3 transitions
 
 
 def test_shape_validation(ctx):
