@@ -13,11 +13,13 @@
 
 static void *const FAKE = (void *)0x10000;      // aligned, never dereferenced
 
-struct Chain {                                  // a tenant of n 3x3 convolutions, 16 channels, 6x6, batch 8
+// a tenant of n operators on 16 channels, 6x6, batch 8: 3x3 convolutions, or (pre_activation) every second and third operator
+// a per-channel affine + ReLU and the 1x1 convolution behind it, the pair that the executor issues as one launch
+struct Chain {
     std::vector<gacer_op> ops;
     std::vector<gacer_tensor> tensors;
     gacer_tenant desc;
-    explicit Chain(int n)
+    explicit Chain(int n, bool pre_activation = false)
     {
         tensors.push_back({8, 16, 6, 6, FAKE});
         for (int i = 0; i < n; ++i) {
@@ -27,6 +29,12 @@ struct Chain {                                  // a tenant of n 3x3 convolution
             op.kind = GACER_CONV2D; op.in0 = i; op.in1 = -1; op.res = -1; op.out = i + 1;
             op.w = FAKE; op.bias = (const float *)FAKE;
             op.cin = 16; op.cout = 16; op.kh = op.kw = 3; op.stride = 1; op.pad = 1; op.groups = 1; op.act = GACER_ACT_RELU; op.alpha = 1.f;
+            if (pre_activation && i % 3 == 1) {
+                op.kind = GACER_AFFINE_ACT; op.w = nullptr; op.bias = nullptr; op.scale = op.shift = (const float *)FAKE;
+                op.kh = op.kw = 1; op.pad = 0;
+            } else if (pre_activation && i % 3 == 2) {
+                op.kh = op.kw = 1; op.pad = 0;
+            }
             ops.push_back(op);
         }
         std::memset(&desc, 0, sizeof desc);
@@ -45,10 +53,18 @@ int main()
         std::vector<Chain> chains;
         chains.reserve(NT);
         std::vector<int> n_ops;
-        for (int t = 0; t < NT; ++t) { n_ops.push_back(2 + (int)(rng() % 6)); chains.emplace_back(n_ops.back()); }
+        for (int t = 0; t < NT; ++t) { n_ops.push_back(2 + (int)(rng() % 6)); chains.emplace_back(n_ops.back(), t % 2 == 1); }
         std::vector<gacer_tenant> descs;
         for (Chain &c : chains) { c.desc.ops = c.ops.data(); c.desc.tensors = c.tensors.data(); descs.push_back(c.desc); }
         CHECK(gacer_load_tenants(ctx, descs.data(), NT) == GACER_OK);
+        {   // launch fusion: fewer launches with it when a pre-activation pair exists, one per operator without it
+            int fused = 0, plain = 0, total = 0;
+            for (int n : n_ops) total += n;
+            CHECK(gacer_launch_count(ctx, GACER_MODE_SEQUENTIAL, &fused) == GACER_OK);
+            CHECK(gacer_set_fuse_affine(ctx, 0) == GACER_OK);
+            CHECK(gacer_launch_count(ctx, GACER_MODE_SEQUENTIAL, &plain) == GACER_OK && plain == total && fused <= plain);
+            CHECK(gacer_set_fuse_affine(ctx, trial % 2) == GACER_OK);
+        }
         // Matrix_P -> edges -> text -> plan -> installed
         const int n_ptr = (int)(rng() % 4);
         std::vector<int> P;
