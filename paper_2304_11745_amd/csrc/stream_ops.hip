@@ -188,6 +188,66 @@ __global__ __launch_bounds__(TPB, 4) void dwconv3_kernel(StreamArgs a)
     }
 }
 
+// ---- depthwise K x K with K known at compile time (5 x 5): the loops are unrolled and branch-free, so the taps and their
+// weights are requested together instead of one load per trip of a loop; a tap outside the image reads as zero and is
+// multiplied like the others, which leaves the FMA chain of dwconv_kernel (row-major from zero) bit for bit.
+template <typename T, int V, int K>
+__device__ __forceinline__ void dwconv_rows(const StreamArgs &a)
+{
+    const int CV = (a.c_hi - a.c_lo) / V;
+    const int64_t total = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * CV;
+    const int64_t idx = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (idx >= total) return;
+    const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
+    const int p1 = div_by(p0, a.div_w), ow = p0 - p1 * a.Wo;
+    const int p2 = div_by(p1, a.div_h), oh = p1 - p2 * a.Ho;
+    const int n = a.n_lo + p2;
+    const int c = a.c_lo + cv * V;
+    const T *x = (const T *)a.x;
+    const T *w = (const T *)a.w;
+    const int ih0 = oh * a.stride - a.pad, iw0 = ow * a.stride - a.pad;
+    float acc[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) acc[q] = 0.f;
+#pragma unroll
+    for (int r = 0; r < K; ++r) {
+        const int ih = ih0 + r;
+        const bool row_ok = ih >= 0 && ih < a.H;
+        Vec<T, V> xv[K], wv[K];
+#pragma unroll
+        for (int s = 0; s < K; ++s) {
+            const int iw = iw0 + s;
+            const bool ok = row_ok && iw >= 0 && iw < a.W;
+            // a tap outside the image reads the first pixel of the image instead (any valid address) and is then zeroed
+            const int64_t o = ok ? (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c : (int64_t)n * a.H * a.W * a.C + c;
+            xv[s] = ld_vec<T, V>(x, o);
+            if (!ok) {
+#pragma unroll
+                for (int q = 0; q < V; ++q) xv[s].set(q, 0.f);
+            }
+            wv[s] = ld_vec<T, V>(w, (int64_t)(r * K + s) * a.C + c);
+        }
+#pragma unroll
+        for (int s = 0; s < K; ++s)
+#pragma unroll
+            for (int q = 0; q < V; ++q) acc[q] = __fmaf_rn(xv[s].get(q), wv[s].get(q), acc[q]);
+    }
+    const int64_t o = (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.C + c;
+    Vec<T, V> rv, yv;
+    if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
+#pragma unroll
+    for (int q = 0; q < V; ++q) {
+        if (a.bias) acc[q] = __fadd_rn(acc[q], a.bias[c + q]);
+        if (a.res) acc[q] = __fadd_rn(acc[q], rv.get(q));
+    }
+    activate_n<V>(acc, a.act);
+#pragma unroll
+    for (int q = 0; q < V; ++q) yv.set(q, acc[q]);
+    st_vec<T, V>((T *)a.y, o, yv);
+}
+
+template <typename T, int V> __global__ __launch_bounds__(TPB) void dwconv5_kernel(StreamArgs a) { dwconv_rows<T, V, 5>(a); }
+
 // ---- pooling k x k: window maximum, or (pool_avg, unpadded) window mean added in row-major order --------
 template <typename T, int V>
 __global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
@@ -557,6 +617,7 @@ LaunchInfo launch_dwconv(const StreamArgs &a, hipStream_t s, bool dry)
         }
     }
     const int64_t outs = (int64_t)(a.n_hi - a.n_lo) * a.Ho * a.Wo * (a.c_hi - a.c_lo);
+    if (a.k == 5) { GACER_DISPATCH_VEC(dwconv5_kernel, "dwconv5x5") }
     GACER_DISPATCH_VEC(dwconv_kernel, "dwconv")
 }
 
