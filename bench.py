@@ -32,7 +32,7 @@ HBM_PEAK = 8.0e12
 TRAFFIC = {
     2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": 13.19e6, "write_bytes": 6.22e6, "plan": "unsplit",
         "launches_per_round": 16, "algorithmic_bytes": 10.62e6,
-        "sources_sha256": "41794d64500b5170269e9376f868608db28500da5f8cdbe5a5bd068500106910"},
+        "sources_sha256": "ee2f21e25c10b8eba2fb652bf2dfb3a1686c32b4a6d43289bfff11a1ddf2b8df"},
 }
 TRAFFIC_SOURCES = ["igemm.hip", "stream_ops.hip", "device_util.h", "kernels.h"]
 
