@@ -268,11 +268,24 @@ def run_op(t, i, tensors, params):
 
 def run_tenant(t, x, params, splits=None, keep_all=False):
     """Forward pass.  ``splits`` maps op index -> (axis, factor), axis in {'batch','cout'}.
-    Returns the output tensor (or the list of all tensors with keep_all)."""
+    Returns the output tensor (or the list of all tensors with keep_all).
+
+    A tensor listed in ``t.views`` is a channel window of a wider tensor: writing it writes those channels of the wider
+    tensor, reading it reads them (that is all a concatenation along channels is)."""
+    views = getattr(t, "views", {})
     T = [None] * len(t.tensors)
     T[t.input] = np.ascontiguousarray(x, dtype=np.float32)
     P = [np.ascontiguousarray(p, dtype=np.float32) for p in params]
+
+    def window(i):
+        base, off = views[i]
+        if T[base] is None:
+            T[base] = np.zeros(t.tensors[base], np.float32)
+        return T[base][:, off:off + t.tensors[i][1]]
     for i, op in enumerate(t.ops):
+        for src in (op.in0, op.in1, op.res):
+            if src in views:
+                T[src] = np.ascontiguousarray(window(src))
         y = np.zeros(t.tensors[op.out], np.float32)
         axis, f = (splits or {}).get(i, ("none", 1))
         if axis == "batch":
@@ -286,4 +299,9 @@ def run_tenant(t, x, params, splits=None, keep_all=False):
         if t.dtype == "bf16":
             lib().orc_round_bf16(_p(y), y.size)
         T[op.out] = y
+        if op.out in views:
+            window(op.out)[...] = y
+    if keep_all:
+        for i in views:
+            T[i] = np.ascontiguousarray(window(i))
     return T if keep_all else T[t.output]

@@ -11,7 +11,7 @@ Nothing here computes anything: builders emit shapes and parameter recipes,
 ``materialise`` draws the seeded numbers.
 """
 from dataclasses import dataclass, field
-from typing import List, Tuple
+from typing import Dict, List, Tuple
 import math
 import numpy as np
 
@@ -66,6 +66,9 @@ class Tenant:
     input: int = 0
     output: int = 0
     input_dist: str = "uniform"   # 'uniform' U[-1,1) | 'normal002' N(0, 0.02^2)
+    # channel windows: tensor index -> (index of the wider tensor it lives in, first channel).  A window shares the wider
+    # tensor's storage, so writing windows one after the other concatenates along channels without a copy.
+    views: Dict[int, Tuple[int, int]] = field(default_factory=dict)
 
 
 class _B:
@@ -85,11 +88,25 @@ class _B:
     def shape(self, i):
         return self.t.tensors[i]
 
-    def conv(self, x, cout, k, stride=1, pad=0, act="none", res=-1, bn=False, groups=1):
+    def view(self, base, c_off, c):
+        """Channels [c_off, c_off + c) of tensor ``base`` as a tensor of its own (shared storage)."""
+        n, cb, h, w = self.shape(base)
+        assert base not in self.t.views and 0 <= c_off and c_off + c <= cb
+        y = self.tensor(n, c, h, w)
+        self.t.views[y] = (base, c_off)
+        return y
+
+    def _out(self, out, shape):
+        if out is None:
+            return self.tensor(*shape)
+        assert self.shape(out) == tuple(shape)
+        return out
+
+    def conv(self, x, cout, k, stride=1, pad=0, act="none", res=-1, bn=False, groups=1, out=None):
         n, c, h, w = self.shape(x)
         ho = (h + 2 * pad - k) // stride + 1
         wo = (w + 2 * pad - k) // stride + 1
-        y = self.tensor(n, cout, ho, wo)
+        y = self._out(out, (n, cout, ho, wo))
         fan_in = (c // groups) * k * k
         fold = 1.0 / math.sqrt(1.0 + BN_EPS) if bn else 1.0
         wi = self.param((cout, c // groups, k, k), "he_uniform", fan_in, fold)
@@ -112,11 +129,11 @@ class _B:
         self.t.ops.append(Op("gemm", x, y, res=res, w=wi, bias=bi, cin=cin, cout=cout, act=act))
         return y
 
-    def maxpool(self, x, k, stride, pad):
+    def maxpool(self, x, k, stride, pad, out=None):
         n, c, h, w = self.shape(x)
         ho = (h + 2 * pad - k) // stride + 1
         wo = (w + 2 * pad - k) // stride + 1
-        y = self.tensor(n, c, ho, wo)
+        y = self._out(out, (n, c, ho, wo))
         self.t.ops.append(Op("maxpool", x, y, cin=c, cout=c, kh=k, kw=k, stride=stride, pad=pad))
         return y
 
@@ -166,15 +183,15 @@ class _B:
         self.t.ops.append(Op("concat", a, y, in1=b, cin=ca, cout=ca + cb))
         return y
 
-    def avgpool(self, x, k, stride):
+    def avgpool(self, x, k, stride, out=None):
         n, c, h, w = self.shape(x)
-        y = self.tensor(n, c, (h - k) // stride + 1, (w - k) // stride + 1)
+        y = self._out(out, (n, c, (h - k) // stride + 1, (w - k) // stride + 1))
         self.t.ops.append(Op("avgpool", x, y, cin=c, cout=c, kh=k, kw=k, stride=stride, pad=0))
         return y
 
-    def act(self, x, act):
+    def act(self, x, act, out=None):
         n, c, h, w = self.shape(x)
-        y = self.tensor(n, c, h, w)
+        y = self._out(out, (n, c, h, w))
         self.t.ops.append(Op("act", x, y, cin=c, cout=c, act=act))
         return y
 
@@ -417,22 +434,45 @@ def mobilenetv3_large(dtype="bf16", batch=8, hw=224):
 # BN-ReLU-conv1x1 (half the channels) and a 2x2 mean pool.  BatchNorms that
 # follow a convolution are folded into it; the ones that follow a
 # concatenation cannot be and stay as per-channel affine operators.
+# The concatenation itself is storage, not work (in_place): a block owns one
+# tensor as wide as its last layer's input plus output, the pool in front of
+# the block and every layer write their channel windows of it, and a layer
+# reads the prefix written so far.  in_place=False spells the same network with
+# a concatenation operator that copies.
 # ----------------------------------------------------------------------------
-def _densenet(name, dtype, batch, hw, growth, blocks, init, bn_size, classes):
+def _densenet(name, dtype, batch, hw, growth, blocks, init, bn_size, classes, in_place=True):
     b = _B(name, dtype, batch)
     x = b.tensor(batch, 3, hw, hw)
     y = b.conv(x, init, 7, 2, 3, "relu", bn=True)
-    y = b.maxpool(y, 3, 2, 1)
+
+    def into_block(src, k, stride, pad, layers):
+        """The pool in front of a block (max with padding, mean without); in place, it writes the first window of the block's tensor."""
+        pool = (lambda out: b.maxpool(src, k, stride, pad, out=out)) if pad else (lambda out: b.avgpool(src, k, stride, out=out))
+        if not in_place:
+            return pool(None), None
+        n, c, h, w = b.shape(src)
+        blk = b.tensor(n, c + layers * growth, (h + 2 * pad - k) // stride + 1, (w + 2 * pad - k) // stride + 1)
+        return pool(b.view(blk, 0, c)), blk
+
+    y, blk = into_block(y, 3, 2, 1, blocks[0])
     for bi, layers in enumerate(blocks):
-        for _ in range(layers):
+        c = b.shape(y)[1]
+        for l in range(layers):
+            if in_place and l > 0:
+                y = b.view(blk, 0, c)           # everything written so far
             z = b.bn_affine(y, "relu")
             z = b.conv(z, bn_size * growth, 1, 1, 0, "relu", bn=True)
-            z = b.conv(z, growth, 3, 1, 1, "none")
-            y = b.concat(y, z)
+            if in_place:
+                b.conv(z, growth, 3, 1, 1, "none", out=b.view(blk, c, growth))
+            else:
+                y = b.concat(y, b.conv(z, growth, 3, 1, 1, "none"))
+            c += growth
+        if in_place:
+            y = blk                             # all of its windows are written
         if bi + 1 < len(blocks):
             z = b.bn_affine(y, "relu")
-            z = b.conv(z, b.shape(y)[1] // 2, 1, 1, 0, "none")
-            y = b.avgpool(z, 2, 2)
+            z = b.conv(z, c // 2, 1, 1, 0, "none")
+            y, blk = into_block(z, 2, 2, 0, blocks[bi + 1])
     y = b.bn_affine(y, "relu")
     y = b.gavgpool(y)
     y = b.gemm(y, classes, flatten=True)

@@ -271,11 +271,21 @@ def _torch_forward(t, x, params):
     """Independent walk of the same graph with torch CPU fp64 ops."""
     T = {t.input: torch.from_numpy(x).double()}
     P = [torch.from_numpy(p).double() for p in params]
+    views = getattr(t, "views", {})
+    parts = {}                                       # wider tensor -> {first channel: window}, concatenated when read
     actf = {"none": lambda v: v, "relu": torch.relu, "relu6": lambda v: torch.clamp(v, 0, 6), "gelu": tF.gelu,
             "hswish": tF.hardswish, "hsigmoid": tF.hardsigmoid}
+    def read(i):
+        if i in views:                               # a prefix of the wider tensor: the windows written so far, in channel order
+            base, off = views[i]
+            whole = torch.cat([parts[base][k] for k in sorted(parts[base])], dim=1)
+            return whole[:, off:off + t.tensors[i][1]]
+        if i in parts:
+            return torch.cat([parts[i][k] for k in sorted(parts[i])], dim=1)
+        return T[i]
     for op in t.ops:
-        a = T[op.in0]
-        r = T[op.res] if op.res >= 0 else 0
+        a = read(op.in0)
+        r = read(op.res) if op.res >= 0 else 0
         if op.kind in ("conv", "dwconv"):
             y = actf[op.act](tF.conv2d(a, P[op.w], P[op.bias], stride=op.stride, padding=op.pad, groups=op.groups) + r)
         elif op.kind == "gemm":
@@ -319,7 +329,9 @@ def _torch_forward(t, x, params):
         else:
             raise ValueError(op.kind)
         T[op.out] = y
-    return T[t.output].numpy()
+        if op.out in views:
+            parts.setdefault(views[op.out][0], {})[views[op.out][1]] = y
+    return read(t.output).numpy()
 
 
 def eltwise_mix(dtype="f32", batch=3):
@@ -348,6 +360,25 @@ def test_graph_walk_vs_torch_fp64(maker):
     ref = _torch_forward(t, x, p)
     # fp32 storage of every intermediate tensor vs an unrounded fp64 pass
     assert np.abs(y - ref).max() <= 2e-5 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_channel_windows_are_concatenation(dtype):
+    """The same DenseNet-shaped graph written with channel windows of one tensor per block and with a concatenation
+    operator per layer: identical outputs, bit for bit, and identical block tensors."""
+    from synth import graphs as G
+    a = G._densenet("windows", dtype, 2, 40, 8, [2, 3], 12, 2, 10, in_place=True)
+    b = G._densenet("copies", dtype, 2, 40, 8, [2, 3], 12, 2, 10, in_place=False)
+    assert len(b.ops) - len(a.ops) == 5 and not b.views      # one concatenation per layer fewer
+    assert len(a.views) == (1 + 2 + 1) + (1 + 3 + 2)         # per block: the pool's window, one per layer, a prefix for every layer but the first
+    xa, pa = synth.materialise(a, 11)
+    xb, pb = synth.materialise(b, 11)
+    assert np.array_equal(xa, xb) and all(np.array_equal(u, v) for u, v in zip(pa, pb))
+    Ta, Tb = F.run_tenant(a, xa, pa, keep_all=True), F.run_tenant(b, xb, pb, keep_all=True)
+    assert np.array_equal(Ta[a.output], Tb[b.output])
+    blocks_a = [Ta[i] for i in range(len(a.tensors)) if i in {v[0] for v in a.views.values()}]
+    last_cat = [Tb[op.out] for op in b.ops if op.kind == "concat"]
+    assert np.array_equal(blocks_a[0], last_cat[1]) and np.array_equal(blocks_a[1], last_cat[4])
 
 
 @pytest.mark.parametrize("maker", [synth.small_cnn, synth.small_resnet, synth.small_mbv2, synth.small_mbv3, synth.small_densenet,

@@ -66,13 +66,29 @@ def test_graphs_are_topologically_ordered():
     for cfg in sorted(synth.CONFIG_NAMES):
         tenants, _ = synth.build_config(cfg, "full", with_data=False)
         for t in tenants:
-            written = {t.input}
+            # channels written so far, per tensor that owns storage (a channel window writes / reads channels of its base)
+            have = {i: set() for i in range(len(t.tensors)) if i not in t.views}
+
+            def channels(i):
+                base, off = t.views.get(i, (i, 0))
+                return base, set(range(off, off + t.tensors[i][1]))
+
+            def write(i):
+                base, ch = channels(i)
+                assert not (have[base] & ch), "written twice"
+                have[base] |= ch
+
+            def readable(i):
+                base, ch = channels(i)
+                return ch <= have[base]
+            write(t.input)
             for op in t.ops:
                 for i in (op.in0, op.in1, op.res):
-                    assert i < 0 or i in written
-                assert op.out not in written
-                written.add(op.out)
-            assert t.output in written
+                    assert i < 0 or readable(i)
+                write(op.out)
+            assert readable(t.output)
+            for i, (base, off) in t.views.items():
+                assert base not in t.views and t.tensors[base][0] == t.tensors[i][0] and t.tensors[base][2:] == t.tensors[i][2:]
             assert all(s[0] % t.batch == 0 for s in t.tensors)
 
 
