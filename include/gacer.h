@@ -78,9 +78,22 @@ typedef enum {
  * the first (extent % factor) chunks are one element longer, sizes sum to the extent. */
 typedef enum { GACER_AXIS_NONE = 0, GACER_AXIS_BATCH = 1, GACER_AXIS_COUT = 2 } gacer_axis;
 
+/*
+ * A tensor is stored channels-last: position (n, h, w) holds its c channels contiguously.  With pitch == 0 positions follow
+ * each other without gaps (pitch = c) and `base`, `c_off` are ignored.  With pitch != 0 the tensor is a channel window of a
+ * wider one: `base` indexes a gap-free tensor of the same n, h, w with c(base) == pitch, the window starts at channel c_off
+ * of it (c_off + c <= pitch, dptr == dptr(base) + c_off elements; a window that does not start on a 16-byte boundary is
+ * served by the element-wise kernel paths) and neighbouring positions are pitch elements apart.  Windows let a network concatenate along channels without a copy (DenseNet: every layer writes its
+ * window of one buffer per block, the next layer reads a prefix of it).  A window may be in0 of CONV2D, of a per-position
+ * GEMM, of AFFINE_ACT and of ACT, and out of those and of MAXPOOL / AVGPOOL; a residual input (`res`) of an operator that
+ * writes a window is not supported.  Windows written by different operators must not overlap; a window is readable once
+ * every channel of it has been written.
+ */
 typedef struct {
     int64_t n, c, h, w; /* logical shape; n must be a multiple of the tenant's batch */
-    void *dptr;         /* device, caller-owned, 16-byte aligned                     */
+    void *dptr;         /* device, caller-owned, 16-byte aligned (windows: see above) */
+    int64_t pitch;      /* elements between neighbouring positions; 0 = c            */
+    int base, c_off;    /* pitch != 0: the wider tensor and the first channel in it  */
 } gacer_tensor;
 
 /*

@@ -30,7 +30,8 @@ EXPORTS = ["gacer_create", "gacer_destroy", "gacer_load_tenants", "gacer_set_pla
 
 
 class gacer_tensor(C.Structure):
-    _fields_ = [("n", C.c_int64), ("c", C.c_int64), ("h", C.c_int64), ("w", C.c_int64), ("dptr", C.c_void_p)]
+    _fields_ = [("n", C.c_int64), ("c", C.c_int64), ("h", C.c_int64), ("w", C.c_int64), ("dptr", C.c_void_p),
+                ("pitch", C.c_int64), ("base", C.c_int), ("c_off", C.c_int)]
 
 
 class gacer_op(C.Structure):

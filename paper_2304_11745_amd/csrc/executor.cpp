@@ -137,13 +137,14 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
             g.H = (int)in.h; g.W = (int)in.w; g.Cin = (int)in.c; g.Ho = (int)out.h; g.Wo = (int)out.w;
             g.kh = op.kind == GACER_GEMM ? 1 : op.kh; g.kw = op.kind == GACER_GEMM ? 1 : op.kw;
             g.stride = op.kind == GACER_GEMM ? 1 : op.stride; g.pad = op.kind == GACER_GEMM ? 0 : op.pad;
-            g.x_pix = in.c; g.x_img = in.h * in.w * in.c;
+            const int64_t pitch = in.pitch ? in.pitch : in.c;
+            g.x_pix = pitch; g.x_img = in.h * in.w * pitch;
         }
         g.K = g.kh * g.kw * g.Cin;
-        g.x_bytes = in.n * in.c * in.h * in.w * (int64_t)esz;
+        g.x_bytes = (in.n * in.h * in.w * (in.pitch ? in.pitch : in.c) - (in.pitch ? in.c_off : 0)) * (int64_t)esz;   // to the end of the allocation
         g.w_bytes = (int64_t)out.c * g.K * (int64_t)esz;
         g.w_row = g.K;
-        g.y_row = out.c;
+        g.y_row = out.pitch ? out.pitch : out.c;
         g.m_lo = b_lo * q_out * g.Ho * g.Wo; g.m_hi = b_hi * q_out * g.Ho * g.Wo;
         g.n_lo = c_lo; g.n_hi = c_hi;
         g.ksplit = t.ksplit[oi]; g.kb_per_slice = t.kb_per_slice[oi];
@@ -197,6 +198,7 @@ Launch make_launch(const Tenant &t, int oi, int b_lo, int b_hi, int c_lo, int c_
         s.n_lo = b_lo * q_out; s.n_hi = b_hi * q_out; s.c_lo = c_lo; s.c_hi = c_hi;
         s.rows_per_item = (int64_t)q_out * out.h * out.w;
         s.gate = nullptr; s.c_split = 0; s.pool_avg = 0;
+        s.x_pitch = in.pitch ? in.pitch : in.c; s.y_pitch = out.pitch ? out.pitch : out.c;
         switch (op.kind) {
         case GACER_DWCONV2D: l.kind = LK_DWCONV; break;
         case GACER_MAXPOOL: l.kind = LK_MAXPOOL; break;
@@ -269,21 +271,57 @@ gacer_plan *make_plan(const std::vector<gacer_split> &splits, const std::vector<
 // ------------------------------------------------------------------------------------------------
 static bool same_shape(const gacer_tensor &a, const gacer_tensor &b) { return a.n == b.n && a.c == b.c && a.h == b.h && a.w == b.w; }
 
-static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, const std::vector<char> &written)
+// Which channels of which allocation hold data: a strided tensor is a channel window of its base tensor, every other
+// tensor owns its channels.  A tensor is readable when all of its channels are written, writable when none is.
+struct Written {
+    const gacer_tenant &t;
+    std::vector<std::vector<char>> ch;
+    explicit Written(const gacer_tenant &tt) : t(tt), ch(tt.n_tensors)
+    {
+        for (int i = 0; i < t.n_tensors; ++i)
+            if (!t.tensors[i].pitch) ch[i].assign((size_t)t.tensors[i].c, 0);
+    }
+    int owner(int i) const { return t.tensors[i].pitch ? t.tensors[i].base : i; }
+    int first(int i) const { return t.tensors[i].pitch ? t.tensors[i].c_off : 0; }
+    int count(int i) const
+    {
+        const std::vector<char> &v = ch[owner(i)];
+        int k = 0;
+        for (int64_t q = 0; q < t.tensors[i].c; ++q) k += v[first(i) + q];
+        return k;
+    }
+    bool all(int i) const { return count(i) == t.tensors[i].c; }
+    bool none(int i) const { return count(i) == 0; }
+    void mark(int i)
+    {
+        std::vector<char> &v = ch[owner(i)];
+        for (int64_t q = 0; q < t.tensors[i].c; ++q) v[first(i) + q] = 1;
+    }
+};
+
+static gacer_status check_op(Ctx *c, int ti, const gacer_tenant &t, int oi, const Written &written)
 {
     const gacer_op &op = t.ops[oi];
     auto bad = [&](const char *why) { return fail(c, GACER_ESHAPE, "tenant %d op %d: %s", ti, oi, why); };
     auto idx_ok = [&](int i, bool required) {
         if (i < 0) return !required;
-        return i < t.n_tensors && written[i] != 0;
+        return i < t.n_tensors && written.all(i);
     };
     if ((int)op.kind < 0 || (int)op.kind > (int)GACER_AVGPOOL) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown kind", ti, oi);
     if ((int)op.act < 0 || (int)op.act > (int)GACER_ACT_HSIGMOID) return fail(c, GACER_EINVAL, "tenant %d op %d: unknown activation", ti, oi);
     if (!idx_ok(op.in0, true)) return bad("in0 missing or not written by an earlier operator");
     if (!idx_ok(op.in1, false) || !idx_ok(op.res, false)) return bad("in1/res not written by an earlier operator");
     if (op.out < 0 || op.out >= t.n_tensors) return bad("out index out of range");
-    if (written[op.out]) return bad("out tensor is written twice");
+    if (!written.none(op.out)) return bad("out tensor is written twice");
     const gacer_tensor &in = t.tensors[op.in0], &out = t.tensors[op.out];
+    {   // channel windows: only where the kernels take a position pitch
+        const bool per_position = op.kind == GACER_CONV2D || (op.kind == GACER_GEMM && op.cin == in.c && in.h * in.w > 1);
+        const bool in_ok = per_position || op.kind == GACER_AFFINE_ACT || op.kind == GACER_ACT;
+        const bool out_ok = in_ok || op.kind == GACER_MAXPOOL || op.kind == GACER_AVGPOOL;
+        if (in.pitch && !in_ok) return bad("in0 is a channel window, which this operator kind does not read");
+        if (out.pitch && (!out_ok || op.res >= 0)) return bad("out is a channel window, which this operator kind (or an operator with a residual) does not write");
+        if ((op.in1 >= 0 && t.tensors[op.in1].pitch) || (op.res >= 0 && t.tensors[op.res].pitch)) return bad("in1 / res must not be channel windows");
+    }
     if (op.res >= 0 && !same_shape(t.tensors[op.res], out)) return bad("res shape differs from out");
     const int B = t.batch;
     switch (op.kind) {
@@ -463,7 +501,10 @@ static void fuse_into(Launch &pw, const Tenant &T, int i)
 {
     const gacer_op &af = T.ops[i];
     GemmArgs &g = pw.g;
-    g.x = T.tensors[af.in0].dptr;               // same shape as the tensor the product read before: strides and bounds stay
+    const gacer_tensor &in = T.tensors[af.in0];  // same shape as the tensor the product read before, possibly a channel window
+    const int64_t pitch = in.pitch ? in.pitch : in.c;
+    g.x = in.dptr; g.x_pix = pitch; g.x_img = in.h * in.w * pitch;
+    g.x_bytes = (in.n * in.h * in.w * pitch - (in.pitch ? in.c_off : 0)) * (int64_t)(T.dtype == GACER_BF16 ? 2 : 4);
     g.pre_scale = af.scale; g.pre_shift = af.shift; g.pre_y = T.tensors[af.out].dptr; g.pre_act = (int)af.act;
 }
 
@@ -691,21 +732,30 @@ gacer_status gacer_load_tenants(gacer_ctx *c, const gacer_tenant *tenants, int n
             const gacer_tensor &x = t.tensors[i];
             if (x.n < 1 || x.c < 1 || x.h < 1 || x.w < 1) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: non-positive extent", ti, i);
             if (!x.dptr) return fail(c, GACER_EINVAL, "tenant %d tensor %d: null device pointer", ti, i);
-            if (((uintptr_t)x.dptr) % 16) return fail(c, GACER_EINVAL, "tenant %d tensor %d: device pointer not 16-byte aligned", ti, i);
+            if (!x.pitch && ((uintptr_t)x.dptr) % 16) return fail(c, GACER_EINVAL, "tenant %d tensor %d: device pointer not 16-byte aligned", ti, i);
             if (x.n * x.c * x.h * x.w * (t.dtype == GACER_BF16 ? 2 : 4) >= ((int64_t)1 << 31))
                 return fail(c, GACER_ESHAPE, "tenant %d tensor %d: 2 GiB or more", ti, i);
+            if (x.pitch) {                      // a channel window of a wider, gap-free tensor
+                if (x.base < 0 || x.base >= t.n_tensors || x.base == i) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: base index out of range", ti, i);
+                const gacer_tensor &b = t.tensors[x.base];
+                if (b.pitch || b.c != x.pitch || b.n != x.n || b.h != x.h || b.w != x.w)
+                    return fail(c, GACER_ESHAPE, "tenant %d tensor %d: base must be a gap-free tensor (n, pitch, h, w)", ti, i);
+                if (x.c_off < 0 || x.c_off + x.c > x.pitch) return fail(c, GACER_ESHAPE, "tenant %d tensor %d: window leaves its base", ti, i);
+                if ((const char *)x.dptr != (const char *)b.dptr + (size_t)x.c_off * (t.dtype == GACER_BF16 ? 2 : 4))
+                    return fail(c, GACER_EINVAL, "tenant %d tensor %d: pointer is not base + c_off", ti, i);
+            }
         }
-        std::vector<char> written(t.n_tensors, 0);
-        written[t.input] = 1;
+        Written written(t);
+        written.mark(t.input);
         for (int oi = 0; oi < t.n_ops; ++oi) {
             gacer_status st = check_op(c, ti, t, oi, written);
             if (st != GACER_OK) return st;
             const gacer_op &op = t.ops[oi];
             for (const void *p : {(const void *)op.w, (const void *)op.bias, (const void *)op.scale, (const void *)op.shift})
                 if (((uintptr_t)p) % 16) return fail(c, GACER_EINVAL, "tenant %d op %d: parameter pointer not 16-byte aligned", ti, oi);
-            written[op.out] = 1;
+            written.mark(op.out);
         }
-        if (!written[t.output]) return fail(c, GACER_ESHAPE, "tenant %d: output tensor is never written", ti);
+        if (!written.all(t.output)) return fail(c, GACER_ESHAPE, "tenant %d: output tensor is never written", ti);
         Tenant &T = fresh[ti];
         T.ops.assign(t.ops, t.ops + t.n_ops);
         T.tensors.assign(t.tensors, t.tensors + t.n_tensors);

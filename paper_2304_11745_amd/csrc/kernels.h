@@ -78,6 +78,7 @@ struct StreamArgs {
     const void *gate;          // eltwise: per-(image, channel) factor [N][C] in the tensor dtype, or null
     int c_split;               // concat: channels of x (the first input); the rest of C come from x2
     int pool_avg;              // pooling: 0 = window maximum, 1 = unpadded window mean
+    int64_t x_pitch, y_pitch;  // eltwise (x, y) and pooling (y): elements between neighbouring positions (C unless the tensor is a channel window)
     // set by the launcher (see GemmArgs): divisors for the channel vectors per position, the positions (or position
     // tiles) per output row, and the output rows per image of this launch
     unsigned div_cv[2], div_w[2], div_h[2];

@@ -279,7 +279,7 @@ __global__ __launch_bounds__(TPB) void maxpool_kernel(StreamArgs a)
     Vec<T, V> yv;
 #pragma unroll
     for (int q = 0; q < V; ++q) yv.set(q, a.pool_avg ? __fdiv_rn(m[q], (float)(a.k * a.k)) : m[q]);
-    st_vec<T, V>((T *)a.y, (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.C + c, yv);
+    st_vec<T, V>((T *)a.y, (((int64_t)n * a.Ho + oh) * a.Wo + ow) * a.y_pitch + c, yv);
 }
 
 // ---- global average pooling ------------------------------------------------------------------------
@@ -329,8 +329,8 @@ __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
     const int p0 = div_by((int)idx, a.div_cv), cv = (int)idx - p0 * CV;       // idx < 2^31: a tensor holds fewer elements
     const int64_t pos = (int64_t)a.n_lo * P + p0;
     const int c = a.c_lo + cv * V;
-    const int64_t o = pos * a.C + c;
-    const Vec<T, V> xv = ld_vec<T, V>((const T *)a.x, o);
+    const int64_t o = pos * a.C + c;            // x2, res and the gate are gap-free; x and y may be channel windows
+    const Vec<T, V> xv = ld_vec<T, V>((const T *)a.x, pos * a.x_pitch + c);
     Vec<T, V> bv, rv, gv, yv;
     if (a.x2) bv = ld_vec<T, V>((const T *)a.x2, o);
     if (a.res) rv = ld_vec<T, V>((const T *)a.res, o);
@@ -351,7 +351,7 @@ __global__ __launch_bounds__(TPB) void eltwise_kernel(StreamArgs a)
     activate_n<V>(out, a.act);
 #pragma unroll
     for (int q = 0; q < V; ++q) yv.set(q, out[q]);
-    st_vec<T, V>((T *)a.y, o, yv);
+    st_vec<T, V>((T *)a.y, pos * a.y_pitch + c, yv);
 }
 
 // ---- channel concatenation: y[pos][c] = c < c_split ? x[pos][c] : x2[pos][c - c_split] ----------------------
@@ -544,7 +544,7 @@ static bool aligned16(const void *p) { return ((uintptr_t)p % 16) == 0; }
 template <typename T, int VFULL>
 static bool vec_ok(const StreamArgs &a)
 {
-    return a.C % VFULL == 0 && a.c_lo % VFULL == 0 && (a.c_hi - a.c_lo) % VFULL == 0 && aligned16(a.x) && aligned16(a.y) &&
+    return a.C % VFULL == 0 && a.x_pitch % VFULL == 0 && a.y_pitch % VFULL == 0 && a.c_lo % VFULL == 0 && (a.c_hi - a.c_lo) % VFULL == 0 && aligned16(a.x) && aligned16(a.y) &&
            aligned16(a.x2) && aligned16(a.res) && aligned16(a.w) && aligned16(a.gate);
 }
 

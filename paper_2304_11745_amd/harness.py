@@ -44,12 +44,17 @@ class Session:
         descs = (B.gacer_tenant * len(tenants))()
         for ti, (t, (x, params)) in enumerate(zip(tenants, data)):
             tdt = torch.bfloat16 if t.dtype == "bf16" else torch.float32
-            acts = [torch.zeros((n, h, w, c), dtype=tdt, device=self.dev) for (n, c, h, w) in t.tensors]
+            views = getattr(t, "views", {})
+            acts = [None if i in views else torch.zeros((n, h, w, c), dtype=tdt, device=self.dev)
+                    for i, (n, c, h, w) in enumerate(t.tensors)]
+            for i, (base, off) in views.items():             # a channel window shares the wider tensor's storage
+                acts[i] = acts[base][..., off:off + t.tensors[i][1]]
             acts[t.input].copy_(torch.from_numpy(np.ascontiguousarray(x.transpose(0, 2, 3, 1))).to(tdt))
             self.acts.append(acts)
             tens = (B.gacer_tensor * len(acts))()
             for i, ((n, c, h, w), a) in enumerate(zip(t.tensors, acts)):
-                tens[i] = B.gacer_tensor(n, c, h, w, a.data_ptr())
+                base, off = views.get(i, (0, 0))
+                tens[i] = B.gacer_tensor(n, c, h, w, a.data_ptr(), t.tensors[base][1] if i in views else 0, base, off)
             dev_params = {}
 
             def dparam(idx, kind=None, op=None):

@@ -25,7 +25,11 @@ def descriptors(tenants, mutate=None):
     keep = []
     descs = (B.gacer_tenant * len(tenants))()
     for ti, t in enumerate(tenants):
-        tens = (B.gacer_tensor * len(t.tensors))(*[B.gacer_tensor(n, c, h, w, FAKE) for (n, c, h, w) in t.tensors])
+        esz = 2 if t.dtype == "bf16" else 4
+        views = getattr(t, "views", {})
+        tens = (B.gacer_tensor * len(t.tensors))(*[
+            B.gacer_tensor(n, c, h, w, FAKE + views[i][1] * esz, t.tensors[views[i][0]][1], views[i][0], views[i][1]) if i in views
+            else B.gacer_tensor(n, c, h, w, FAKE) for i, (n, c, h, w) in enumerate(t.tensors)])
         ops = (B.gacer_op * len(t.ops))()
         for i, op in enumerate(t.ops):
             p = lambda idx: FAKE if idx >= 0 else None
@@ -123,7 +127,9 @@ def test_shape_validation(ctx):
 
 def test_shape_validation_of_gate_concat_and_mean_pool(ctx):
     """Squeeze-and-excitation gate, channel concatenation, unpadded mean pooling: each shape rule rejects its violation."""
-    for maker, kind in ((synth.small_mbv3, "scale"), (synth.small_densenet, "concat"), (synth.small_densenet, "avgpool")):
+    from synth import graphs as G
+    copying_densenet = lambda dtype, batch: G._densenet("copies", dtype, batch, 40, 8, [2, 3], 12, 2, 10, in_place=False)
+    for maker, kind in ((synth.small_mbv3, "scale"), (copying_densenet, "concat"), (synth.small_densenet, "avgpool")):
         tenants = [maker("f32", 2)]
         k = next(i for i, op in enumerate(tenants[0].ops) if op.kind == kind)
         st, _ = load(ctx, tenants)
@@ -146,6 +152,42 @@ def test_shape_validation_of_gate_concat_and_mean_pool(ctx):
         d[0].ops[0].act = 6
     st, _ = load(ctx, [synth.small_mbv3("f32", 2)], unknown_act)
     assert st == B.GACER_EINVAL
+
+
+def test_channel_window_validation(ctx):
+    """Tensors that are channel windows of a wider tensor: every rule of the declaration rejects its violation."""
+    t = synth.small_densenet("f32", 2)
+    assert t.views
+    st, _ = load(ctx, [t])
+    assert st == B.GACER_OK, B.gacer_last_error(ctx)
+    first_slot = next(i for i, (base, off) in sorted(t.views.items()) if off > 0)        # a layer's output window
+    prefix = next(i for i, (base, off) in sorted(t.views.items()) if off == 0 and i > first_slot)
+    base = t.views[first_slot][0]
+    reader = next(k for k, op in enumerate(t.ops) if op.in0 == prefix)
+    writer = next(k for k, op in enumerate(t.ops) if op.out == first_slot)
+
+    def leaves_base(d):
+        d[0].tensors[first_slot].c_off = t.tensors[base][1] - 1
+    def wrong_pointer(d):
+        d[0].tensors[first_slot].dptr = FAKE
+    def wrong_pitch(d):
+        d[0].tensors[first_slot].pitch += 4
+    def window_of_a_window(d):
+        d[0].tensors[first_slot].base = prefix
+    def overlapping(d):                               # the layer's window moved onto channels the pool has already written
+        d[0].tensors[first_slot].c_off = 0
+        d[0].tensors[first_slot].dptr = FAKE
+    def read_too_early(d):                            # the prefix reader moved in front of the layer that completes the prefix
+        d[0].ops[writer - 1].in0 = prefix
+    def unsupported_reader(d):                        # global pooling takes no position pitch
+        d[0].ops[reader].kind = B.GACER_GAVGPOOL
+    def residual_into_window(d):
+        d[0].ops[writer].res = d[0].ops[writer].in0
+    for bad, status in ((leaves_base, B.GACER_ESHAPE), (wrong_pointer, B.GACER_EINVAL), (wrong_pitch, B.GACER_ESHAPE),
+                        (window_of_a_window, B.GACER_ESHAPE), (overlapping, B.GACER_ESHAPE), (read_too_early, B.GACER_ESHAPE),
+                        (unsupported_reader, B.GACER_ESHAPE), (residual_into_window, B.GACER_ESHAPE)):
+        st, _ = load(ctx, [t], bad)
+        assert st == status, (bad.__name__, st, B.gacer_last_error(ctx))
 
 
 def _plan(splits=(), syncs=()):
