@@ -32,7 +32,7 @@ HBM_PEAK = 8.0e12
 TRAFFIC = {
     2: {"kernel": "igemm_dma_taps_f32_64x64x32s3", "fetch_bytes": 13.19e6, "write_bytes": 6.22e6, "plan": "unsplit",
         "launches_per_round": 16, "algorithmic_bytes": 10.62e6,
-        "sources_sha256": "ee2f21e25c10b8eba2fb652bf2dfb3a1686c32b4a6d43289bfff11a1ddf2b8df"},
+        "sources_sha256": "725166bda9138105229d7d1f25ee13b3b905c12dde4e4a3f2d15a37ff79c3ad3"},
 }
 TRAFFIC_SOURCES = ["igemm.hip", "stream_ops.hip", "device_util.h", "kernels.h"]
 
