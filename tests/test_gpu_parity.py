@@ -243,11 +243,13 @@ def test_stream_placement_over_hardware_queues(gpu):
     assert outs[0] == outs[1]
 
 
-def test_captured_round_replays_bit_exact(gpu):
+@pytest.mark.parametrize("config", [3, 8])
+def test_captured_round_replays_bit_exact(gpu, config):
     """A round captured into a HIP graph must reproduce the eager round bit for bit, on every replay, with
-    eager rounds and synchronisations in between, for all three modes and a decomposed, pointer-ordered plan."""
+    eager rounds and synchronisations in between, for all three modes and a decomposed, pointer-ordered plan
+    (config 8: with fused launches, channel-window tensors, gates and mean pools in the graph)."""
     from paper_2304_11745_amd import binding as B
-    tenants, data = synth.build_config(3, "small")
+    tenants, data = synth.build_config(config, "small")
     sess = gpu.Session(tenants, data)
     n_ops = [len(t.ops) for t in tenants]
     sess.set_plan(sess.uniform_splits("cout", 2, tenants=[0, 1]) + sess.uniform_splits("batch", 2, tenants=[2]),
@@ -272,10 +274,12 @@ def test_captured_round_replays_bit_exact(gpu):
     sess.close()
 
 
-def test_threaded_issue_bit_exact(gpu):
-    """One host thread per tenant (8 tenants, pointers + decomposition): same bits as the single-threaded run."""
+@pytest.mark.parametrize("config", [4, 8])
+def test_threaded_issue_bit_exact(gpu, config):
+    """One host thread per tenant (config 4: 8 tenants; config 8: fused launches and channel-window tensors), pointers +
+    decomposition: same bits as the single-threaded run."""
     from paper_2304_11745_amd import binding as B
-    tenants, data = synth.build_config(4, "small")
+    tenants, data = synth.build_config(config, "small")
     sess = gpu.Session(tenants, data)
     n_ops = [len(t.ops) for t in tenants]
     sess.poison_outputs()
