@@ -5,7 +5,8 @@ A step is one round: every tenant of the workload runs once (inputs, weights and
 resident in HBM).  Three executions of the same kernels are timed: sequential (one stream, unsplit),
 stream-parallel (one stream per tenant, unsplit, no ordering) and regulated (the chosen plan:
 operator chunks + pointer edges).  ``value`` is the regulated aggregate items/s of the headline
-workload (configs[1]); ``per_config`` carries the same measurements for configs[2..4].
+workload (configs[1]); ``per_config`` carries the same measurements for configs[2..4], ``paper_mixes`` for three tenant
+mixes of the paper's own evaluation (its Table 2) that need no dataset.
 
 Prints ONE JSON line.  Plan selection (profile, search, short trials) happens before the timed
 region, as in offline deployment (Section 4.4, "Search Cost Analysis").
@@ -321,7 +322,7 @@ def run_config(config, args, cpu_budget_s):
         "roofline": roof,
     }
     sess.close()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and cpu_budget_s > 0:
         out["cpu_baseline"] = cpu_baseline(tenants, data, cpu_budget_s, floor_s=min(10.0, 0.4 * cpu_budget_s))
     return out
 
@@ -406,6 +407,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="headline workload: 1..5 = the configurations, 6.. = tenant mixes of the paper's evaluation (default 2)")
     ap.add_argument("--also", default="3,4,5", help="further workloads reported under per_config (comma separated; '' for none)")
+    ap.add_argument("--mixes", default=None, help="tenant mixes of the paper's evaluation reported under paper_mixes, without a CPU "
+                                                  "baseline (comma separated; '' for none; default: 6,7,8 in the plain default run only)")
     ap.add_argument("--scale", default="full", choices=["full", "small"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--plan", default="auto", help="auto | unsplit")
@@ -472,6 +475,15 @@ def main():
             r = run_config(c, args, 12.0)
             r.pop("plan_selection", None)                  # kept on stderr; the line stays readable
             out["per_config"][str(c)] = r
+    if args.mixes is None:                                 # any narrowing flag means: exactly what was asked for
+        args.mixes = "6,7,8" if (args.config == 2 and args.also == "3,4,5" and not args.only_regulated and args.scale == "full") else ""
+    mixes = [int(c) for c in args.mixes.split(",") if c.strip() and int(c) != args.config and int(c) not in also]
+    if mixes:
+        out["paper_mixes"] = {}
+        for c in mixes:
+            r = run_config(c, args, 0.0)
+            r.pop("plan_selection", None)
+            out["paper_mixes"][str(c)] = r
     print(json.dumps(out), flush=True)
 
 
