@@ -142,8 +142,8 @@ def calibrated_table(sess, B, rows, measured_unsplit_ms):
 
 
 def choose_plan(sess, B, trial_rounds):
-    """Candidates: the searched plan (Algorithm 1 + spatial regulation on the profiled table), plain stream-parallel, and
-    uniform sweeps; each is measured for a few rounds next to what the model predicts for it; the fastest is refined
+    """Candidates: the searched plan (Algorithm 1 + spatial regulation on the profiled table), its decompositions alone and its
+    pointers alone, plain stream-parallel, and uniform sweeps; each is measured for a few rounds next to what the model predicts for it; the fastest is refined
     (gacer_refine) and installed.  Because the unsplit plan is a candidate, the regulated run is never slower than
     stream-parallel by more than measurement noise."""
     t0 = time.perf_counter()
@@ -154,6 +154,10 @@ def choose_plan(sess, B, trial_rounds):
     t_search = time.perf_counter() - t0
     none_P = [[] for _ in sess.tenants]
     cands = {"searched": (splits, syncs, P), "unsplit": ([], [], none_P)}
+    # the two halves of the searched plan on their own (the Spatial / Temporal / GACER decomposition of Section 5.2, Fig. 7)
+    if splits and syncs:
+        cands["searched-spatial-only"] = (splits, [], none_P)
+        cands["searched-temporal-only"] = ([], syncs, P)
     for axis in ("batch", "cout"):
         for f in (2, 4):
             sp = sess.uniform_splits(axis, f)
