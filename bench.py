@@ -242,7 +242,9 @@ def dominant_roofline(trace, dtype, config):
     d = per_kernel[dom]
     avg_ms = d["ms"] / d["launches"]
     traffic, profiled = measured_traffic(config, dom, d["launches"])
-    if d["flops"] > 0:
+    # which roof bounds the kernel: the one its algorithmic work would take longer under (a contraction whose arithmetic
+    # intensity lies below the ridge of its dtype is a bandwidth-bound kernel, e.g. bf16 pointwise products with short K)
+    if d["flops"] / PEAK[dtype] >= d["bytes"] / HBM_PEAK and d["flops"] > 0:
         achieved = d["flops"] / d["launches"] / (avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
                 "frac": achieved / (PEAK[dtype] / 1e12), "traffic": traffic}
